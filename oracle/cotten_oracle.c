@@ -1,0 +1,194 @@
+/*
+ * fp64 CPU oracle for bidirectional cosine-similarity attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * GPU library must compute.  It shares no code with the HIP path and nothing in
+ * the product path may call it; only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg do.
+ *
+ * What it follows (Cotten4Rec, section "Model Description"):
+ *   - the CosineAttention definition, Sim(Q,K) V with Sim the product of the
+ *     row-normalised Q and the transposed row-normalised K       (quadratic form);
+ *   - the scaled variant, the same expression times the scalar 1/n^m, here a
+ *     scalar `scale` handed in by the caller;
+ *   - the reordered variant, Q_hat (K_hat^T V), a d x d state built first
+ *     (linear form);
+ *   - section "Cosine Similarity and CUDA Kernel": a row x is normalised as
+ *     x / sqrt(sum_c x_c^2 + eps), eps INSIDE the square root.
+ * Readings where the paper is silent: only Q and K are normalised (V never is);
+ * the key-padding mask m_j in {0,1} removes key/value row j from the sum and
+ * masks nothing on the query side; the backward is the chain rule applied to
+ * the expressions above (the paper prints none).
+ *
+ * Pins (tests/test_oracle_pins.py): linear == quadratic on small inputs;
+ * closed forms; unit norms; masked-key invariance; permutation equivariance;
+ * fp64 autograd of the library expression; central finite differences and an
+ * independently derived n x n route for the backward.
+ *
+ * Layout: Q,K,V,O,dO,dQ,dK,dV are [B,H,N,d] row-major doubles; mask is [B,N]
+ * bytes (1 = valid key) or NULL for "all valid".  Slices (b,h) are independent
+ * and are spread over OpenMP threads; inside a slice every loop is sequential.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int cotten_oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* r(x) = sqrt(sum_c x_c^2 + eps) */
+static double row_norm(const double* x, int d, double eps) {
+  double ss = 0.0;
+  for (int c = 0; c < d; ++c) ss += x[c] * x[c];
+  return sqrt(ss + eps);
+}
+
+static int key_valid(const uint8_t* mask, int b, int N, int j) {
+  return mask == NULL ? 1 : (mask[(size_t)b * N + j] != 0);
+}
+
+/* Definition: O_i = scale * sum_j m_j cos(q_i, k_j) v_j, forming every one of
+ * the N x N cosines explicitly. */
+void cotten_oracle_fwd_quadratic(const double* Q, const double* K, const double* V,
+                                 const uint8_t* mask, double* O, int B, int H, int N,
+                                 int d, double scale, double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const double *q = Q + off, *k = K + off, *v = V + off;
+    double* o = O + off;
+    double* rk = (double*)malloc(sizeof(double) * (size_t)N);
+    for (int j = 0; j < N; ++j) rk[j] = row_norm(k + (size_t)j * d, d, eps);
+    for (int i = 0; i < N; ++i) {
+      const double rq = row_norm(q + (size_t)i * d, d, eps);
+      for (int c = 0; c < d; ++c) o[(size_t)i * d + c] = 0.0;
+      for (int j = 0; j < N; ++j) {
+        if (!key_valid(mask, b, N, j)) continue;
+        double dot = 0.0;
+        for (int a = 0; a < d; ++a) dot += q[(size_t)i * d + a] * k[(size_t)j * d + a];
+        const double cosine = dot / (rq * rk[j]);
+        for (int c = 0; c < d; ++c) o[(size_t)i * d + c] += cosine * v[(size_t)j * d + c];
+      }
+      for (int c = 0; c < d; ++c) o[(size_t)i * d + c] *= scale;
+    }
+    free(rk);
+  }
+}
+
+/* S[a][c] = sum_j m_j khat_j[a] v_j[c]   (the d x d state of the reordered form) */
+static void build_state(const double* k, const double* v, const uint8_t* mask, int b,
+                        int N, int d, double eps, double* S) {
+  for (int a = 0; a < d * d; ++a) S[a] = 0.0;
+  for (int j = 0; j < N; ++j) {
+    if (!key_valid(mask, b, N, j)) continue;
+    const double rk = row_norm(k + (size_t)j * d, d, eps);
+    for (int a = 0; a < d; ++a) {
+      const double kh = k[(size_t)j * d + a] / rk;
+      for (int c = 0; c < d; ++c) S[(size_t)a * d + c] += kh * v[(size_t)j * d + c];
+    }
+  }
+}
+
+/* Reordered form: S = Khat^T V under the key mask, then O_i = scale * qhat_i S. */
+void cotten_oracle_fwd_linear(const double* Q, const double* K, const double* V,
+                              const uint8_t* mask, double* O, int B, int H, int N, int d,
+                              double scale, double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const double *q = Q + off, *k = K + off, *v = V + off;
+    double* o = O + off;
+    double* S = (double*)malloc(sizeof(double) * (size_t)d * d);
+    build_state(k, v, mask, b, N, d, eps, S);
+    for (int i = 0; i < N; ++i) {
+      const double rq = row_norm(q + (size_t)i * d, d, eps);
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int a = 0; a < d; ++a) acc += (q[(size_t)i * d + a] / rq) * S[(size_t)a * d + c];
+        o[(size_t)i * d + c] = scale * acc;
+      }
+    }
+    free(S);
+  }
+}
+
+/* Backward of the reordered form, chain rule step by step.  With
+ *   xhat = x / r(x),  r = sqrt(|x|^2 + eps)   =>   dx = (dxhat - xhat (xhat . dxhat)) / r
+ * (exact also for eps > 0, because d r / d x = x / r):
+ *   dS      = scale * sum_i qhat_i^T dO_i          (all N query rows)
+ *   dqhat_i = scale * dO_i S^T
+ *   dV_j    = m_j * khat_j dS
+ *   dkhat_j = m_j * v_j dS^T
+ * dK_j and dV_j are exactly zero at masked keys. */
+void cotten_oracle_bwd(const double* Q, const double* K, const double* V,
+                       const uint8_t* mask, const double* dO, double* dQ, double* dK,
+                       double* dV, int B, int H, int N, int d, double scale, double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const double *q = Q + off, *k = K + off, *v = V + off, *go = dO + off;
+    double *gq = dQ + off, *gk = dK + off, *gv = dV + off;
+    double* S = (double*)malloc(sizeof(double) * (size_t)d * d);
+    double* dS = (double*)malloc(sizeof(double) * (size_t)d * d);
+    double* xh = (double*)malloc(sizeof(double) * (size_t)d);
+    double* gh = (double*)malloc(sizeof(double) * (size_t)d);
+    build_state(k, v, mask, b, N, d, eps, S);
+
+    for (int a = 0; a < d * d; ++a) dS[a] = 0.0;
+    for (int i = 0; i < N; ++i) {
+      const double rq = row_norm(q + (size_t)i * d, d, eps);
+      for (int a = 0; a < d; ++a) {
+        const double qh = q[(size_t)i * d + a] / rq;
+        for (int c = 0; c < d; ++c) dS[(size_t)a * d + c] += scale * qh * go[(size_t)i * d + c];
+      }
+    }
+
+    for (int i = 0; i < N; ++i) {
+      const double rq = row_norm(q + (size_t)i * d, d, eps);
+      double proj = 0.0;
+      for (int a = 0; a < d; ++a) {
+        xh[a] = q[(size_t)i * d + a] / rq;
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += go[(size_t)i * d + c] * S[(size_t)a * d + c];
+        gh[a] = scale * acc;
+        proj += xh[a] * gh[a];
+      }
+      for (int a = 0; a < d; ++a) gq[(size_t)i * d + a] = (gh[a] - xh[a] * proj) / rq;
+    }
+
+    for (int j = 0; j < N; ++j) {
+      if (!key_valid(mask, b, N, j)) {
+        for (int a = 0; a < d; ++a) gk[(size_t)j * d + a] = gv[(size_t)j * d + a] = 0.0;
+        continue;
+      }
+      const double rk = row_norm(k + (size_t)j * d, d, eps);
+      for (int a = 0; a < d; ++a) xh[a] = k[(size_t)j * d + a] / rk;
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int a = 0; a < d; ++a) acc += xh[a] * dS[(size_t)a * d + c];
+        gv[(size_t)j * d + c] = acc;
+      }
+      double proj = 0.0;
+      for (int a = 0; a < d; ++a) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += v[(size_t)j * d + c] * dS[(size_t)a * d + c];
+        gh[a] = acc;
+        proj += xh[a] * gh[a];
+      }
+      for (int a = 0; a < d; ++a) gk[(size_t)j * d + a] = (gh[a] - xh[a] * proj) / rk;
+    }
+    free(S); free(dS); free(xh); free(gh);
+  }
+}
