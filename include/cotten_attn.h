@@ -1,0 +1,126 @@
+/*
+ * cotten_attn.h -- C ABI of the MI355X (gfx950) cosine-similarity attention library.
+ *
+ * The operation (Cotten4Rec, section "Model Description"): for every head-slice
+ * (b,h) with per-head matrices Q, K, V of N rows and d_h columns,
+ *
+ *     xhat   = x / sqrt(sum_c x_c^2 + eps)        row-wise, for rows of Q and of K
+ *                                                 (section "Cosine Similarity and
+ *                                                  CUDA Kernel": eps inside the root)
+ *     S      = sum_j m_j khat_j^T v_j             d_h x d_h state of the reordered
+ *                                                 CosineAttention  Qhat (Khat^T V)
+ *     O_i    = scale * qhat_i S                   scale = the scalar normaliser
+ *                                                 1/n^m of the scaled CosineAttention
+ *
+ * m_j in {0,1} is a key-padding mask (1 = valid key).  The mask acts on keys
+ * only: O and dQ are produced for all N query rows, and dO of every row flows
+ * into the gradients.  The backward entry point returns the exact gradients of
+ * the expression above,
+ *
+ *     dS   = scale * sum_i qhat_i^T dO_i
+ *     dQ_i = (g_i - qhat_i (qhat_i . g_i)) / r(q_i),   g_i = scale * dO_i S^T
+ *     dV_j = m_j * khat_j dS
+ *     dK_j = m_j * (h_j - khat_j (khat_j . h_j)) / r(k_j),   h_j = v_j dS^T
+ *
+ * with r(x) = sqrt(sum_c x_c^2 + eps); dK and dV rows of masked keys are written
+ * as exact zeros.  If a batch row has no valid key, O = 0 for it.
+ *
+ * Memory.  Every pointer is a DEVICE pointer owned by the caller.  Q, K, V, O,
+ * dO, dQ, dK, dV are [B, H, N, d_h] row-major and contiguous (each slice (b,h) is
+ * one contiguous N x d_h block), element type given by `dtype`; mask is [B, N]
+ * bytes shared by the H heads, or NULL for "every key valid".  Tensor base
+ * pointers must be 16-byte aligned.  Outputs must not overlap inputs or each
+ * other.  Masked K/V rows are never dereferenced into arithmetic: they may hold
+ * anything, NaN and Inf included.
+ *
+ * Arithmetic.  Row norms, the state and every accumulation are fp32 whatever
+ * the I/O type (the paper keeps norms and partial sums in float32 under 16-bit
+ * I/O).  Results are deterministic: reductions use a fixed order, no float
+ * atomics, so two calls on the same inputs give identical bits.
+ *
+ * Execution.  Calls only enqueue kernels on `stream` (a hipStream_t passed as
+ * void*; NULL = the default stream) and return; they never synchronise.  The
+ * library runs on the device that is current in the calling thread.
+ *
+ * Workspace.  Long sequences are split over several workgroups per slice; the
+ * partial d_h x d_h states travel through a workspace of
+ * cotten_attn_workspace_bytes(...) bytes (0 when a shape needs none).  The *_ex
+ * entry points take it from cotten_params; when params->workspace is NULL (and
+ * for the plain entry points) the library keeps one buffer per device that it
+ * allocates with hipMalloc on first need, grows when a larger shape arrives and
+ * never frees; calls that share it must be ordered on one stream.
+ *
+ * Errors.  Every entry point returns a cotten_status; 0 is success, negative
+ * values are listed below.  Argument validation happens on the host before any
+ * device work and never touches the GPU, so a failed call has enqueued nothing.
+ */
+#ifndef COTTEN_ATTN_H_
+#define COTTEN_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cotten_dtype {
+  COTTEN_F32 = 0,  /* float I/O                                   */
+  COTTEN_BF16 = 1  /* bfloat16 I/O, fp32 norms and accumulation   */
+} cotten_dtype;
+
+typedef enum cotten_status {
+  COTTEN_OK = 0,
+  COTTEN_ERR_NULL_POINTER = -1,         /* a required tensor pointer is NULL            */
+  COTTEN_ERR_BAD_SHAPE = -2,            /* B, H or N < 1, or sizes overflow the launch  */
+  COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64}                      */
+  COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is neither COTTEN_F32 nor COTTEN_BF16  */
+  COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
+  COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* params->workspace_bytes below the requirement */
+  COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf   */
+  COTTEN_ERR_LAUNCH = -8,               /* the HIP runtime refused a launch             */
+  COTTEN_ERR_ALLOC = -9                 /* the library-owned workspace could not grow   */
+} cotten_status;
+
+typedef struct cotten_params {
+  int dtype;              /* a cotten_dtype                                             */
+  float scale;            /* scalar normaliser s; <= 0 selects the default 1/N          */
+  float eps;              /* epsilon inside the square root; < 0 selects 1e-6; 0 allowed */
+  void* workspace;        /* device buffer, 16-byte aligned, or NULL = library-owned    */
+  size_t workspace_bytes; /* size of `workspace` (ignored when it is NULL)              */
+} cotten_params;
+
+/* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):
+ * O = scale * Qhat (Khat^T V) under the key mask.  fp32 I/O, scale = 1/N, eps = 1e-6. */
+int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                    void* O, int B, int H, int N, int d_h, void* stream);
+
+/* Backward of the same expression: given dO writes dQ, dK, dV (formulas above).
+ * fp32 I/O, scale = 1/N, eps = 1e-6.  The state S is rebuilt from K, V; nothing
+ * saved by the forward call is needed. */
+int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                    const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
+                    int d_h, void* stream);
+
+/* Same operations with explicit dtype, scale, eps and workspace.  `params` must not
+ * be NULL. */
+int cotten_attn_fwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                       void* O, int B, int H, int N, int d_h, void* stream,
+                       const cotten_params* params);
+int cotten_attn_bwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                       const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
+                       int d_h, void* stream, const cotten_params* params);
+
+/* Bytes of workspace the given call would use (pure host arithmetic; 0 for an
+ * unsupported shape).  Grows like B*H*d_h^2 times the number of sequence splits,
+ * never like N*d_h or N^2: the method keeps only the d_h x d_h state ("Memory and
+ * Compute Complexity"). */
+size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd);
+
+/* Static, NUL-terminated description of a status code. */
+const char* cotten_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COTTEN_ATTN_H_ */

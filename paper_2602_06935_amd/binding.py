@@ -1,0 +1,174 @@
+"""Thin ctypes binding of libcotten_attn.so (same names as include/cotten_attn.h).
+
+Argument marshalling only: every arithmetic step runs in the HIP kernels.  torch is
+used for device memory (`torch.empty`, `.data_ptr()`) and for the current stream.
+There is no CPU fallback: if the library cannot be loaded, or a tensor is not on
+the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcotten_attn.so")
+
+COTTEN_F32 = 0
+COTTEN_BF16 = 1
+
+EXPORTS = (
+    "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
+    "cotten_attn_workspace_bytes", "cotten_status_string",
+)
+
+
+class CottenParams(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int), ("scale", ctypes.c_float), ("eps", ctypes.c_float),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class CottenError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"cotten_attn status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """dlopen the in-tree library; compile it first only when no build exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip = ctypes.c_void_p, ctypes.c_int
+    lib.cotten_attn_fwd.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
+    lib.cotten_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
+    lib.cotten_attn_fwd_ex.argtypes = lib.cotten_attn_fwd.argtypes + [ctypes.POINTER(CottenParams)]
+    lib.cotten_attn_bwd_ex.argtypes = lib.cotten_attn_bwd.argtypes + [ctypes.POINTER(CottenParams)]
+    for f in (lib.cotten_attn_fwd, lib.cotten_attn_bwd, lib.cotten_attn_fwd_ex, lib.cotten_attn_bwd_ex):
+        f.restype = ctypes.c_int
+    lib.cotten_attn_workspace_bytes.argtypes = [ip, ip, ip, ip, ip, ip]
+    lib.cotten_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.cotten_status_string.argtypes = [ip]
+    lib.cotten_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def cotten_status_string(status: int) -> str:
+    return load_library().cotten_status_string(int(status)).decode()
+
+
+def cotten_attn_workspace_bytes(B: int, H: int, N: int, d_h: int, dtype: int, is_bwd: bool) -> int:
+    return int(load_library().cotten_attn_workspace_bytes(B, H, N, d_h, dtype, int(bool(is_bwd))))
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise CottenError(status, cotten_status_string(status))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return COTTEN_F32
+    if t.dtype == torch.bfloat16:
+        return COTTEN_BF16
+    raise TypeError(f"unsupported I/O dtype {t.dtype}")
+
+
+def _prep(name: str, t: torch.Tensor, like: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous [B,H,N,d_h]")
+    if like is not None and (t.shape != like.shape or t.dtype != like.dtype or t.device != like.device):
+        raise ValueError(f"{name} must match Q in shape, dtype and device")
+    return t
+
+
+def _mask_ptr(mask: Optional[torch.Tensor], B: int, N: int, dev) -> Optional[int]:
+    if mask is None:
+        return None
+    if mask.dtype != torch.uint8 or tuple(mask.shape) != (B, N) or not mask.is_contiguous() or mask.device != dev:
+        raise ValueError("mask must be a contiguous uint8 [B,N] tensor on the same device")
+    return mask.data_ptr()
+
+
+def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor]) -> CottenParams:
+    p = CottenParams()
+    p.dtype = _dtype_code(Q)
+    p.scale = 0.0 if scale is None else float(scale)
+    p.eps = -1.0 if eps is None else float(eps)
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous GPU tensor")
+        p.workspace = workspace.data_ptr()
+        p.workspace_bytes = workspace.numel() * workspace.element_size()
+    else:
+        p.workspace = None
+        p.workspace_bytes = 0
+    return p
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                    mask: Optional[torch.Tensor], O: Optional[torch.Tensor] = None, *,
+                    scale: Optional[float] = None, eps: Optional[float] = None,
+                    stream=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O."""
+    lib = load_library()
+    Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q)
+    if Q.dim() != 4:
+        raise ValueError("expected [B,H,N,d_h]")
+    B, H, N, d = Q.shape
+    if O is None:
+        O = torch.empty_like(Q)
+    _prep("O", O, Q)
+    prm = _params(Q, scale, eps, workspace)
+    with torch.cuda.device(Q.device):
+        _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                      _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
+                                      B, H, N, d, _stream_handle(stream), ctypes.byref(prm)))
+    return O
+
+
+def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                    mask: Optional[torch.Tensor], dO: torch.Tensor,
+                    dQ: Optional[torch.Tensor] = None, dK: Optional[torch.Tensor] = None,
+                    dV: Optional[torch.Tensor] = None, *, scale: Optional[float] = None,
+                    eps: Optional[float] = None, stream=None,
+                    workspace: Optional[torch.Tensor] = None
+                    ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors."""
+    lib = load_library()
+    Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q); dO = _prep("dO", dO, Q)
+    if Q.dim() != 4:
+        raise ValueError("expected [B,H,N,d_h]")
+    B, H, N, d = Q.shape
+    dQ = torch.empty_like(Q) if dQ is None else _prep("dQ", dQ, Q)
+    dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
+    dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
+    prm = _params(Q, scale, eps, workspace)
+    with torch.cuda.device(Q.device):
+        _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                      _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),
+                                      dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                      B, H, N, d, _stream_handle(stream), ctypes.byref(prm)))
+    return dQ, dK, dV

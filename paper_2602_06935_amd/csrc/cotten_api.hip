@@ -1,0 +1,152 @@
+// C-ABI entry points: host-side validation, defaults, workspace, dispatch.
+// See include/cotten_attn.h for the contract of every function.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <mutex>
+
+#include "../../include/cotten_attn.h"
+#include "cotten_launch.h"
+
+namespace {
+
+constexpr float kDefaultEps = 1e-6f;
+constexpr int kMaxDevices = 64;
+
+bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape checks shared by both directions.  Pure host arithmetic.
+int check_shape(int B, int H, int N, int d_h, int dtype) {
+  if (dtype != COTTEN_F32 && dtype != COTTEN_BF16) return COTTEN_ERR_BAD_DTYPE;
+  if (B < 1 || H < 1 || N < 1) return COTTEN_ERR_BAD_SHAPE;
+  if (!head_dim_ok(d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
+  const long long slices = static_cast<long long>(B) * H;
+  if (slices > (1ll << 24)) return COTTEN_ERR_BAD_SHAPE;         // grid.x = slices * splits
+  if (N > (1 << 24)) return COTTEN_ERR_BAD_SHAPE;
+  return COTTEN_OK;
+}
+
+// Library-owned workspace: one buffer per device, grown on demand, never freed.
+struct DeviceWorkspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+DeviceWorkspace g_ws[kMaxDevices];
+std::mutex g_ws_mutex;
+
+int own_workspace(size_t need, float** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return COTTEN_ERR_ALLOC;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  DeviceWorkspace& w = g_ws[dev];
+  if (w.bytes < need) {
+    // Work already enqueued may still read the old buffer: drain before replacing it.
+    if (w.ptr != nullptr) {
+      if (hipDeviceSynchronize() != hipSuccess) return COTTEN_ERR_ALLOC;
+      (void)hipFree(w.ptr);
+      w.ptr = nullptr;
+      w.bytes = 0;
+    }
+    size_t cap = need < (size_t{1} << 20) ? (size_t{1} << 20) : need;
+    void* p = nullptr;
+    if (hipMalloc(&p, cap) != hipSuccess) {
+      (void)hipGetLastError();
+      return COTTEN_ERR_ALLOC;
+    }
+    w.ptr = p;
+    w.bytes = cap;
+  }
+  *out = static_cast<float*>(w.ptr);
+  return COTTEN_OK;
+}
+
+int resolve(const cotten_params* prm, int N, float* scale, float* eps) {
+  *scale = prm->scale > 0.0f ? prm->scale : 1.0f / static_cast<float>(N);
+  *eps = prm->eps < 0.0f ? kDefaultEps : prm->eps;
+  if (!std::isfinite(prm->scale) || !std::isfinite(prm->eps)) return COTTEN_ERR_BAD_PARAM;
+  return COTTEN_OK;
+}
+
+int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* mask,
+        const void* dO, void* O, void* dQ, void* dK, void* dV, int B, int H, int N, int d_h,
+        void* stream, const cotten_params* prm) {
+  if (prm == nullptr) return COTTEN_ERR_NULL_POINTER;
+  if (Q == nullptr || K == nullptr || V == nullptr) return COTTEN_ERR_NULL_POINTER;
+  if (bwd ? (dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr) : (O == nullptr))
+    return COTTEN_ERR_NULL_POINTER;
+  if (int rc = check_shape(B, H, N, d_h, prm->dtype)) return rc;
+  const void* tensors[8] = {Q, K, V, bwd ? dO : O, dQ, dK, dV, prm->workspace};
+  for (const void* t : tensors)
+    if (t != nullptr && !aligned16(t)) return COTTEN_ERR_MISALIGNED;
+
+  cotten::Problem p{};
+  if (int rc = resolve(prm, N, &p.scale, &p.eps)) return rc;
+  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, bwd);
+  const size_t need = plan.workspace_floats * sizeof(float);
+  if (prm->workspace != nullptr) {
+    if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
+    p.workspace = static_cast<float*>(prm->workspace);
+  } else if (need > 0) {
+    if (int rc = own_workspace(need, &p.workspace)) return rc;
+  }
+  p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
+  p.O = O; p.dQ = dQ; p.dK = dK; p.dV = dV;
+  p.B = B; p.H = H; p.N = N; p.D = d_h;
+  p.dtype = prm->dtype;
+  p.stream = static_cast<hipStream_t>(stream);
+  const hipError_t err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
+  return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
+}
+
+const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0};
+
+}  // namespace
+
+extern "C" {
+
+int cotten_attn_fwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask, void* O,
+                       int B, int H, int N, int d_h, void* stream, const cotten_params* params) {
+  return run(false, Q, K, V, mask, nullptr, O, nullptr, nullptr, nullptr, B, H, N, d_h, stream,
+             params);
+}
+
+int cotten_attn_bwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                       const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N, int d_h,
+                       void* stream, const cotten_params* params) {
+  return run(true, Q, K, V, mask, dO, nullptr, dQ, dK, dV, B, H, N, d_h, stream, params);
+}
+
+int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* mask, void* O,
+                    int B, int H, int N, int d_h, void* stream) {
+  return cotten_attn_fwd_ex(Q, K, V, mask, O, B, H, N, d_h, stream, &kDefaults);
+}
+
+int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                    const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N, int d_h,
+                    void* stream) {
+  return cotten_attn_bwd_ex(Q, K, V, mask, dO, dQ, dK, dV, B, H, N, d_h, stream, &kDefaults);
+}
+
+size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd) {
+  if (check_shape(B, H, N, d_h, dtype) != COTTEN_OK) return 0;
+  return cotten::make_plan(B, H, N, d_h, is_bwd != 0).workspace_floats * sizeof(float);
+}
+
+const char* cotten_status_string(int status) {
+  switch (status) {
+    case COTTEN_OK: return "ok";
+    case COTTEN_ERR_NULL_POINTER: return "a required pointer is NULL";
+    case COTTEN_ERR_BAD_SHAPE: return "B, H and N must be >= 1 and within launch limits";
+    case COTTEN_ERR_UNSUPPORTED_HEAD_DIM: return "d_h must be 16, 32 or 64";
+    case COTTEN_ERR_BAD_DTYPE: return "dtype must be COTTEN_F32 or COTTEN_BF16";
+    case COTTEN_ERR_MISALIGNED: return "tensor and workspace pointers must be 16-byte aligned";
+    case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";
+    case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite";
+    case COTTEN_ERR_LAUNCH: return "HIP kernel launch failed";
+    case COTTEN_ERR_ALLOC: return "could not allocate the library-owned workspace";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

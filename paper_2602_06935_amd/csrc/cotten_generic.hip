@@ -1,0 +1,384 @@
+// Generic two-kernel path of the cosine attention: vector-ALU arithmetic, tiles
+// staged through LDS.  Works for every supported (dtype, d_h, N); the tuned
+// kernels take over the shapes they cover.
+//
+//   state kernel : one workgroup reduces a block of rows of one slice to a
+//                  partial d x d state  sum_j xhat_j^T y_j   (x,y) = (K,V) under
+//                  the key mask, and for the backward also (Q,dO) unmasked.
+//   apply kernels: sum the partial states of the slice in a fixed order, then
+//                  stream row tiles:  O = s Qhat S   /   dQ, dK, dV.
+//
+// Thread mapping inside a 32-row tile: 8 consecutive lanes own one row, each
+// lane owns D/8 consecutive columns of it (one 128-bit access for fp32/d_h=32
+// and bf16/d_h=64), so a row norm is an in-lane sum plus three lane exchanges.
+#include "cotten_device.h"
+#include "cotten_launch.h"
+
+namespace cotten {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileRows = kThreads / 8;  // 32
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void state_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const T* __restrict__ dO, const uint8_t* __restrict__ mask, float* __restrict__ ws,
+    int H, int N, int splits, int rows_per_split, size_t second_offset, float eps) {
+  constexpr int CH = D / 8;   // columns per lane when loading
+  constexpr int R = D / 16;   // each thread accumulates an R x R block of the state
+  __shared__ float xs[kTileRows][D];
+  __shared__ float ys[kTileRows][D];
+
+  const int tid = threadIdx.x;
+  const int split = blockIdx.x % splits;
+  const int bh = blockIdx.x / splits;
+  const bool second = blockIdx.y == 1;  // (Q,dO) -> dS instead of (K,V) -> S
+  const size_t base = static_cast<size_t>(bh) * N * D;
+  const T* __restrict__ X = (second ? Q : K) + base;
+  const T* __restrict__ Y = (second ? dO : V) + base;
+  const uint8_t* __restrict__ m =
+      (second || mask == nullptr) ? nullptr : mask + static_cast<size_t>(bh / H) * N;
+
+  const int r_begin = split * rows_per_split;
+  const int r_end = min(N, r_begin + rows_per_split);
+  const int lrow = tid >> 3, chunk = tid & 7;
+  const int ty = tid >> 4, tx = tid & 15;
+
+  float acc[R][R];
+#pragma unroll
+  for (int i = 0; i < R; ++i)
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[i][j] = 0.0f;
+
+  for (int r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+    const int row = r0 + lrow;
+    bool live = row < r_end;
+    if (live && m != nullptr) live = m[row] != 0;
+    float x[CH], y[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) x[i] = y[i] = 0.0f;
+    if (live) {
+      load_chunk<T, CH>(X + static_cast<size_t>(row) * D + chunk * CH, x);
+      load_chunk<T, CH>(Y + static_cast<size_t>(row) * D + chunk * CH, y);
+    }
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) ss += x[i] * x[i];
+    ss = sum8(ss);
+    const float inv = inv_norm(ss, eps);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      xs[lrow][chunk * CH + i] = live ? x[i] * inv : 0.0f;
+      ys[lrow][chunk * CH + i] = y[i];
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int r = 0; r < kTileRows; ++r) {
+      float a[R], c[R];
+#pragma unroll
+      for (int i = 0; i < R; ++i) a[i] = xs[r][ty * R + i];
+#pragma unroll
+      for (int j = 0; j < R; ++j) c[j] = ys[r][tx * R + j];
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int j = 0; j < R; ++j) acc[i][j] += a[i] * c[j];
+    }
+    __syncthreads();
+  }
+
+  float* __restrict__ out =
+      ws + (second ? second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
+#pragma unroll
+  for (int i = 0; i < R; ++i)
+#pragma unroll
+    for (int j = 0; j < R; ++j) out[(ty * R + i) * D + tx * R + j] = acc[i][j];
+}
+
+// Sums the partial states of every slice in split order (fixed order => results do
+// not depend on scheduling).  One thread per state element; grid.y selects S or dS.
+__global__ __launch_bounds__(kThreads) void reduce_states_kernel(
+    const float* __restrict__ partial, float* __restrict__ reduced, int splits, int dd,
+    size_t total, size_t partial_second_offset) {
+  const size_t e = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (e >= total) return;
+  const size_t bh = e / dd, k = e % dd;
+  const float* __restrict__ src =
+      partial + (blockIdx.y ? partial_second_offset : 0) + bh * splits * dd + k;
+  float s = 0.0f;
+  for (int p = 0; p < splits; ++p) s += src[static_cast<size_t>(p) * dd];
+  reduced[(blockIdx.y ? total : 0) + e] = s;
+}
+
+// Copies the reduced state of one slice into LDS, times `scale`, either as is
+// (dst[a][c]) or transposed (dst[c][a]).
+template <int D, bool TRANSPOSE>
+__device__ __forceinline__ void load_state(const float* __restrict__ state, float scale,
+                                           float (*dst)[D]) {
+  for (int e = threadIdx.x; e < D * D; e += kThreads) {
+    const float s = state[e] * scale;
+    const int a = e / D, c = e % D;
+    if (TRANSPOSE) dst[c][a] = s; else dst[a][c] = s;
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
+    const T* __restrict__ Q, const float* __restrict__ states, T* __restrict__ O, int N,
+    int splits, int rows_per_split, float scale, float eps) {
+  constexpr int CH = D / 8;
+  __shared__ float S[D][D];
+  __shared__ float qs[kTileRows][D + 4];
+
+  const int tid = threadIdx.x;
+  const int split = blockIdx.x % splits;
+  const int bh = blockIdx.x / splits;
+  const size_t base = static_cast<size_t>(bh) * N * D;
+  const int r_begin = split * rows_per_split;
+  const int r_end = min(N, r_begin + rows_per_split);
+  const int lrow = tid >> 3, chunk = tid & 7;
+
+  load_state<D, false>(states + static_cast<size_t>(bh) * D * D, scale, S);
+  __syncthreads();
+
+  for (int r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+    const int row = r0 + lrow;
+    const bool live = row < r_end;
+    float q[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) q[i] = 0.0f;
+    if (live) load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * D + chunk * CH, q);
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) ss += q[i] * q[i];
+    const float inv = inv_norm(sum8(ss), eps);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) qs[lrow][chunk * CH + i] = q[i] * inv;
+    __syncthreads();
+    float o[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) o[i] = 0.0f;
+#pragma unroll 8
+    for (int a = 0; a < D; ++a) {
+      const float qa = qs[lrow][a];
+#pragma unroll
+      for (int i = 0; i < CH; ++i) o[i] += qa * S[a][chunk * CH + i];
+    }
+    if (live) store_chunk<T, CH>(O + base + static_cast<size_t>(row) * D + chunk * CH, o);
+    __syncthreads();
+  }
+}
+
+// blockIdx.y == 0: dQ from (Q, dO, S).   blockIdx.y == 1: dK, dV from (K, V, dS).
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const T* __restrict__ dO, const uint8_t* __restrict__ mask,
+    const float* __restrict__ states, const float* __restrict__ dstates, T* __restrict__ dQ,
+    T* __restrict__ dK, T* __restrict__ dV, int H, int N, int splits, int rows_per_split,
+    float scale, float eps) {
+  constexpr int CH = D / 8;
+  __shared__ float M0[D][D];              // S^T (dQ blocks)  or dS   (dK/dV blocks)
+  __shared__ float M1[D][D];              // unused           or dS^T
+  __shared__ float t0[kTileRows][D + 4];  // dO rows          or khat rows
+  __shared__ float t1[kTileRows][D + 4];  // unused           or v rows
+
+  const int tid = threadIdx.x;
+  const int split = blockIdx.x % splits;
+  const int bh = blockIdx.x / splits;
+  const size_t base = static_cast<size_t>(bh) * N * D;
+  const int r_begin = split * rows_per_split;
+  const int r_end = min(N, r_begin + rows_per_split);
+  const int lrow = tid >> 3, chunk = tid & 7;
+  const int c0 = chunk * CH;
+
+  if (blockIdx.y == 0) {
+    load_state<D, true>(states + static_cast<size_t>(bh) * D * D, scale, M0);  // M0[c][a] = s S[a][c]
+    __syncthreads();
+    for (int r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+      const int row = r0 + lrow;
+      const bool live = row < r_end;
+      float q[CH], g[CH];
+#pragma unroll
+      for (int i = 0; i < CH; ++i) q[i] = g[i] = 0.0f;
+      if (live) {
+        load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * D + c0, q);
+        load_chunk<T, CH>(dO + base + static_cast<size_t>(row) * D + c0, g);
+      }
+      float ss = 0.0f;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) ss += q[i] * q[i];
+      const float inv = inv_norm(sum8(ss), eps);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        q[i] *= inv;
+        t0[lrow][c0 + i] = g[i];
+        g[i] = 0.0f;
+      }
+      __syncthreads();
+#pragma unroll 8
+      for (int c = 0; c < D; ++c) {
+        const float dc = t0[lrow][c];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) g[i] += dc * M0[c][c0 + i];  // g_a = s sum_c dO_c S[a][c]
+      }
+      float proj = 0.0f;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) proj += q[i] * g[i];
+      proj = sum8(proj);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) g[i] = (g[i] - q[i] * proj) * inv;
+      if (live) store_chunk<T, CH>(dQ + base + static_cast<size_t>(row) * D + c0, g);
+      __syncthreads();
+    }
+  } else {
+    const float* __restrict__ ds = dstates + static_cast<size_t>(bh) * D * D;
+    load_state<D, false>(ds, scale, M0);  // dS[a][c]
+    load_state<D, true>(ds, scale, M1);   // dS^T[c][a]
+    const uint8_t* __restrict__ m =
+        mask == nullptr ? nullptr : mask + static_cast<size_t>(bh / H) * N;
+    __syncthreads();
+    for (int r0 = r_begin; r0 < r_end; r0 += kTileRows) {
+      const int row = r0 + lrow;
+      const bool inrange = row < r_end;
+      bool live = inrange;
+      if (live && m != nullptr) live = m[row] != 0;
+      float k[CH], v[CH], gv[CH], h[CH];
+#pragma unroll
+      for (int i = 0; i < CH; ++i) k[i] = v[i] = 0.0f;
+      if (live) {
+        load_chunk<T, CH>(K + base + static_cast<size_t>(row) * D + c0, k);
+        load_chunk<T, CH>(V + base + static_cast<size_t>(row) * D + c0, v);
+      }
+      float ss = 0.0f;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) ss += k[i] * k[i];
+      const float inv = inv_norm(sum8(ss), eps);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        k[i] *= inv;
+        t0[lrow][c0 + i] = k[i];
+        t1[lrow][c0 + i] = v[i];
+        gv[i] = h[i] = 0.0f;
+      }
+      __syncthreads();
+#pragma unroll 8
+      for (int a = 0; a < D; ++a) {
+        const float ka = t0[lrow][a];  // dV_c = sum_a khat_a dS[a][c]
+        const float va = t1[lrow][a];  // h_a  = sum_c v_c dS[a][c] = sum_c v_c dS^T[c][a]
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          gv[i] += ka * M0[a][c0 + i];
+          h[i] += va * M1[a][c0 + i];
+        }
+      }
+      float proj = 0.0f;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) proj += k[i] * h[i];
+      proj = sum8(proj);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        h[i] = live ? (h[i] - k[i] * proj) * inv : 0.0f;
+        gv[i] = live ? gv[i] : 0.0f;
+      }
+      if (inrange) {
+        store_chunk<T, CH>(dK + base + static_cast<size_t>(row) * D + c0, h);
+        store_chunk<T, CH>(dV + base + static_cast<size_t>(row) * D + c0, gv);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Where the reduced states live: behind the partials when a reduction is needed,
+// otherwise the single partial of each slice already is the state.
+template <int D>
+const float* reduce_if_split(const Problem& p, const Plan& plan, int nstates) {
+  if (plan.splits == 1) return p.workspace;
+  const size_t BH = static_cast<size_t>(p.B) * p.H;
+  const size_t total = BH * D * D;
+  float* reduced = p.workspace + BH * plan.splits * D * D * nstates;
+  const dim3 grid(static_cast<unsigned>((total + kThreads - 1) / kThreads), nstates, 1);
+  hipLaunchKernelGGL(reduce_states_kernel, grid, dim3(kThreads), 0, p.stream, p.workspace, reduced,
+                     plan.splits, D * D, total, BH * plan.splits * D * D);
+  return reduced;
+}
+
+template <typename T, int D>
+hipError_t run_fwd(const Problem& p, const Plan& plan) {
+  const int BH = p.B * p.H;
+  const dim3 grid(static_cast<unsigned>(BH) * plan.splits, 1, 1);
+  hipLaunchKernelGGL((state_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+                     static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
+                     static_cast<const T*>(p.V), static_cast<const T*>(nullptr), p.mask,
+                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps);
+  const float* states = reduce_if_split<D>(p, plan, 1);
+  hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+                     static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.N,
+                     plan.splits, plan.rows_per_split, p.scale, p.eps);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t run_bwd(const Problem& p, const Plan& plan) {
+  const int BH = p.B * p.H;
+  const dim3 grid(static_cast<unsigned>(BH) * plan.splits, 2, 1);
+  const size_t second = static_cast<size_t>(BH) * plan.splits * D * D;
+  hipLaunchKernelGGL((state_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+                     static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
+                     static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask,
+                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps);
+  const float* states = reduce_if_split<D>(p, plan, 2);
+  const float* dstates = states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * D * D);
+  hipLaunchKernelGGL((apply_bwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+                     static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
+                     static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask, states,
+                     dstates, static_cast<T*>(p.dQ), static_cast<T*>(p.dK),
+                     static_cast<T*>(p.dV), p.H, p.N, plan.splits, plan.rows_per_split, p.scale,
+                     p.eps);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
+  switch (p.D) {
+    case 16: return bwd ? run_bwd<T, 16>(p, plan) : run_fwd<T, 16>(p, plan);
+    case 32: return bwd ? run_bwd<T, 32>(p, plan) : run_fwd<T, 32>(p, plan);
+    case 64: return bwd ? run_bwd<T, 64>(p, plan) : run_fwd<T, 64>(p, plan);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+Plan make_plan(int B, int H, int N, int D, bool is_bwd) {
+  // Enough workgroups to fill 256 compute units a few times over, at least one
+  // 32-row tile each.
+  const long BH = static_cast<long>(B) * H;
+  long splits = (2048 + BH - 1) / BH;
+  const long max_splits = (N + kTileRows - 1) / kTileRows;
+  if (splits > max_splits) splits = max_splits;
+  if (splits < 1) splits = 1;
+  long rows = (N + splits - 1) / splits;
+  rows = (rows + kTileRows - 1) / kTileRows * kTileRows;
+  splits = (N + rows - 1) / rows;
+  const size_t nstates = is_bwd ? 2 : 1;
+  Plan plan;
+  plan.splits = static_cast<int>(splits);
+  plan.rows_per_split = static_cast<int>(rows);
+  // partial states, plus the reduced states when there is more than one partial
+  plan.workspace_floats =
+      static_cast<size_t>(BH) * D * D * nstates * (splits + (splits > 1 ? 1 : 0));
+  return plan;
+}
+
+hipError_t launch_generic_fwd(const Problem& p, const Plan& plan) {
+  return p.dtype == 0 ? dispatch_d<float>(p, plan, false) : dispatch_d<bf16>(p, plan, false);
+}
+
+hipError_t launch_generic_bwd(const Problem& p, const Plan& plan) {
+  return p.dtype == 0 ? dispatch_d<float>(p, plan, true) : dispatch_d<bf16>(p, plan, true);
+}
+
+}  // namespace cotten

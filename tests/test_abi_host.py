@@ -1,0 +1,100 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any device work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_06935_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cotten_attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cotten_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(0, -10, -1):
+        s = binding.cotten_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 10
+    assert binding.cotten_status_string(-99) == "unknown status"
+
+
+def _fwd(lib, Q=0x1000, K=0x2000, V=0x3000, mask=None, O=0x4000, B=2, H=2, N=8, d=32, prm=None):
+    if prm is None:
+        return lib.cotten_attn_fwd(Q, K, V, mask, O, B, H, N, d, None)
+    return lib.cotten_attn_fwd_ex(Q, K, V, mask, O, B, H, N, d, None, ctypes.byref(prm))
+
+
+def _bwd(lib, Q=0x1000, K=0x2000, V=0x3000, dO=0x4000, dQ=0x5000, dK=0x6000, dV=0x7000,
+         B=2, H=2, N=8, d=32):
+    return lib.cotten_attn_bwd(Q, K, V, None, dO, dQ, dK, dV, B, H, N, d, None)
+
+
+def test_validation_errors_touch_no_device(lib):
+    assert _fwd(lib, Q=None) == -1
+    assert _fwd(lib, O=None) == -1
+    assert _bwd(lib, dO=None) == -1
+    assert _bwd(lib, dK=None) == -1
+    assert lib.cotten_attn_fwd_ex(0x1000, 0x2000, 0x3000, None, 0x4000, 1, 1, 8, 32, None, None) == -1
+    assert _fwd(lib, B=0) == -2
+    assert _fwd(lib, N=-5) == -2
+    assert _bwd(lib, H=0) == -2
+    assert _fwd(lib, d=48) == -3
+    assert _fwd(lib, d=128) == -3
+    assert _bwd(lib, d=0) == -3
+    assert _fwd(lib, K=0x2004) == -5
+    assert _bwd(lib, dV=0x7008) == -5
+    p = binding.CottenParams(7, 0.0, -1.0, None, 0)
+    assert _fwd(lib, prm=p) == -4
+    p = binding.CottenParams(binding.COTTEN_BF16, float("nan"), -1.0, None, 0)
+    assert _fwd(lib, prm=p) == -7
+    p = binding.CottenParams(binding.COTTEN_F32, 0.0, float("inf"), None, 0)
+    assert _fwd(lib, prm=p) == -7
+
+
+def test_workspace_rules(lib):
+    f = binding.cotten_attn_workspace_bytes
+    assert f(0, 2, 50, 32, 0, False) == 0 and f(4, 2, 50, 48, 0, False) == 0
+    for (B, H, N, d, dt) in [(256, 2, 50, 32, 0), (256, 2, 200, 32, 0), (128, 4, 200, 64, 1),
+                             (16, 4, 4096, 64, 1), (1, 1, 1 << 20, 64, 1)]:
+        fw, bw = f(B, H, N, d, dt, False), f(B, H, N, d, dt, True)
+        assert bw <= 2 * max(fw, 1) + 2 * B * H * d * d * 4
+        # only d x d states, a bounded number of them: independent of N once N is long
+        assert bw <= 2 * (2 * B * H + 2049) * d * d * 4
+    # a caller-provided workspace that is too small is refused on the host
+    need = f(16, 4, 4096, 64, 1, True)
+    if need > 16:
+        p = binding.CottenParams(binding.COTTEN_BF16, 0.0, -1.0, 0x10000, need - 16)
+        assert lib.cotten_attn_bwd_ex(0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000,
+                                      16, 4, 4096, 64, None, ctypes.byref(p)) == -6
+        p = binding.CottenParams(binding.COTTEN_BF16, 0.0, -1.0, 0x10004, need)
+        assert lib.cotten_attn_bwd_ex(0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000,
+                                      16, 4, 4096, 64, None, ctypes.byref(p)) == -5
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 32)
+    with pytest.raises(ValueError):
+        binding.cotten_attn_fwd(x, x, x, None)

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle on the
+same seeded inputs.  Bars: relative L2 error per output tensor <= 1e-5 for fp32 I/O and
+<= 2e-2 for bf16 I/O with fp32 accumulation."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_06935_amd import binding
+from paper_2602_06935_amd.inputs import WORKLOADS, make_batch, round_to_bf16
+
+from gpu_util import FP32_BAR, bar_for, gpu_bwd, gpu_fwd, rel_l2, to_f64, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _check_batch(oracle, b, fwd=True, bwd=True, label=""):
+    w = b.workload
+    bar = bar_for(w.dtype)
+    errs = {}
+    if fwd:
+        ref = oracle.fwd_linear(b.Q, b.K, b.V, b.mask, scale=b.scale, eps=b.eps)
+        got = gpu_fwd(b.Q, b.K, b.V, b.mask, w.dtype, scale=b.scale, eps=b.eps)
+        errs["O"] = rel_l2(got, ref)
+    if bwd:
+        refs = oracle.bwd(b.Q, b.K, b.V, b.dO, b.mask, scale=b.scale, eps=b.eps)
+        gots = gpu_bwd(b.Q, b.K, b.V, b.dO, b.mask, w.dtype, scale=b.scale, eps=b.eps)
+        for n, g, r in zip(("dQ", "dK", "dV"), gots, refs):
+            errs[n] = rel_l2(g, r)
+            if b.mask is not None and n in ("dK", "dV"):
+                dead = np.broadcast_to((b.mask == 0)[:, None, :, None], g.shape)
+                assert np.all(g[dead] == 0.0), f"{n}: masked rows must be exact zeros"
+    _say(f"[parity] {label or w.name} seed={b.seed} shape={b.Q.shape} {w.dtype} "
+         + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    for k, v in errs.items():
+        assert v <= bar, f"{k}: rel L2 {v:.3e} above {bar:.0e}"
+    return errs
+
+
+# ------------------------------------------------------------- the five workloads
+
+@pytest.mark.parametrize("seed", [0, 42, 123])
+def test_cfg1_forward_full_size(oracle, seed):
+    b = make_batch("cfg1", seed)
+    _check_batch(oracle, b, fwd=True, bwd=False)
+    # the plain entry point (fp32, scale 1/N, eps 1e-6) through its own symbol
+    lib = binding.load_library()
+    tq, tk, tv = (to_gpu(x, "f32") for x in (b.Q, b.K, b.V))
+    O = torch.empty_like(tq)
+    rc = lib.cotten_attn_fwd(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), None, O.data_ptr(),
+                             4, 2, 50, 32, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert rc == 0
+    assert rel_l2(to_f64(O), oracle.fwd_quadratic(b.Q, b.K, b.V, None, scale=1 / 50, eps=1e-6)) <= FP32_BAR
+
+
+@pytest.mark.parametrize("name,seed", [("cfg2", 0), ("cfg2", 42), ("cfg3", 0), ("cfg3", 123),
+                                       ("cfg4", 0), ("cfg4", 42)])
+def test_workloads_full_size(oracle, name, seed):
+    _check_batch(oracle, make_batch(name, seed))
+
+
+def test_cfg4_tiny_rows_reported_separately(oracle):
+    b = make_batch("cfg4", 7)
+    ref = oracle.bwd(b.Q, b.K, b.V, b.dO, b.mask, scale=b.scale, eps=b.eps)
+    got = gpu_bwd(b.Q, b.K, b.V, b.dO, b.mask, "bf16", scale=b.scale, eps=b.eps)
+    for name, X, g, r in (("dQ", b.Q, got[0], ref[0]), ("dK", b.K, got[1], ref[1])):
+        tiny = np.linalg.norm(X, axis=-1) < 1e-2
+        e_tiny, e_norm = rel_l2(g[tiny], r[tiny]), rel_l2(g[~tiny], r[~tiny])
+        _say(f"[parity] cfg4 {name}: tiny rows {e_tiny:.2e}  normal rows {e_norm:.2e}")
+        assert e_tiny <= 2e-2 and e_norm <= 2e-2
+
+
+def test_cfg5_long_history(oracle):
+    b = make_batch("cfg5", 0)
+    w = b.workload
+    _check_batch(oracle, b)
+    # the linear GPU path against the QUADRATIC definition on 2 sampled slices
+    got = gpu_fwd(b.Q, b.K, b.V, b.mask, w.dtype, scale=b.scale, eps=b.eps)
+    rng = np.random.default_rng(5)
+    for _ in range(2):
+        bi, hi = int(rng.integers(w.B)), int(rng.integers(w.H))
+        sl = (slice(bi, bi + 1), slice(hi, hi + 1))
+        ref = oracle.fwd_quadratic(b.Q[sl], b.K[sl], b.V[sl], b.mask[bi:bi + 1], scale=b.scale, eps=b.eps)
+        e = rel_l2(got[sl], ref)
+        _say(f"[parity] cfg5 slice ({bi},{hi}) vs quadratic form: {e:.2e}")
+        assert e <= 2e-2
+
+
+# ------------------------------------------------------------------- edge cases
+
+def _case(seed, B, H, N, d, dtype="f32", sigma=1.0):
+    rng = np.random.default_rng(seed)
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)).astype(np.float32) * np.float32(sigma) for _ in range(4))
+    if dtype == "bf16":
+        Q, K, V, dO = (round_to_bf16(x) for x in (Q, K, V, dO))
+    return Q, K, V, dO
+
+
+def _check_case(oracle, Q, K, V, dO, mask, dtype, scale=None, eps=None, label=""):
+    bar = bar_for(dtype)
+    oe = 1e-6 if eps is None else eps
+    ref_o = oracle.fwd_linear(Q, K, V, mask, scale=scale, eps=oe)
+    ref_g = oracle.bwd(Q, K, V, dO, mask, scale=scale, eps=oe)
+    got_o = gpu_fwd(Q, K, V, mask, dtype, scale=scale, eps=eps)
+    got_g = gpu_bwd(Q, K, V, dO, mask, dtype, scale=scale, eps=eps)
+    errs = [rel_l2(got_o, ref_o)] + [rel_l2(g, r) for g, r in zip(got_g, ref_g)]
+    _say(f"[parity] {label} shape={Q.shape} {dtype} " + " ".join(f"{e:.2e}" for e in errs))
+    assert all(np.isfinite(x).all() for x in (got_o, *got_g))
+    assert max(errs) <= bar, errs
+    return got_o, got_g
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d", [16, 32, 64])
+@pytest.mark.parametrize("N", [1, 7, 33, 200, 515])
+def test_ragged_shapes(oracle, dtype, d, N):
+    B, H = 3, 2
+    Q, K, V, dO = _case(N * 100 + d, B, H, N, d, dtype)
+    mask = (np.random.default_rng(N + d).random((B, N)) < 0.7).astype(np.uint8)
+    mask[:, -1] = 1
+    _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"ragged N={N} d={d}")
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 64)])
+def test_mask_semantics(oracle, dtype, d):
+    B, H, N = 4, 2, 77
+    Q, K, V, dO = _case(11, B, H, N, d, dtype)
+    mask = np.zeros((B, N), np.uint8)
+    mask[0, :] = 1            # full
+    mask[1, -1] = 1           # a single valid key
+    mask[2, ::3] = 1          # scattered (not contiguous padding)
+    # batch row 3: no valid key at all -> O = 0, dK = dV = 0
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, dtype, label="mask semantics")
+    assert np.all(got_o[3] == 0.0) and np.all(got_g[1][3] == 0.0) and np.all(got_g[2][3] == 0.0)
+    # garbage (NaN, Inf, huge) in masked K/V rows changes nothing, bit for bit
+    K2, V2 = K.copy(), V.copy()
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], K.shape)
+    K2[dead] = np.nan
+    V2[dead] = np.inf
+    o2 = gpu_fwd(Q, K2, V2, mask, dtype)
+    g2 = gpu_bwd(Q, K2, V2, dO, mask, dtype)
+    assert np.array_equal(o2, got_o)
+    for a, c in zip(g2, got_g):
+        assert np.array_equal(a, c)
+    # mask = NULL equals an all-ones mask, bit for bit
+    ones = np.ones((B, N), np.uint8)
+    assert np.array_equal(gpu_fwd(Q, K, V, None, dtype), gpu_fwd(Q, K, V, ones, dtype))
+
+
+@pytest.mark.parametrize("eps", [1e-12, 1e-6, 1e-3])
+def test_eps_and_scale(oracle, eps):
+    Q, K, V, dO = _case(21, 2, 2, 90, 32)
+    Q[0, 0, :5] *= 1e-4          # rows whose norm is comparable to sqrt(eps)
+    K[1, 1, 3:9] *= 1e-4
+    mask = np.ones((2, 90), np.uint8); mask[1, :40] = 0
+    _check_case(oracle, Q, K, V, dO, mask, "f32", scale=0.37, eps=eps, label=f"eps={eps}")
+
+
+def test_zero_rows_stay_finite(oracle):
+    Q, K, V, dO = _case(22, 2, 1, 40, 32)
+    Q[0, 0, 3] = 0.0
+    K[1, 0, 5] = 0.0
+    _check_case(oracle, Q, K, V, dO, None, "f32", label="zero rows")
+
+
+def test_deterministic_bits_and_caller_workspace():
+    b = make_batch("cfg3", 1, B=32)
+    w = b.workload
+    o1 = gpu_fwd(b.Q, b.K, b.V, b.mask, w.dtype)
+    g1 = gpu_bwd(b.Q, b.K, b.V, b.dO, b.mask, w.dtype)
+    need = binding.cotten_attn_workspace_bytes(32, w.H, w.N, w.d_h, binding.COTTEN_F32, True)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        o2 = gpu_fwd(b.Q, b.K, b.V, b.mask, w.dtype, workspace=ws)
+        g2 = gpu_bwd(b.Q, b.K, b.V, b.dO, b.mask, w.dtype, workspace=ws, stream=side)
+    assert np.array_equal(o1, o2)
+    for a, c in zip(g1, g2):
+        assert np.array_equal(a, c)
+
+
+def test_binding_reports_library_errors():
+    x = torch.zeros(1, 1, 8, 48, device="cuda")
+    with pytest.raises(binding.CottenError) as ei:
+        binding.cotten_attn_fwd(x, x, x, None)
+    assert ei.value.status == -3
