@@ -82,7 +82,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
 
   cotten::Problem p{};
   if (int rc = resolve(prm, N, &p.scale, &p.eps)) return rc;
-  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, bwd);
+  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
   const size_t need = plan.workspace_floats * sizeof(float);
   if (prm->workspace != nullptr) {
     if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
@@ -95,7 +95,11 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   p.B = B; p.H = H; p.N = N; p.D = d_h;
   p.dtype = prm->dtype;
   p.stream = static_cast<hipStream_t>(stream);
-  const hipError_t err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
+  hipError_t err;
+  if (plan.path == cotten::Plan::kGeneric)
+    err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
+  else
+    err = bwd ? cotten::launch_mfma_bf16_bwd(p, plan) : cotten::launch_mfma_bf16_fwd(p, plan);
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 
@@ -130,7 +134,7 @@ int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* 
 
 size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd) {
   if (check_shape(B, H, N, d_h, dtype) != COTTEN_OK) return 0;
-  return cotten::make_plan(B, H, N, d_h, is_bwd != 0).workspace_floats * sizeof(float);
+  return cotten::make_plan(B, H, N, d_h, dtype, is_bwd != 0).workspace_floats * sizeof(float);
 }
 
 const char* cotten_status_string(int status) {

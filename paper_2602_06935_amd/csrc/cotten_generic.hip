@@ -291,20 +291,6 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
   }
 }
 
-// Where the reduced states live: behind the partials when a reduction is needed,
-// otherwise the single partial of each slice already is the state.
-template <int D>
-const float* reduce_if_split(const Problem& p, const Plan& plan, int nstates) {
-  if (plan.splits == 1) return p.workspace;
-  const size_t BH = static_cast<size_t>(p.B) * p.H;
-  const size_t total = BH * D * D;
-  float* reduced = p.workspace + BH * plan.splits * D * D * nstates;
-  const dim3 grid(static_cast<unsigned>((total + kThreads - 1) / kThreads), nstates, 1);
-  hipLaunchKernelGGL(reduce_states_kernel, grid, dim3(kThreads), 0, p.stream, p.workspace, reduced,
-                     plan.splits, D * D, total, BH * plan.splits * D * D);
-  return reduced;
-}
-
 template <typename T, int D>
 hipError_t run_fwd(const Problem& p, const Plan& plan) {
   const int BH = p.B * p.H;
@@ -313,7 +299,7 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(nullptr), p.mask,
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps);
-  const float* states = reduce_if_split<D>(p, plan, 1);
+  const float* states = launch_reduce_states(p, plan, 1);
   hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.N,
                      plan.splits, plan.rows_per_split, p.scale, p.eps);
@@ -329,7 +315,7 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask,
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps);
-  const float* states = reduce_if_split<D>(p, plan, 2);
+  const float* states = launch_reduce_states(p, plan, 2);
   const float* dstates = states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * D * D);
   hipLaunchKernelGGL((apply_bwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
@@ -352,19 +338,54 @@ hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
 
 }  // namespace
 
-Plan make_plan(int B, int H, int N, int D, bool is_bwd) {
-  // Enough workgroups to fill 256 compute units a few times over, at least one
-  // 32-row tile each.
+const float* launch_reduce_states(const Problem& p, const Plan& plan, int nstates) {
+  if (plan.splits == 1) return p.workspace;
+  const size_t BH = static_cast<size_t>(p.B) * p.H;
+  const int dd = p.D * p.D;
+  const size_t total = BH * dd;
+  float* reduced = p.workspace + BH * plan.splits * dd * nstates;
+  const dim3 grid(static_cast<unsigned>((total + kThreads - 1) / kThreads), nstates, 1);
+  hipLaunchKernelGGL(reduce_states_kernel, grid, dim3(kThreads), 0, p.stream, p.workspace, reduced,
+                     plan.splits, dd, total, BH * plan.splits * dd);
+  return reduced;
+}
+
+Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
   const long BH = static_cast<long>(B) * H;
-  long splits = (2048 + BH - 1) / BH;
-  const long max_splits = (N + kTileRows - 1) / kTileRows;
-  if (splits > max_splits) splits = max_splits;
-  if (splits < 1) splits = 1;
-  long rows = (N + splits - 1) / splits;
-  rows = (rows + kTileRows - 1) / kTileRows * kTileRows;
-  splits = (N + rows - 1) / rows;
   const size_t nstates = is_bwd ? 2 : 1;
   Plan plan;
+  long splits, rows;
+  if (mfma_bf16_supports(dtype, D)) {
+    // One workgroup per slice while that fills the chip or the slice is short; otherwise
+    // cut the sequence so that about 512 workgroups exist, in blocks of 64 rows.
+    constexpr long kFusedMaxN = 2048, kBlock = 64;
+    if (N <= kFusedMaxN && (BH >= 256 || N <= 256)) {
+      plan.path = Plan::kFused;
+      plan.splits = 1;
+      plan.rows_per_split = N;
+      plan.workspace_floats = 0;
+      return plan;
+    }
+    plan.path = Plan::kSplit;
+    splits = (512 + BH - 1) / BH;
+    const long by_len = (N + kFusedMaxN - 1) / kFusedMaxN;
+    if (splits < by_len) splits = by_len;
+    const long max_splits = (N + kBlock - 1) / kBlock;
+    if (splits > max_splits) splits = max_splits;
+    rows = (N + splits - 1) / splits;
+    rows = (rows + kBlock - 1) / kBlock * kBlock;
+  } else {
+    // Enough workgroups to fill 256 compute units a few times over, at least one
+    // 32-row tile each.
+    plan.path = Plan::kGeneric;
+    splits = (2048 + BH - 1) / BH;
+    const long max_splits = (N + kTileRows - 1) / kTileRows;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    rows = (N + splits - 1) / splits;
+    rows = (rows + kTileRows - 1) / kTileRows * kTileRows;
+  }
+  splits = (N + rows - 1) / rows;
   plan.splits = static_cast<int>(splits);
   plan.rows_per_split = static_cast<int>(rows);
   // partial states, plus the reduced states when there is more than one partial

@@ -25,19 +25,34 @@ struct Problem {
 };
 
 // How a call is cut into workgroups.
+//   path        : kFused   one workgroup per slice runs every phase in one launch (no workspace)
+//                 kSplit   MFMA kernels, `splits` workgroups per slice, states via the workspace
+//                 kGeneric vector-ALU kernels for shapes the MFMA kernels do not cover
 //   splits      : workgroups per slice in the state-reduction kernel; each reduces
 //                 `rows_per_split` consecutive rows to one partial d x d state
-//   workspace   : floats = B*H*splits*D*D (forward) or twice that (backward: S and dS)
+//   workspace   : floats; partial states [nstates][B*H*splits][D*D], followed, when
+//                 splits > 1, by the reduced states [nstates][B*H][D*D]
 struct Plan {
+  enum Path { kGeneric = 0, kFused = 1, kSplit = 2 };
+  Path path;
   int splits;
   int rows_per_split;
   size_t workspace_floats;
 };
 
-Plan make_plan(int B, int H, int N, int D, bool is_bwd);
+Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd);
 
-// Two-kernel path (state reduction, then apply) for any supported shape.
+// Sums the partial states in split order; returns where the reduced states are
+// (the partials themselves when splits == 1).  nstates = 1 (S) or 2 (S and dS).
+const float* launch_reduce_states(const Problem& p, const Plan& plan, int nstates);
+
+// Vector-ALU path (state reduction, then apply) for any supported shape.
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
+
+// MFMA path, bf16 I/O with d_h = 64.
+bool mfma_bf16_supports(int dtype, int D);
+hipError_t launch_mfma_bf16_fwd(const Problem& p, const Plan& plan);
+hipError_t launch_mfma_bf16_bwd(const Problem& p, const Plan& plan);
 
 }  // namespace cotten
