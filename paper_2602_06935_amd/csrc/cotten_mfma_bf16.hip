@@ -18,6 +18,22 @@
 #include "cotten_device.h"
 #include "cotten_launch.h"
 
+// Optional phase timestamps for tuning builds (-DCOTTEN_TRACE): wave w of workgroup b < 8
+// stores the shader clock at trace point i.  Compiles to nothing otherwise.
+#ifdef COTTEN_TRACE
+__device__ long long cotten_trace_buf[8 * 4 * 16];
+#define COTTEN_TRACE_POINT(i)                                                        \
+  do {                                                                               \
+    if (blockIdx.x < 8 && blockIdx.y == 0 && (threadIdx.x & 63) == 0)                \
+      cotten_trace_buf[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
+  } while (0)
+extern "C" int cotten_trace_read(long long* host, int n) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(cotten_trace_buf), n * sizeof(long long)));
+}
+#else
+#define COTTEN_TRACE_POINT(i) do {} while (0)
+#endif
+
 namespace cotten {
 namespace {
 
@@ -41,9 +57,7 @@ constexpr int kTileBytes = TR * RS * 2;       // 2304
 constexpr int kScratchBytes = TR * SCS * 4;   // 4352
 constexpr int kWaveBytes = 2 * kTileBytes + 2 * kScratchBytes;  // 13312
 constexpr int kWorkBytes = kWaves * kWaveBytes;                 // 53248
-constexpr int kStateBytes = D * D * 4;                          // fp32 reduction buffer
 constexpr int kOperandBytes = D * RS * 2;                       // one bf16 state operand
-static_assert(2 * kStateBytes <= kWorkBytes, "reduction buffers alias the working set");
 // LDS map: [working set / reduction buffers][operand 0][operand 1][mask bytes]
 constexpr int kOp0Offset = kWorkBytes;
 constexpr int kOp1Offset = kOp0Offset + kOperandBytes;
@@ -69,6 +83,31 @@ __device__ __forceinline__ u32x4_t pack8(const float (&f)[8]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
   return r;
+}
+
+// Sum over the 8 consecutive lanes that share one row, by lane-permuting adds (no LDS).
+__device__ __forceinline__ float row_sum8(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // other quad of the 8
+  return x;
+}
+
+// Sum of squares of the 8 bf16 values in a 128-bit register group (fp32 accumulation).
+__device__ __forceinline__ float sumsq8(const u32x4_t r) {
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(r[i] << 16), hi = __uint_as_float(r[i] & 0xffff0000u);
+    s += lo * lo;
+    s += hi * hi;
+  }
+  return s;
+}
+
+// 1/sqrt(ss + eps) for a live row (hardware reciprocal square root, about 1 ulp), 0 otherwise.
+__device__ __forceinline__ float inv_norm_or_zero(float ss, float eps, bool live) {
+  return live ? __builtin_amdgcn_rsqf(ss + eps) : 0.0f;
 }
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -98,16 +137,18 @@ struct Raw {
   int live;
 };
 
-// mask_lds[row - m_base] != 0 <=> row is in range and valid.  USE_Y: second tensor wanted.
+// Loads tile rows row0 .. row0+15.  A row takes part when it is below `row_limit` and, if
+// `flags` is given, flags[row - m_base] != 0 (LDS copy of the key mask).  USE_Y: second tensor.
 template <bool USE_Y>
 __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const bf16* __restrict__ X,
                                          const bf16* __restrict__ Y, int row0,
-                                         const uint8_t* mask_lds, int m_base) {
+                                         const uint8_t* flags, int m_base, int row_limit) {
   r.live = 0;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int row = row0 + L.r8 + 8 * h;
-    const bool live = mask_lds[row - m_base] != 0;
+    bool live = row < row_limit;
+    if (flags != nullptr) live = flags[row - m_base] != 0;
     r.x[h] = u32x4_t{0, 0, 0, 0};
     r.y[h] = u32x4_t{0, 0, 0, 0};
     if (live) {
@@ -119,24 +160,27 @@ __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const bf16* __re
   }
 }
 
-// Normalises the x rows in fp32, writes xhat (bf16) to Xt and the raw y rows to Yt.
-// Rows that are not live become zeros in both tiles.  inv[h] = 1/r of row h.
-template <bool USE_Y>
+// What becomes of the x rows on their way to the LDS tile.
+enum XMode { kXNone = 0, kXRaw = 1, kXNormalized = 2 };
+
+// inv[h] = 1/r of row h (0 for rows that do not take part; their registers are zero).
+// Xt receives nothing, the raw rows, or xhat rounded to bf16; Yt the raw y rows.
+template <int XMODE, bool USE_Y>
 __device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, lds_bf16* Xt,
                                       lds_bf16* Yt, float (&inv)[2]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    float f[8];
-    unpack8(r.x[h], f);
-    float ss = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ss += f[i] * f[i];
-    inv[h] = inv_norm(sum8(ss), eps);
-    const bool live = (r.live >> h) & 1;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) f[i] = live ? f[i] * inv[h] : 0.0f;
+    inv[h] = inv_norm_or_zero(row_sum8(sumsq8(r.x[h])), eps, (r.live >> h) & 1);
     const int off = (L.r8 + 8 * h) * RS + L.ch * 8;
-    *reinterpret_cast<u32x4_t*>(Xt + off) = pack8(f);
+    if (XMODE == kXNormalized) {
+      float f[8];
+      unpack8(r.x[h], f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] *= inv[h];
+      *reinterpret_cast<u32x4_t*>(Xt + off) = pack8(f);
+    } else if (XMODE == kXRaw) {
+      *reinterpret_cast<u32x4_t*>(Xt + off) = r.x[h];
+    }
     if (USE_Y) *reinterpret_cast<u32x4_t*>(Yt + off) = r.y[h];
   }
 }
@@ -250,25 +294,34 @@ __device__ __forceinline__ void fill_flags(uint8_t* flags, const uint8_t* __rest
   }
 }
 
-// Walks the tiles t0, t0+kWaves, ... < t_end owned by this wave with the next tile's
-// global loads in flight while the current one is processed.
+// First tile of this wave (tile index = wave), issued early by the caller.
+template <bool USE_Y>
+__device__ __forceinline__ void load_first(Raw& a, const Lane& L, const bf16* __restrict__ X,
+                                           const bf16* __restrict__ Y, int row_begin, int n_tiles,
+                                           const uint8_t* flags, int m_base, int row_limit) {
+  a.live = 0;
+  if (L.wave < n_tiles)
+    load_raw<USE_Y>(a, L, X, Y, row_begin + L.wave * TR, flags, m_base, row_limit);
+}
+
+// Walks the tiles wave, wave+kWaves, ... < n_tiles owned by this wave with the next tile's
+// global loads in flight while the current one is processed.  `a` holds the first tile.
 template <bool USE_Y, typename F>
 __device__ __forceinline__ void for_each_tile(const Lane& L, const bf16* __restrict__ X,
                                               const bf16* __restrict__ Y, int row_begin,
                                               int n_tiles, const uint8_t* flags, int m_base,
-                                              F&& body) {
+                                              int row_limit, Raw& a, F&& body) {
   int t = L.wave;
   if (t >= n_tiles) return;
-  Raw a, b;
-  load_raw<USE_Y>(a, L, X, Y, row_begin + t * TR, flags, m_base);
+  Raw b;
   while (true) {
     bool more = t + kWaves < n_tiles;
-    if (more) load_raw<USE_Y>(b, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base);
+    if (more) load_raw<USE_Y>(b, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
     body(a, row_begin + t * TR);
     if (!more) break;
     t += kWaves;
     more = t + kWaves < n_tiles;
-    if (more) load_raw<USE_Y>(a, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base);
+    if (more) load_raw<USE_Y>(a, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
     body(b, row_begin + t * TR);
     if (!more) break;
     t += kWaves;
@@ -276,30 +329,34 @@ __device__ __forceinline__ void for_each_tile(const Lane& L, const bf16* __restr
 }
 
 // ---- passes -------------------------------------------------------------------------
+// Every pass takes the wave's first tile already loaded in `first`.
 
 // acc += sum over live rows of xhat^T y for rows [row_begin, row_begin + 16*n_tiles)
 __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds& W,
                                            const bf16* __restrict__ X, const bf16* __restrict__ Y,
                                            int row_begin, int n_tiles, const uint8_t* flags,
-                                           int m_base, float eps, f32x16_t (&acc)[2][2]) {
-  for_each_tile<true>(L, X, Y, row_begin, n_tiles, flags, m_base, [&](const Raw& r, int) {
+                                           int m_base, int row_limit, float eps, Raw& first,
+                                           f32x16_t (&acc)[2][2]) {
+  for_each_tile<true>(L, X, Y, row_begin, n_tiles, flags, m_base, row_limit, first,
+                      [&](const Raw& r, int) {
     if (__ballot(r.live != 0) == 0) return;  // no live row in this tile (uniform)
     float inv[2];
-    stage<true>(r, L, eps, W.Xt, W.Yt, inv);
+    stage<kXNormalized, true>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
     state_mfma(W.Xt, W.Yt, L, acc);
     wave_lds_fence();
   });
 }
 
-// O rows = qhat rows x W  (W = scale * S, operand image op[c][a])
+// O rows = (q rows x W) / r   (W = scale * S, operand image op[c][a])
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds& W,
                                                const bf16* __restrict__ Q, bf16* __restrict__ O,
-                                               int row_begin, int n_tiles, const uint8_t* flags,
-                                               int m_base, float eps, const Operand& Sop) {
-  for_each_tile<false>(L, Q, Q, row_begin, n_tiles, flags, m_base, [&](const Raw& r, int row0) {
+                                               int row_begin, int n_tiles, int row_limit,
+                                               float eps, Raw& first, const Operand& Sop) {
+  for_each_tile<false>(L, Q, Q, row_begin, n_tiles, nullptr, 0, row_limit, first,
+                       [&](const Raw& r, int row0) {
     float inv[2];
-    stage<false>(r, L, eps, W.Xt, W.Yt, inv);
+    stage<kXRaw, false>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
     f32x4_t out[4];
     apply_mfma(W.Xt, Sop, L, out);
@@ -307,11 +364,11 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds& W,
     wave_lds_fence();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      if ((r.live >> h) & 1) {
-        float o[8];
-        from_scratch(W.Sc0, L, h, o);
-        store_row(O, row0 + L.r8 + 8 * h, L, o);
-      }
+      float o[8];
+      from_scratch(W.Sc0, L, h, o);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] *= inv[h];
+      if ((r.live >> h) & 1) store_row(O, row0 + L.r8 + 8 * h, L, o);
     }
     wave_lds_fence();
   });
@@ -323,15 +380,26 @@ template <bool ACCUM>
 __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds& W,
                                            const bf16* __restrict__ Q, const bf16* __restrict__ dO,
                                            bf16* __restrict__ dQ, int row_begin, int n_tiles,
-                                           const uint8_t* flags, int m_base, float eps,
-                                           const Operand& Sop, f32x16_t (&dsacc)[2][2]) {
-  for_each_tile<true>(L, Q, dO, row_begin, n_tiles, flags, m_base, [&](const Raw& r, int row0) {
+                                           int row_limit, float eps, Raw& first,
+                                           const lds_bf16* Simage, f32x16_t (&dsacc)[2][2]) {
+  // With the 64 accumulator registers live the operand is re-read from LDS for every tile;
+  // without them it stays in registers.
+  Operand held;
+  if (!ACCUM) held.load(Simage, L);
+  for_each_tile<true>(L, Q, dO, row_begin, n_tiles, nullptr, 0, row_limit, first,
+                      [&](const Raw& r, int row0) {
     float inv[2];
-    stage<true>(r, L, eps, W.Xt, W.Yt, inv);
+    stage<ACCUM ? kXNormalized : kXNone, true>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
     if (ACCUM) state_mfma(W.Xt, W.Yt, L, dsacc);
     f32x4_t out[4];
-    apply_mfma(W.Yt, Sop, L, out);  // g = scale * dO S^T
+    if (ACCUM) {
+      Operand fresh;
+      fresh.load(Simage, L);
+      apply_mfma(W.Yt, fresh, L, out);  // g = scale * dO S^T
+    } else {
+      apply_mfma(W.Yt, held, L, out);
+    }
     to_scratch(out, W.Sc0, L);
     wave_lds_fence();
 #pragma unroll
@@ -345,7 +413,7 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds& W,
         q[i] *= inv[h];
         proj += q[i] * g[i];
       }
-      proj = sum8(proj);
+      proj = row_sum8(proj);
 #pragma unroll
       for (int i = 0; i < 8; ++i) g[i] = (g[i] - q[i] * proj) * inv[h];
       if ((r.live >> h) & 1) store_row(dQ, row0 + L.r8 + 8 * h, L, g);
@@ -354,21 +422,22 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds& W,
   });
 }
 
-// dK, dV rows from (K, V) and scale * dS: dV = khat dS (operand image op[c][a]),
-// h = v dS^T (operand image op[a][c]).  Rows that are in range but masked get zeros.
+// dK, dV rows from (K, V) and scale * dS: dV = (k dS)/r (operand image op[c][a]),
+// h = v dS^T (operand image op[a][c]).  Rows below row_limit that are masked get zeros.
 __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds& W,
                                             const bf16* __restrict__ K, const bf16* __restrict__ V,
                                             bf16* __restrict__ dK, bf16* __restrict__ dV,
                                             int row_begin, int n_tiles, const uint8_t* flags,
-                                            int m_base, int N, float eps, const Operand& dSop_v,
-                                            const Operand& dSop_h) {
-  for_each_tile<true>(L, K, V, row_begin, n_tiles, flags, m_base, [&](const Raw& r, int row0) {
-    const float zeros[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                            int m_base, int row_limit, float eps, Raw& first,
+                                            const Operand& dSop_v, const Operand& dSop_h) {
+  for_each_tile<true>(L, K, V, row_begin, n_tiles, flags, m_base, row_limit, first,
+                      [&](const Raw& r, int row0) {
     if (__ballot(r.live != 0) == 0) {  // nothing live: only the zero rows are due
+      const float zeros[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int row = row0 + L.r8 + 8 * h;
-        if (row < N) {
+        if (row < row_limit) {
           store_row(dK, row, L, zeros);
           store_row(dV, row, L, zeros);
         }
@@ -376,7 +445,7 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds& W,
       return;
     }
     float inv[2];
-    stage<true>(r, L, eps, W.Xt, W.Yt, inv);
+    stage<kXRaw, true>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
     f32x4_t out[4];
     apply_mfma(W.Xt, dSop_v, L, out);
@@ -387,7 +456,6 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds& W,
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int row = row0 + L.r8 + 8 * h;
-      const bool live = (r.live >> h) & 1;
       float gv[8], hh[8], k[8];
       from_scratch(W.Sc0, L, h, gv);
       from_scratch(W.Sc1, L, h, hh);
@@ -395,16 +463,16 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds& W,
       float proj = 0.0f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        k[i] *= inv[h];
+        k[i] *= inv[h];      // inv = 0 on masked rows: khat, dK and dV come out as exact zeros
         proj += k[i] * hh[i];
       }
-      proj = sum8(proj);
+      proj = row_sum8(proj);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        hh[i] = live ? (hh[i] - k[i] * proj) * inv[h] : 0.0f;
-        gv[i] = live ? gv[i] : 0.0f;
+        hh[i] = (hh[i] - k[i] * proj) * inv[h];
+        gv[i] *= inv[h];
       }
-      if (row < N) {
+      if (row < row_limit) {
         store_row(dK, row, L, hh);
         store_row(dV, row, L, gv);
       }
@@ -415,11 +483,33 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds& W,
 
 // ---- workgroup-level state handling -------------------------------------------------
 
+// Reduction buffers: two fp32 images of the 64x64 state stored column-major with a padded
+// stride, R[n * kRStride + m], so that the 4 consecutive rows an accumulator register
+// group holds move as one 128-bit LDS access.
+constexpr int kRStride = 68;
+constexpr int kRFloats = D * kRStride;
+static_assert(2 * kRFloats * 4 <= kWorkBytes, "reduction buffers alias the working set");
+
+__device__ __forceinline__ f32x4_t quad(const f32x16_t& a, int j) {
+  return f32x4_t{a[4 * j], a[4 * j + 1], a[4 * j + 2], a[4 * j + 3]};
+}
+
 // Sums the four per-wave accumulators in the fixed order (w0 + w1) + (w2 + w3):
-// afterwards R0 + R1 (two fp32 64x64 buffers at the start of LDS) is the total.
+// afterwards R0 + R1 (at the start of LDS) is the total.
 __device__ __forceinline__ void wg_reduce(const Lane& L, unsigned char* smem,
                                           const f32x16_t (&acc)[2][2]) {
-  float* R = reinterpret_cast<float*>(smem) + (L.wave >> 1) * (D * D);
+  float* R = reinterpret_cast<float*>(smem) + (L.wave >> 1) * kRFloats;
+  f32x4_t* dst[2][2][4];
+#pragma unroll
+  for (int at = 0; at < 2; ++at)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int m = 32 * at + 8 * j + 4 * (L.lane >> 5);
+        const int n = 32 * ct + (L.lane & 31);
+        dst[at][ct][j] = reinterpret_cast<f32x4_t*>(R + n * kRStride + m);
+      }
   __syncthreads();  // working set no longer in use
   if ((L.wave & 1) == 0) {
 #pragma unroll
@@ -427,38 +517,75 @@ __device__ __forceinline__ void wg_reduce(const Lane& L, unsigned char* smem,
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = 32 * at + 8 * (v >> 2) + 4 * (L.lane >> 5) + (v & 3);
-          R[m * D + 32 * ct + (L.lane & 31)] = acc[at][ct][v];
-        }
+        for (int j = 0; j < 4; ++j)
+          *dst[at][ct][j] = quad(acc[at][ct], j);
   }
   __syncthreads();
   if ((L.wave & 1) == 1) {
+    f32x4_t other[2][2][4];  // all reads first, so that they overlap
 #pragma unroll
     for (int at = 0; at < 2; ++at)
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = 32 * at + 8 * (v >> 2) + 4 * (L.lane >> 5) + (v & 3);
-          R[m * D + 32 * ct + (L.lane & 31)] += acc[at][ct][v];
-        }
+        for (int j = 0; j < 4; ++j) other[at][ct][j] = *dst[at][ct][j];
+#pragma unroll
+    for (int at = 0; at < 2; ++at)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          *dst[at][ct][j] = other[at][ct][j] +
+                            quad(acc[at][ct], j);
   }
   __syncthreads();
 }
 
-// Builds bf16 operand images from a 64x64 fp32 state M (given as src0 [+ src1]):
-//   natural image   op[m][n] = scale * M[m][n]   (for products contracting over n)
-//   transposed image op[n][m] = scale * M[m][n]  (for products contracting over m)
-__device__ __forceinline__ void make_operands(const float* src0, const float* src1, float scale,
+// Element (m, n) of the reduced state: from LDS (R0 + R1) or from a row-major global array.
+struct StateSource {
+  const float* lds;     // R0 (R1 follows) or nullptr
+  const float* global;  // row-major 64x64 or nullptr
+  __device__ __forceinline__ float at(int m, int n) const {
+    if (lds != nullptr) return lds[n * kRStride + m] + lds[kRFloats + n * kRStride + m];
+    return global[m * D + n];
+  }
+};
+
+// Builds bf16 operand images of scale * M for the apply products:
+//   natural    op[m][n] = M[m][n]   (products contracting over n)
+//   transposed op[n][m] = M[m][n]   (products contracting over m)
+// Two neighbouring elements are rounded together and leave as one 32-bit LDS write.
+__device__ __forceinline__ void make_operands(const StateSource src, float scale,
                                               lds_bf16* natural, lds_bf16* transposed) {
-  for (int e = threadIdx.x; e < D * D; e += kThreads) {
-    float v = src0[e];
-    if (src1 != nullptr) v += src1[e];
-    const bf16 b = from_float<bf16>(v * scale);
-    const int m = e >> 6, n = e & 63;
-    if (natural != nullptr) natural[m * RS + n] = b.bits;
-    if (transposed != nullptr) transposed[n * RS + m] = b.bits;
+  constexpr int kPer = D * D / 2 / kThreads;  // element pairs per thread
+  if (natural != nullptr) {
+    float lo[kPer], hi[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, m = e >> 5, n = (e & 31) * 2;
+      lo[i] = src.at(m, n);
+      hi[i] = src.at(m, n + 1);
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, m = e >> 5, n = (e & 31) * 2;
+      *reinterpret_cast<uint32_t*>(natural + m * RS + n) = pack_bf16(lo[i] * scale, hi[i] * scale);
+    }
+  }
+  if (transposed != nullptr) {
+    float lo[kPer], hi[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, n = e & 63, m = (e >> 6) * 2;
+      lo[i] = src.at(m, n);
+      hi[i] = src.at(m + 1, n);
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, n = e & 63, m = (e >> 6) * 2;
+      *reinterpret_cast<uint32_t*>(transposed + n * RS + m) =
+          pack_bf16(lo[i] * scale, hi[i] * scale);
+    }
   }
 }
 
@@ -484,26 +611,26 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(
   const int bh = blockIdx.x;
   const size_t base = static_cast<size_t>(bh) * N * D;
   const int n_tiles = (N + TR - 1) / TR;
-  const int n_flags = n_tiles * TR;
-  uint8_t* kflags = smem + kMaskOffset;        // valid keys
-  uint8_t* rflags = kflags + n_flags;          // rows in range
+  uint8_t* kflags = smem + kMaskOffset;  // valid keys
   lds_bf16* op0 = reinterpret_cast<lds_bf16*>(smem + kOp0Offset);
 
+  Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
+  load_first<false>(qfirst, L, Q + base, Q + base, 0, n_tiles, nullptr, 0, N);
   fill_flags(kflags, mask == nullptr ? nullptr : mask + static_cast<size_t>(bh / H) * N, 0,
-             n_flags, N);
-  fill_flags(rflags, nullptr, 0, n_flags, N);
+             n_tiles * TR, N);
   __syncthreads();
+  load_first<true>(kfirst, L, K + base, V + base, 0, n_tiles, kflags, 0, N);
 
   f32x16_t acc[2][2];
   zero_acc(acc);
-  state_pass(L, W, K + base, V + base, 0, n_tiles, kflags, 0, eps, acc);
+  state_pass(L, W, K + base, V + base, 0, n_tiles, kflags, 0, N, eps, kfirst, acc);
   wg_reduce(L, smem, acc);
-  const float* R0 = reinterpret_cast<const float*>(smem);
-  make_operands(R0, R0 + D * D, scale, nullptr, op0);  // O = qhat S: contraction over rows of S
+  // O = qhat S: contraction over rows of S
+  make_operands(StateSource{reinterpret_cast<const float*>(smem), nullptr}, scale, nullptr, op0);
   __syncthreads();
   Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass(L, W, Q + base, O + base, 0, n_tiles, rflags, 0, eps, Sop);
+  fwd_apply_pass(L, W, Q + base, O + base, 0, n_tiles, N, eps, qfirst, Sop);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(
@@ -515,38 +642,45 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(
   const int bh = blockIdx.x;
   const size_t base = static_cast<size_t>(bh) * N * D;
   const int n_tiles = (N + TR - 1) / TR;
-  const int n_flags = n_tiles * TR;
   uint8_t* kflags = smem + kMaskOffset;
-  uint8_t* rflags = kflags + n_flags;
   lds_bf16* op0 = reinterpret_cast<lds_bf16*>(smem + kOp0Offset);
   lds_bf16* op1 = reinterpret_cast<lds_bf16*>(smem + kOp1Offset);
-  const float* R0 = reinterpret_cast<const float*>(smem);
+  const StateSource reduced{reinterpret_cast<const float*>(smem), nullptr};
 
+  COTTEN_TRACE_POINT(0);
+  Raw qfirst, kfirst;
+  load_first<true>(qfirst, L, Q + base, dO + base, 0, n_tiles, nullptr, 0, N);
   fill_flags(kflags, mask == nullptr ? nullptr : mask + static_cast<size_t>(bh / H) * N, 0,
-             n_flags, N);
-  fill_flags(rflags, nullptr, 0, n_flags, N);
+             n_tiles * TR, N);
   __syncthreads();
+  COTTEN_TRACE_POINT(1);
+  load_first<true>(kfirst, L, K + base, V + base, 0, n_tiles, kflags, 0, N);
 
   f32x16_t acc[2][2];
   zero_acc(acc);
-  state_pass(L, W, K + base, V + base, 0, n_tiles, kflags, 0, eps, acc);
+  state_pass(L, W, K + base, V + base, 0, n_tiles, kflags, 0, N, eps, kfirst, acc);
+  COTTEN_TRACE_POINT(2);
   wg_reduce(L, smem, acc);
-  make_operands(R0, R0 + D * D, scale, op0, nullptr);  // g = dO S^T: contraction over columns of S
+  COTTEN_TRACE_POINT(3);
+  make_operands(reduced, scale, op0, nullptr);  // g = dO S^T: contraction over columns of S
   __syncthreads();
-  {
-    Operand Sop;
-    Sop.load(op0, L);
-    zero_acc(acc);
-    bwd_q_pass<true>(L, W, Q + base, dO + base, dQ + base, 0, n_tiles, rflags, 0, eps, Sop, acc);
-  }
+  zero_acc(acc);
+  COTTEN_TRACE_POINT(4);
+  bwd_q_pass<true>(L, W, Q + base, dO + base, dQ + base, 0, n_tiles, N, eps, qfirst, op0, acc);
+  COTTEN_TRACE_POINT(5);
+  // the key/value tiles are walked again: get the first one moving before the reduction
+  load_first<true>(kfirst, L, K + base, V + base, 0, n_tiles, kflags, 0, N);
   wg_reduce(L, smem, acc);
-  make_operands(R0, R0 + D * D, scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
+  COTTEN_TRACE_POINT(6);
+  make_operands(reduced, scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
   __syncthreads();
   Operand dS_v, dS_h;
   dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
   dS_h.load(op0, L);  // h = v dS^T: contraction over columns of dS
-  bwd_kv_pass(L, W, K + base, V + base, dK + base, dV + base, 0, n_tiles, kflags, 0, N, eps, dS_v,
-              dS_h);
+  COTTEN_TRACE_POINT(7);
+  bwd_kv_pass(L, W, K + base, V + base, dK + base, dV + base, 0, n_tiles, kflags, 0, N, eps,
+              kfirst, dS_v, dS_h);
+  COTTEN_TRACE_POINT(8);
 }
 
 // Split path, step 1: partial states of a block of rows.  blockIdx.y = 0: (K,V) under
@@ -564,18 +698,23 @@ __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(
   const int r_begin = split * rows_per_split;
   const int r_end = min(N, r_begin + rows_per_split);
   const int n_tiles = (r_end - r_begin + TR - 1) / TR;
-  uint8_t* flags = smem + kMaskOffset;
-  fill_flags(flags, (second || mask == nullptr) ? nullptr : mask + static_cast<size_t>(bh / H) * N,
-             r_begin, n_tiles * TR, r_end);
-  __syncthreads();
+  const bool masked = !second && mask != nullptr;
+  uint8_t* flags = masked ? smem + kMaskOffset : nullptr;
+  const bf16* X = (second ? Q : K) + base;
+  const bf16* Y = (second ? dO : V) + base;
+  if (masked) {
+    fill_flags(flags, mask + static_cast<size_t>(bh / H) * N, r_begin, n_tiles * TR, r_end);
+    __syncthreads();
+  }
+  Raw first;
+  load_first<true>(first, L, X, Y, r_begin, n_tiles, flags, r_begin, r_end);
   f32x16_t acc[2][2];
   zero_acc(acc);
-  state_pass(L, W, (second ? Q : K) + base, (second ? dO : V) + base, r_begin, n_tiles, flags,
-             r_begin, eps, acc);
+  state_pass(L, W, X, Y, r_begin, n_tiles, flags, r_begin, r_end, eps, first, acc);
   wg_reduce(L, smem, acc);
-  const float* R0 = reinterpret_cast<const float*>(smem);
+  const StateSource reduced{reinterpret_cast<const float*>(smem), nullptr};
   float* out = ws + (second ? second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
-  for (int e = threadIdx.x; e < D * D; e += kThreads) out[e] = R0[e] + R0[D * D + e];
+  for (int e = threadIdx.x; e < D * D; e += kThreads) out[e] = reduced.at(e >> 6, e & 63);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(
@@ -589,14 +728,15 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(
   const int r_begin = split * rows_per_split;
   const int r_end = min(N, r_begin + rows_per_split);
   const int n_tiles = (r_end - r_begin + TR - 1) / TR;
-  uint8_t* flags = smem + kMaskOffset;
   lds_bf16* op0 = reinterpret_cast<lds_bf16*>(smem + kOp0Offset);
-  fill_flags(flags, nullptr, r_begin, n_tiles * TR, r_end);
-  make_operands(states + static_cast<size_t>(bh) * D * D, nullptr, scale, nullptr, op0);
+  Raw first;
+  load_first<false>(first, L, Q + base, Q + base, r_begin, n_tiles, nullptr, 0, r_end);
+  make_operands(StateSource{nullptr, states + static_cast<size_t>(bh) * D * D}, scale, nullptr,
+                op0);
   __syncthreads();
   Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass(L, W, Q + base, O + base, r_begin, n_tiles, flags, r_begin, eps, Sop);
+  fwd_apply_pass(L, W, Q + base, O + base, r_begin, n_tiles, r_end, eps, first, Sop);
 }
 
 // blockIdx.y = 0: dQ of a block of rows;  blockIdx.y = 1: dK, dV of a block of rows.
@@ -614,32 +754,35 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(
   const int r_begin = split * rows_per_split;
   const int r_end = min(N, r_begin + rows_per_split);
   const int n_tiles = (r_end - r_begin + TR - 1) / TR;
-  uint8_t* flags = smem + kMaskOffset;
   lds_bf16* op0 = reinterpret_cast<lds_bf16*>(smem + kOp0Offset);
   lds_bf16* op1 = reinterpret_cast<lds_bf16*>(smem + kOp1Offset);
+  Raw first;
   if (blockIdx.y == 0) {
-    fill_flags(flags, nullptr, r_begin, n_tiles * TR, r_end);
-    make_operands(states + static_cast<size_t>(bh) * D * D, nullptr, scale, op0, nullptr);
+    load_first<true>(first, L, Q + base, dO + base, r_begin, n_tiles, nullptr, 0, r_end);
+    make_operands(StateSource{nullptr, states + static_cast<size_t>(bh) * D * D}, scale, op0,
+                  nullptr);
     __syncthreads();
-    Operand Sop;
-    Sop.load(op0, L);
     f32x16_t unused[2][2];
-    bwd_q_pass<false>(L, W, Q + base, dO + base, dQ + base, r_begin, n_tiles, flags, r_begin, eps,
-                      Sop, unused);
+    bwd_q_pass<false>(L, W, Q + base, dO + base, dQ + base, r_begin, n_tiles, r_end, eps, first,
+                      op0, unused);
   } else {
-    fill_flags(flags, mask == nullptr ? nullptr : mask + static_cast<size_t>(bh / H) * N, r_begin,
-               n_tiles * TR, r_end);
-    make_operands(dstates + static_cast<size_t>(bh) * D * D, nullptr, scale, op0, op1);
+    uint8_t* flags = mask != nullptr ? smem + kMaskOffset : nullptr;
+    if (flags != nullptr)
+      fill_flags(flags, mask + static_cast<size_t>(bh / H) * N, r_begin, n_tiles * TR, r_end);
+    make_operands(StateSource{nullptr, dstates + static_cast<size_t>(bh) * D * D}, scale, op0,
+                  op1);
     __syncthreads();
+    load_first<true>(first, L, K + base, V + base, r_begin, n_tiles, flags, r_begin, r_end);
     Operand dS_v, dS_h;
     dS_v.load(op1, L);
     dS_h.load(op0, L);
     bwd_kv_pass(L, W, K + base, V + base, dK + base, dV + base, r_begin, n_tiles, flags, r_begin,
-                r_end, eps, dS_v, dS_h);
+                r_end, eps, first, dS_v, dS_h);
   }
 }
 
-// Dynamic LDS above 64 KB has to be granted per kernel (and per device) first.
+// Dynamic LDS above 64 KB has to be granted per kernel first; two workgroups share a
+// compute unit's 160 KB.
 constexpr int kMaxLdsBytes = 80 * 1024;
 template <typename Kern>
 hipError_t allow_lds(Kern kern, size_t bytes) {
@@ -664,7 +807,7 @@ hipError_t launch_mfma_bf16_fwd(const Problem& p, const Plan& plan) {
   const unsigned BH = static_cast<unsigned>(p.B) * p.H;
   hipError_t err;
   if (plan.path == Plan::kFused) {
-    const size_t lds = lds_bytes((p.N + TR - 1) / TR * TR, 2);
+    const size_t lds = lds_bytes((p.N + TR - 1) / TR * TR, 1);
     if ((err = allow_lds(fused_fwd_kernel, lds)) != hipSuccess) return err;
     hipLaunchKernelGGL(fused_fwd_kernel, dim3(BH), dim3(kThreads), lds, p.stream, Q, K, V, p.mask,
                        O, p.H, p.N, p.scale, p.eps);
@@ -694,7 +837,7 @@ hipError_t launch_mfma_bf16_bwd(const Problem& p, const Plan& plan) {
   const unsigned BH = static_cast<unsigned>(p.B) * p.H;
   hipError_t err;
   if (plan.path == Plan::kFused) {
-    const size_t lds = lds_bytes((p.N + TR - 1) / TR * TR, 2);
+    const size_t lds = lds_bytes((p.N + TR - 1) / TR * TR, 1);
     if ((err = allow_lds(fused_bwd_kernel, lds)) != hipSuccess) return err;
     hipLaunchKernelGGL(fused_bwd_kernel, dim3(BH), dim3(kThreads), lds, p.stream, Q, K, V, p.mask,
                        dO, dQ, dK, dV, p.H, p.N, p.scale, p.eps);
