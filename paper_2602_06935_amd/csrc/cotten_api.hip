@@ -99,7 +99,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   if (plan.path == cotten::Plan::kGeneric)
     err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
   else
-    err = bwd ? cotten::launch_mfma_bf16_bwd(p, plan) : cotten::launch_mfma_bf16_fwd(p, plan);
+    err = bwd ? cotten::launch_mfma_bwd(p, plan) : cotten::launch_mfma_fwd(p, plan);
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 

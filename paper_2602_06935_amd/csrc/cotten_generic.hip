@@ -355,7 +355,7 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
   const size_t nstates = is_bwd ? 2 : 1;
   Plan plan;
   long splits, rows;
-  if (mfma_bf16_supports(dtype, D)) {
+  if (mfma_supports(dtype, D)) {
     // One workgroup per slice while that fills the chip or the slice is short; otherwise
     // cut the sequence so that about 512 workgroups exist, in blocks of 64 rows.
     constexpr long kFusedMaxN = 2048, kBlock = 64;

@@ -50,9 +50,9 @@ const float* launch_reduce_states(const Problem& p, const Plan& plan, int nstate
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 
-// MFMA path, bf16 I/O with d_h = 64.
-bool mfma_bf16_supports(int dtype, int D);
-hipError_t launch_mfma_bf16_fwd(const Problem& p, const Plan& plan);
-hipError_t launch_mfma_bf16_bwd(const Problem& p, const Plan& plan);
+// MFMA path: bf16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows).
+bool mfma_supports(int dtype, int D);
+hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan);
+hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 
 }  // namespace cotten

@@ -1,0 +1,1018 @@
+// MFMA path of the cosine attention for 128-byte rows on gfx950:
+//     bf16 I/O with d_h = 64   and   fp32 I/O with d_h = 32.
+//
+// Work unit: one wavefront streams 16-row tiles of a slice.  A tile is loaded with
+// 128-bit accesses (8 lanes per 128-byte row, 8 rows per instruction) and parked in a
+// wave-private LDS tile, from which the matrix cores are fed:
+//   state products  S += Xhat^T Y  (contraction over rows; Xhat normalised in fp32 registers
+//                   before it is written to the tile)
+//                   bf16: 32x32x16 MFMA, operands fetched with the transposing LDS read
+//                   fp32: 32x32x2 MFMA, one LDS dword per lane and step
+//   apply products  T = X W        (contraction over columns; X raw, the 1/r of each row is
+//                   applied to the result; W held in registers)
+//                   bf16: 16x16x32 MFMA      fp32: 16x16x4 MFMA
+// Products come back through a wave-private fp32 scratch tile into the load layout,
+// where the epilogue (projection off the normalised row, 1/r, masking) runs in fp32
+// next to the unrounded inputs and results leave with 128-bit stores.
+//
+// Fused kernels (one workgroup = 4 waves per slice) run all phases in one launch;
+// split kernels cut long sequences over several workgroups per slice and pass
+// partial states through the workspace.
+#include "cotten_device.h"
+#include "cotten_launch.h"
+
+// Optional phase timestamps for tuning builds (-DCOTTEN_TRACE): wave w of workgroup b < 8
+// stores the shader clock at trace point i.  Compiles to nothing otherwise.
+#ifdef COTTEN_TRACE
+__device__ long long cotten_trace_buf[8 * 4 * 16];
+#define COTTEN_TRACE_POINT(i)                                                        \
+  do {                                                                               \
+    if (blockIdx.x < 8 && blockIdx.y == 0 && (threadIdx.x & 63) == 0)                \
+      cotten_trace_buf[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
+  } while (0)
+extern "C" int cotten_trace_read(long long* host, int n) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(cotten_trace_buf), n * sizeof(long long)));
+}
+#else
+#define COTTEN_TRACE_POINT(i) do {} while (0)
+#endif
+
+namespace cotten {
+namespace {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int TR = 16;               // rows per wave tile
+constexpr int kRowBytes = 128;       // one row of Q, K, V ... in global memory
+constexpr int kTileStride = 144;     // bytes per row of an LDS tile (128 + 16 of padding)
+constexpr int kTileBytes = TR * kTileStride;
+
+// Sum over the 8 consecutive lanes that share one row, by lane-permuting adds (no LDS).
+__device__ __forceinline__ float row_sum8(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // other quad of the 8
+  return x;
+}
+
+// 1/sqrt(ss + eps) for a live row (hardware reciprocal square root, about 1 ulp), 0 otherwise.
+__device__ __forceinline__ float inv_norm_or_zero(float ss, float eps, bool live) {
+  return live ? __builtin_amdgcn_rsqf(ss + eps) : 0.0f;
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2_t v;
+  v[0] = static_cast<__bf16>(lo);
+  v[1] = static_cast<__bf16>(hi);
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ f32x4_t quad(const f32x16_t& a, int j) {
+  return f32x4_t{a[4 * j], a[4 * j + 1], a[4 * j + 2], a[4 * j + 3]};
+}
+
+// Lane geometry shared by every pass.
+struct Lane {
+  int lane, wave;
+  int r8, ch;    // load layout: tile rows r8 and r8+8, bytes 16*ch .. 16*ch+15 of the row
+  int i16, g16;  // MFMA 16-lane groups: lane%16, lane/16
+  __device__ __forceinline__ Lane() {
+    lane = threadIdx.x & 63;
+    wave = threadIdx.x >> 6;
+    r8 = lane >> 3;
+    ch = lane & 7;
+    i16 = lane & 15;
+    g16 = lane >> 4;
+  }
+};
+
+// ---- the two element formats ----------------------------------------------------------
+//
+// Common vocabulary of a format F:
+//   F::D                  head dimension;  F::EPL = D/8 elements per lane in the load layout
+//   F::unpack / F::pack   128-bit register group <-> EPL floats
+//   F::Acc                accumulators of one D x D state per wave, with mfma() and the
+//                         column-major image R[n*(D+4)+m] used for the cross-wave sum
+//   F::Operand            a D x D matrix W held in registers for apply products, loaded from
+//                         an LDS image op[n][k] (k contiguous); F::apply(tile, W, out)
+//   F::write_image        builds such images from a reduced state
+
+struct Bf16x64 {
+  typedef bf16 io_t;
+  static constexpr int D = 64, EPL = 8, NT = 4;
+  static constexpr int kImageStride = 72;                 // elements per image row
+  static constexpr int kImageBytes = D * kImageStride * 2;
+
+  static __device__ __forceinline__ void unpack(const u32x4_t r, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(r[i] << 16);
+      f[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ u32x4_t pack(const float (&f)[8]) {
+    u32x4_t r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    return r;
+  }
+
+  // Operand of the 32x32x16 MFMA for a contraction over the 16 tile rows: lane gets, for
+  // column cbase + lane%32, the 8 rows 8*(lane/32) .. +7 (two transposing reads of 4 rows).
+  static __device__ __forceinline__ bf16x8_t rows_operand(const unsigned char* T, const Lane& L,
+                                                          int cbase) {
+    const int s = L.i16;
+    const int row = 8 * (L.g16 >> 1) + (s >> 2);
+    const int col = cbase + 16 * (L.g16 & 1) + 4 * (s & 3);
+    typedef bf16x4_t __attribute__((address_space(3))) * lds_v4;
+    const unsigned char* p = T + row * kTileStride + col * 2;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p));
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p + 4 * kTileStride));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+
+  struct Acc {
+    f32x16_t v[2][2];  // [row block of 32][column block of 32]
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[a][c][i] = 0.0f;
+    }
+    // += (X tile)^T (Y tile)
+    __device__ __forceinline__ void mfma(const unsigned char* Xt, const unsigned char* Yt,
+                                         const Lane& L) {
+      bf16x8_t a[2], b[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        a[t] = rows_operand(Xt, L, 32 * t);
+        b[t] = rows_operand(Yt, L, 32 * t);
+      }
+#pragma unroll
+      for (int at = 0; at < 2; ++at)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+          v[at][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[at], b[ct], v[at][ct], 0, 0, 0);
+    }
+    // group g = 0..15 of four consecutive state rows held by this lane, and where it lives
+    __device__ __forceinline__ f32x4_t group(int g) const { return quad(v[g >> 3][(g >> 2) & 1], g & 3); }
+    static __device__ __forceinline__ int group_row(int g, const Lane& L) {
+      return 32 * (g >> 3) + 8 * (g & 3) + 4 * (L.lane >> 5);
+    }
+    static __device__ __forceinline__ int group_col(int g, const Lane& L) {
+      return 32 * ((g >> 2) & 1) + (L.lane & 31);
+    }
+    static constexpr int kGroups = 16;
+  };
+
+  struct Operand {
+    bf16x8_t frag[4][2];
+    __device__ __forceinline__ void load(const unsigned char* image, const Lane& L) {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          frag[nt][ks] = *reinterpret_cast<const bf16x8_t*>(
+              image + ((16 * nt + L.i16) * kImageStride + 8 * L.g16 + 32 * ks) * 2);
+    }
+  };
+
+  // out[nt] (16 rows x 16 columns, fp32) = (tile rows) x W
+  static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
+                                               const Lane& L, f32x4_t (&out)[4]) {
+    bf16x8_t a[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      a[ks] = *reinterpret_cast<const bf16x8_t*>(T + L.i16 * kTileStride + (8 * L.g16 + 32 * ks) * 2);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], W.frag[nt][ks], out[nt], 0, 0, 0);
+    }
+  }
+
+  // two neighbouring image elements (k, k+1) of image row n
+  static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
+                                                          float v0, float v1) {
+    *reinterpret_cast<uint32_t*>(image + (n * kImageStride + k) * 2) = pack_bf16(v0, v1);
+  }
+};
+
+struct F32x32 {
+  typedef float io_t;
+  static constexpr int D = 32, EPL = 4, NT = 2;
+  static constexpr int kImageStride = 36;
+  static constexpr int kImageBytes = D * kImageStride * 4;
+
+  static __device__ __forceinline__ void unpack(const u32x4_t r, float (&f)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(r[i]);
+  }
+  static __device__ __forceinline__ u32x4_t pack(const float (&f)[4]) {
+    u32x4_t r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
+    return r;
+  }
+
+  struct Acc {
+    f32x16_t v;
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = 0.0f;
+    }
+    // += (X tile)^T (Y tile): 32x32x2 steps, lane = column, half-wave = row of the pair
+    __device__ __forceinline__ void mfma(const unsigned char* Xt, const unsigned char* Yt,
+                                         const Lane& L) {
+      const int off = (L.lane >> 5) * kTileStride + (L.lane & 31) * 4;
+      float a[8], b[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        a[s] = *reinterpret_cast<const float*>(Xt + off + 2 * s * kTileStride);
+        b[s] = *reinterpret_cast<const float*>(Yt + off + 2 * s * kTileStride);
+      }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) v = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s], v, 0, 0, 0);
+    }
+    __device__ __forceinline__ f32x4_t group(int g) const { return quad(v, g); }
+    static __device__ __forceinline__ int group_row(int g, const Lane& L) {
+      return 8 * g + 4 * (L.lane >> 5);
+    }
+    static __device__ __forceinline__ int group_col(int, const Lane& L) { return L.lane & 31; }
+    static constexpr int kGroups = 4;
+  };
+
+  // frag[nt][s] = W[8*(lane/16) + s][16*nt + lane%16]
+  struct Operand {
+    float frag[2][8];
+    __device__ __forceinline__ void load(const unsigned char* image, const Lane& L) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const f32x4_t* p = reinterpret_cast<const f32x4_t*>(
+            image + ((16 * nt + L.i16) * kImageStride + 8 * L.g16) * 4);
+        const f32x4_t lo = p[0], hi = p[1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          frag[nt][i] = lo[i];
+          frag[nt][4 + i] = hi[i];
+        }
+      }
+    }
+  };
+
+  static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
+                                               const Lane& L, f32x4_t (&out)[2]) {
+    const f32x4_t* p = reinterpret_cast<const f32x4_t*>(T + L.i16 * kTileStride + 8 * L.g16 * 4);
+    const f32x4_t lo = p[0], hi = p[1];
+    float a[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = lo[i];
+      a[4 + i] = hi[i];
+    }
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], W.frag[nt][s], out[nt], 0, 0, 0);
+    }
+  }
+
+  static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
+                                                          float v0, float v1) {
+    float* p = reinterpret_cast<float*>(image + (n * kImageStride + k) * 4);
+    p[0] = v0;
+    p[1] = v1;
+  }
+};
+
+// ---- LDS map ----------------------------------------------------------------------------
+// [working set of the 4 waves | (aliased) two reduction buffers][image 0][image 1][flags]
+
+template <class F>
+struct Layout {
+  static constexpr int D = F::D;
+  static constexpr int kScratchStride = D + 4;                        // floats
+  static constexpr int kScratchBytes = TR * kScratchStride * 4;
+  static constexpr int kWaveBytes = 2 * kTileBytes + 2 * kScratchBytes;
+  static constexpr int kRStride = D + 4;                              // floats, column-major
+  static constexpr int kRFloats = D * kRStride;
+  static constexpr int kWorkBytes =
+      kWaves * kWaveBytes > 2 * kRFloats * 4 ? kWaves * kWaveBytes : 2 * kRFloats * 4;
+  static constexpr int kImage0 = kWorkBytes;
+  static constexpr int kImage1 = kImage0 + F::kImageBytes;
+  static constexpr int kFlags = kImage1 + F::kImageBytes;
+};
+
+template <class F>
+struct WaveLds {
+  unsigned char* Xt;
+  unsigned char* Yt;
+  float* Sc0;
+  float* Sc1;
+  __device__ __forceinline__ WaveLds(unsigned char* smem, int wave) {
+    unsigned char* base = smem + wave * Layout<F>::kWaveBytes;
+    Xt = base;
+    Yt = base + kTileBytes;
+    Sc0 = reinterpret_cast<float*>(base + 2 * kTileBytes);
+    Sc1 = reinterpret_cast<float*>(base + 2 * kTileBytes + Layout<F>::kScratchBytes);
+  }
+};
+
+// ---- tiles --------------------------------------------------------------------------------
+
+// Raw 16-row tile in the load layout: x[h], y[h] hold row r8 + 8h; `live` bit h says the
+// row takes part (in range and, where a mask applies, a valid key).
+struct Raw {
+  u32x4_t x[2], y[2];
+  int live;
+};
+
+// Loads tile rows row0 .. row0+15.  A row takes part when it is below `row_limit` and, if
+// `flags` is given, flags[row - m_base] != 0 (LDS copy of the key mask).  USE_Y: second tensor.
+template <bool USE_Y>
+__device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const unsigned char* __restrict__ X,
+                                         const unsigned char* __restrict__ Y, int row0,
+                                         const uint8_t* flags, int m_base, int row_limit) {
+  r.live = 0;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int row = row0 + L.r8 + 8 * h;
+    bool live = row < row_limit;
+    if (flags != nullptr) live = flags[row - m_base] != 0;
+    r.x[h] = u32x4_t{0, 0, 0, 0};
+    r.y[h] = u32x4_t{0, 0, 0, 0};
+    if (live) {
+      const size_t off = static_cast<size_t>(row) * kRowBytes + L.ch * 16;
+      r.x[h] = *reinterpret_cast<const u32x4_t*>(X + off);
+      if (USE_Y) r.y[h] = *reinterpret_cast<const u32x4_t*>(Y + off);
+      r.live |= 1 << h;
+    }
+  }
+}
+
+// What becomes of the x rows on their way to the LDS tile.
+enum XMode { kXNone = 0, kXRaw = 1, kXNormalized = 2 };
+
+// inv[h] = 1/r of row h (0 for rows that do not take part; their registers are zero).
+// Xt receives nothing, the raw rows, or xhat; Yt the raw y rows.
+template <class F, int XMODE, bool USE_Y>
+__device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, unsigned char* Xt,
+                                      unsigned char* Yt, float (&inv)[2]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float f[F::EPL];
+    F::unpack(r.x[h], f);
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < F::EPL; ++i) ss += f[i] * f[i];
+    inv[h] = inv_norm_or_zero(row_sum8(ss), eps, (r.live >> h) & 1);
+    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+    if (XMODE == kXNormalized) {
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) f[i] *= inv[h];
+      *reinterpret_cast<u32x4_t*>(Xt + off) = F::pack(f);
+    } else if (XMODE == kXRaw) {
+      *reinterpret_cast<u32x4_t*>(Xt + off) = r.x[h];
+    }
+    if (USE_Y) *reinterpret_cast<u32x4_t*>(Yt + off) = r.y[h];
+  }
+}
+
+// MFMA result layout -> scratch tile (row 4*(lane/16)+v, column 16*nt + lane%16)
+template <class F>
+__device__ __forceinline__ void to_scratch(const f32x4_t (&out)[F::NT], float* Sc, const Lane& L) {
+#pragma unroll
+  for (int nt = 0; nt < F::NT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      Sc[(4 * L.g16 + v) * Layout<F>::kScratchStride + 16 * nt + L.i16] = out[nt][v];
+}
+
+// scratch tile -> load layout: the EPL columns of row r8 + 8h this lane owns
+template <class F>
+__device__ __forceinline__ void from_scratch(const float* Sc, const Lane& L, int h,
+                                             float (&f)[F::EPL]) {
+  const f32x4_t* p = reinterpret_cast<const f32x4_t*>(
+      Sc + (L.r8 + 8 * h) * Layout<F>::kScratchStride + F::EPL * L.ch);
+#pragma unroll
+  for (int q = 0; q < F::EPL / 4; ++q) {
+    const f32x4_t a = p[q];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[4 * q + i] = a[i];
+  }
+}
+
+template <class F>
+__device__ __forceinline__ void store_row(unsigned char* __restrict__ dst, int row, const Lane& L,
+                                          const float (&f)[F::EPL]) {
+  *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 16 * L.ch) = F::pack(f);
+}
+
+// Copies the key mask of rows [m_base, m_base + count) into LDS as "takes part" flags.
+__device__ __forceinline__ void fill_flags(uint8_t* flags, const uint8_t* __restrict__ mask,
+                                           int m_base, int count, int row_limit) {
+  for (int i = threadIdx.x; i < count; i += kThreads) {
+    const int row = m_base + i;
+    uint8_t f = 0;
+    if (row < row_limit) f = mask[row] != 0;
+    flags[i] = f;
+  }
+}
+
+// First tile of this wave (tile index = wave), issued early by the caller.
+template <bool USE_Y>
+__device__ __forceinline__ void load_first(Raw& a, const Lane& L, const unsigned char* __restrict__ X,
+                                           const unsigned char* __restrict__ Y, int row_begin,
+                                           int n_tiles, const uint8_t* flags, int m_base,
+                                           int row_limit) {
+  a.live = 0;
+  if (L.wave < n_tiles)
+    load_raw<USE_Y>(a, L, X, Y, row_begin + L.wave * TR, flags, m_base, row_limit);
+}
+
+// Walks the tiles wave, wave+kWaves, ... < n_tiles owned by this wave with the next tile's
+// global loads in flight while the current one is processed.  `a` holds the first tile.
+template <bool USE_Y, typename Body>
+__device__ __forceinline__ void for_each_tile(const Lane& L, const unsigned char* __restrict__ X,
+                                              const unsigned char* __restrict__ Y, int row_begin,
+                                              int n_tiles, const uint8_t* flags, int m_base,
+                                              int row_limit, Raw& a, Body&& body) {
+  int t = L.wave;
+  if (t >= n_tiles) return;
+  Raw b;
+  while (true) {
+    bool more = t + kWaves < n_tiles;
+    if (more) load_raw<USE_Y>(b, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
+    body(a, row_begin + t * TR);
+    if (!more) break;
+    t += kWaves;
+    more = t + kWaves < n_tiles;
+    if (more) load_raw<USE_Y>(a, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
+    body(b, row_begin + t * TR);
+    if (!more) break;
+    t += kWaves;
+  }
+}
+
+// ---- passes -------------------------------------------------------------------------------
+// Every pass takes the wave's first tile already loaded in `first`.
+
+// Range of rows a pass walks, with the optional LDS flags of the key mask.
+struct Rows {
+  int begin, n_tiles, limit;   // rows [begin, limit), in n_tiles tiles of 16
+  const uint8_t* flags;        // flags[row - begin], or nullptr: every row below limit
+};
+
+// acc += sum over live rows of xhat^T y
+template <class F>
+__device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
+                                           const unsigned char* __restrict__ X,
+                                           const unsigned char* __restrict__ Y, const Rows rows,
+                                           float eps, Raw& first, typename F::Acc& acc) {
+  for_each_tile<true>(L, X, Y, rows.begin, rows.n_tiles, rows.flags, rows.begin, rows.limit, first,
+                      [&](const Raw& r, int) {
+    if (__ballot(r.live != 0) == 0) return;  // no live row in this tile (uniform)
+    float inv[2];
+    stage<F, kXNormalized, true>(r, L, eps, W.Xt, W.Yt, inv);
+    wave_lds_fence();
+    acc.mfma(W.Xt, W.Yt, L);
+    wave_lds_fence();
+  });
+}
+
+// O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
+template <class F>
+__device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
+                                               const unsigned char* __restrict__ Q,
+                                               unsigned char* __restrict__ O, const Rows rows,
+                                               float eps, Raw& first,
+                                               const typename F::Operand& Sop) {
+  for_each_tile<false>(L, Q, Q, rows.begin, rows.n_tiles, nullptr, 0, rows.limit, first,
+                       [&](const Raw& r, int row0) {
+    float inv[2];
+    stage<F, kXRaw, false>(r, L, eps, W.Xt, W.Yt, inv);
+    wave_lds_fence();
+    f32x4_t out[F::NT];
+    F::apply(W.Xt, Sop, L, out);
+    to_scratch<F>(out, W.Sc0, L);
+    wave_lds_fence();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float o[F::EPL];
+      from_scratch<F>(W.Sc0, L, h, o);
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) o[i] *= inv[h];
+      if ((r.live >> h) & 1) store_row<F>(O, row0 + L.r8 + 8 * h, L, o);
+    }
+    wave_lds_fence();
+  });
+}
+
+// dQ rows from (Q, dO) and W = scale * S (image op[a][c]); with ACCUM also dsacc += qhat^T dO.
+template <class F, bool ACCUM>
+__device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
+                                           const unsigned char* __restrict__ Q,
+                                           const unsigned char* __restrict__ dO,
+                                           unsigned char* __restrict__ dQ, const Rows rows,
+                                           float eps, Raw& first, const unsigned char* Simage,
+                                           typename F::Acc& dsacc) {
+  // With the state accumulators live, a large operand is re-read from LDS for every tile;
+  // otherwise it stays in registers.
+  constexpr bool kHold = !ACCUM || sizeof(typename F::Operand) <= 16 * 4;
+  typename F::Operand held;
+  if (kHold) held.load(Simage, L);
+  for_each_tile<true>(L, Q, dO, rows.begin, rows.n_tiles, nullptr, 0, rows.limit, first,
+                      [&](const Raw& r, int row0) {
+    float inv[2];
+    stage<F, ACCUM ? kXNormalized : kXNone, true>(r, L, eps, W.Xt, W.Yt, inv);
+    wave_lds_fence();
+    if (ACCUM) dsacc.mfma(W.Xt, W.Yt, L);
+    f32x4_t out[F::NT];
+    if (kHold) {
+      F::apply(W.Yt, held, L, out);  // g = scale * dO S^T
+    } else {
+      typename F::Operand fresh;
+      fresh.load(Simage, L);
+      F::apply(W.Yt, fresh, L, out);
+    }
+    to_scratch<F>(out, W.Sc0, L);
+    wave_lds_fence();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float g[F::EPL], q[F::EPL];
+      from_scratch<F>(W.Sc0, L, h, g);
+      F::unpack(r.x[h], q);
+      float proj = 0.0f;
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) {
+        q[i] *= inv[h];
+        proj += q[i] * g[i];
+      }
+      proj = row_sum8(proj);
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) g[i] = (g[i] - q[i] * proj) * inv[h];
+      if ((r.live >> h) & 1) store_row<F>(dQ, row0 + L.r8 + 8 * h, L, g);
+    }
+    wave_lds_fence();
+  });
+}
+
+// dK, dV rows from (K, V) and scale * dS: dV = (k dS)/r (image op[c][a]),
+// h = v dS^T (image op[a][c]).  Rows below the limit that are masked get zeros.
+template <class F>
+__device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
+                                            const unsigned char* __restrict__ K,
+                                            const unsigned char* __restrict__ V,
+                                            unsigned char* __restrict__ dK,
+                                            unsigned char* __restrict__ dV, const Rows rows,
+                                            float eps, Raw& first,
+                                            const typename F::Operand& dSop_v,
+                                            const typename F::Operand& dSop_h) {
+  for_each_tile<true>(L, K, V, rows.begin, rows.n_tiles, rows.flags, rows.begin, rows.limit, first,
+                      [&](const Raw& r, int row0) {
+    if (__ballot(r.live != 0) == 0) {  // nothing live: only the zero rows are due
+      float zeros[F::EPL];
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) zeros[i] = 0.0f;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int row = row0 + L.r8 + 8 * h;
+        if (row < rows.limit) {
+          store_row<F>(dK, row, L, zeros);
+          store_row<F>(dV, row, L, zeros);
+        }
+      }
+      return;
+    }
+    float inv[2];
+    stage<F, kXRaw, true>(r, L, eps, W.Xt, W.Yt, inv);
+    wave_lds_fence();
+    f32x4_t out[F::NT];
+    F::apply(W.Xt, dSop_v, L, out);
+    to_scratch<F>(out, W.Sc0, L);
+    F::apply(W.Yt, dSop_h, L, out);
+    to_scratch<F>(out, W.Sc1, L);
+    wave_lds_fence();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int row = row0 + L.r8 + 8 * h;
+      float gv[F::EPL], hh[F::EPL], k[F::EPL];
+      from_scratch<F>(W.Sc0, L, h, gv);
+      from_scratch<F>(W.Sc1, L, h, hh);
+      F::unpack(r.x[h], k);
+      float proj = 0.0f;
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) {
+        k[i] *= inv[h];  // inv = 0 on masked rows: khat, dK and dV come out as exact zeros
+        proj += k[i] * hh[i];
+      }
+      proj = row_sum8(proj);
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) {
+        hh[i] = (hh[i] - k[i] * proj) * inv[h];
+        gv[i] *= inv[h];
+      }
+      if (row < rows.limit) {
+        store_row<F>(dK, row, L, hh);
+        store_row<F>(dV, row, L, gv);
+      }
+    }
+    wave_lds_fence();
+  });
+}
+
+// ---- workgroup-level state handling ---------------------------------------------------------
+
+// Sums the four per-wave accumulators in the fixed order (w0 + w1) + (w2 + w3): afterwards
+// R0 + R1 (two fp32 images at the start of LDS, column-major with padded stride, so that the
+// 4 consecutive state rows a register group holds move as one 128-bit access) is the total.
+template <class F>
+__device__ __forceinline__ void wg_reduce(const Lane& L, unsigned char* smem,
+                                          const typename F::Acc& acc) {
+  typedef typename F::Acc Acc;
+  float* R = reinterpret_cast<float*>(smem) + (L.wave >> 1) * Layout<F>::kRFloats;
+  f32x4_t* dst[Acc::kGroups];
+#pragma unroll
+  for (int g = 0; g < Acc::kGroups; ++g)
+    dst[g] = reinterpret_cast<f32x4_t*>(R + Acc::group_col(g, L) * Layout<F>::kRStride +
+                                        Acc::group_row(g, L));
+  __syncthreads();  // working set no longer in use
+  if ((L.wave & 1) == 0) {
+#pragma unroll
+    for (int g = 0; g < Acc::kGroups; ++g) *dst[g] = acc.group(g);
+  }
+  __syncthreads();
+  if ((L.wave & 1) == 1) {
+    f32x4_t other[Acc::kGroups];  // all reads first, so that they overlap
+#pragma unroll
+    for (int g = 0; g < Acc::kGroups; ++g) other[g] = *dst[g];
+#pragma unroll
+    for (int g = 0; g < Acc::kGroups; ++g) *dst[g] = other[g] + acc.group(g);
+  }
+  __syncthreads();
+}
+
+// Element (m, n) of the reduced state: from LDS (R0 + R1) or from a row-major global array.
+template <class F>
+struct StateSource {
+  const float* lds;     // R0 (R1 follows) or nullptr
+  const float* global;  // row-major D x D or nullptr
+  __device__ __forceinline__ float at(int m, int n) const {
+    if (lds != nullptr)
+      return lds[n * Layout<F>::kRStride + m] + lds[Layout<F>::kRFloats + n * Layout<F>::kRStride + m];
+    return global[m * F::D + n];
+  }
+};
+
+// Builds operand images of scale * M for the apply products:
+//   natural    op[m][n] = M[m][n]   (products contracting over n)
+//   transposed op[n][m] = M[m][n]   (products contracting over m)
+template <class F>
+__device__ __forceinline__ void make_operands(const StateSource<F> src, float scale,
+                                              unsigned char* natural, unsigned char* transposed) {
+  constexpr int D = F::D;
+  constexpr int kPer = D * D / 2 / kThreads;  // element pairs per thread
+  if (natural != nullptr) {
+    float lo[kPer], hi[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, m = e / (D / 2), n = (e % (D / 2)) * 2;
+      lo[i] = src.at(m, n);
+      hi[i] = src.at(m, n + 1);
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, m = e / (D / 2), n = (e % (D / 2)) * 2;
+      F::write_image_pair(natural, m, n, lo[i] * scale, hi[i] * scale);
+    }
+  }
+  if (transposed != nullptr) {
+    float lo[kPer], hi[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, n = e % D, m = (e / D) * 2;
+      lo[i] = src.at(m, n);
+      hi[i] = src.at(m + 1, n);
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = threadIdx.x + i * kThreads, n = e % D, m = (e / D) * 2;
+      F::write_image_pair(transposed, n, m, lo[i] * scale, hi[i] * scale);
+    }
+  }
+}
+
+// ---- kernels ----------------------------------------------------------------------------------
+
+extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+// Arguments common to all kernels of this file (passed by value).
+struct Args {
+  const unsigned char* Q;
+  const unsigned char* K;
+  const unsigned char* V;
+  const unsigned char* dO;
+  const uint8_t* mask;
+  unsigned char* O;
+  unsigned char* dQ;
+  unsigned char* dK;
+  unsigned char* dV;
+  float* ws;                 // partial states (split path)
+  const float* states;       // reduced S (split path)
+  const float* dstates;      // reduced dS (split path)
+  size_t second_offset;      // where the dS partials start in ws
+  int H, N, splits, rows_per_split;
+  float scale, eps;
+};
+
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int bh = blockIdx.x, N = a.N;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const int n_tiles = (N + TR - 1) / TR;
+  uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
+  unsigned char* op0 = smem + Layout<F>::kImage0;
+  const Rows keys{0, n_tiles, N, kflags}, all{0, n_tiles, N, nullptr};
+
+  Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
+  load_first<false>(qfirst, L, a.Q + base, a.Q + base, 0, n_tiles, nullptr, 0, N);
+  if (kflags != nullptr) {
+    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, 0, n_tiles * TR, N);
+    __syncthreads();
+  }
+  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+
+  typename F::Acc acc;
+  acc.zero();
+  state_pass<F>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  wg_reduce<F>(L, smem, acc);
+  // O = qhat S: contraction over rows of S
+  make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), nullptr}, a.scale, nullptr,
+                   op0);
+  __syncthreads();
+  typename F::Operand Sop;
+  Sop.load(op0, L);
+  fwd_apply_pass<F>(L, W, a.Q + base, a.O + base, all, a.eps, qfirst, Sop);
+}
+
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int bh = blockIdx.x, N = a.N;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const int n_tiles = (N + TR - 1) / TR;
+  uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
+  unsigned char* op0 = smem + Layout<F>::kImage0;
+  unsigned char* op1 = smem + Layout<F>::kImage1;
+  const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
+  const Rows keys{0, n_tiles, N, kflags}, all{0, n_tiles, N, nullptr};
+
+  COTTEN_TRACE_POINT(0);
+  Raw qfirst, kfirst;
+  load_first<true>(qfirst, L, a.Q + base, a.dO + base, 0, n_tiles, nullptr, 0, N);
+  if (kflags != nullptr) {
+    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, 0, n_tiles * TR, N);
+    __syncthreads();
+  }
+  COTTEN_TRACE_POINT(1);
+  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+
+  typename F::Acc acc;
+  acc.zero();
+  state_pass<F>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  COTTEN_TRACE_POINT(2);
+  wg_reduce<F>(L, smem, acc);
+  COTTEN_TRACE_POINT(3);
+  make_operands<F>(reduced, a.scale, op0, nullptr);  // g = dO S^T: contraction over columns of S
+  __syncthreads();
+  acc.zero();
+  COTTEN_TRACE_POINT(4);
+  bwd_q_pass<F, true>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, qfirst, op0, acc);
+  COTTEN_TRACE_POINT(5);
+  // the key/value tiles are walked again: get the first one moving before the reduction
+  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+  wg_reduce<F>(L, smem, acc);
+  COTTEN_TRACE_POINT(6);
+  make_operands<F>(reduced, a.scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
+  __syncthreads();
+  typename F::Operand dS_v, dS_h;
+  dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
+  dS_h.load(op0, L);  // h = v dS^T: contraction over columns of dS
+  COTTEN_TRACE_POINT(7);
+  bwd_kv_pass<F>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps, kfirst, dS_v,
+                 dS_h);
+  COTTEN_TRACE_POINT(8);
+}
+
+// Split path, step 1: partial states of a block of rows.  blockIdx.y = 0: (K,V) under
+// the key mask -> partial S;  blockIdx.y = 1: (Q,dO) -> partial dS.
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) {
+  constexpr int D = F::D;
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
+  const bool second = blockIdx.y == 1;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const int r_begin = split * a.rows_per_split;
+  const int r_end = min(N, r_begin + a.rows_per_split);
+  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
+  const bool masked = !second && a.mask != nullptr;
+  uint8_t* flags = masked ? smem + Layout<F>::kFlags : nullptr;
+  const unsigned char* X = (second ? a.Q : a.K) + base;
+  const unsigned char* Y = (second ? a.dO : a.V) + base;
+  if (masked) {
+    fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, r_begin, n_tiles * TR, r_end);
+    __syncthreads();
+  }
+  const Rows rows{r_begin, n_tiles, r_end, flags};
+  Raw first;
+  load_first<true>(first, L, X, Y, r_begin, n_tiles, flags, r_begin, r_end);
+  typename F::Acc acc;
+  acc.zero();
+  state_pass<F>(L, W, X, Y, rows, a.eps, first, acc);
+  wg_reduce<F>(L, smem, acc);
+  const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
+  float* out = a.ws + (second ? a.second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
+  for (int e = threadIdx.x; e < D * D; e += kThreads) out[e] = reduced.at(e / D, e % D);
+}
+
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args a) {
+  constexpr int D = F::D;
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const int r_begin = split * a.rows_per_split;
+  const int r_end = min(N, r_begin + a.rows_per_split);
+  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
+  unsigned char* op0 = smem + Layout<F>::kImage0;
+  const Rows all{r_begin, n_tiles, r_end, nullptr};
+  Raw first;
+  load_first<false>(first, L, a.Q + base, a.Q + base, r_begin, n_tiles, nullptr, 0, r_end);
+  make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
+                   nullptr, op0);
+  __syncthreads();
+  typename F::Operand Sop;
+  Sop.load(op0, L);
+  fwd_apply_pass<F>(L, W, a.Q + base, a.O + base, all, a.eps, first, Sop);
+}
+
+// blockIdx.y = 0: dQ of a block of rows;  blockIdx.y = 1: dK, dV of a block of rows.
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(const Args a) {
+  constexpr int D = F::D;
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const int r_begin = split * a.rows_per_split;
+  const int r_end = min(N, r_begin + a.rows_per_split);
+  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
+  unsigned char* op0 = smem + Layout<F>::kImage0;
+  unsigned char* op1 = smem + Layout<F>::kImage1;
+  Raw first;
+  if (blockIdx.y == 0) {
+    const Rows all{r_begin, n_tiles, r_end, nullptr};
+    load_first<true>(first, L, a.Q + base, a.dO + base, r_begin, n_tiles, nullptr, 0, r_end);
+    make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
+                     op0, nullptr);
+    __syncthreads();
+    typename F::Acc unused;
+    bwd_q_pass<F, false>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, first, op0,
+                         unused);
+  } else {
+    uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
+    if (flags != nullptr)
+      fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, r_begin, n_tiles * TR, r_end);
+    make_operands<F>(StateSource<F>{nullptr, a.dstates + static_cast<size_t>(bh) * D * D}, a.scale,
+                     op0, op1);
+    __syncthreads();
+    const Rows keys{r_begin, n_tiles, r_end, flags};
+    load_first<true>(first, L, a.K + base, a.V + base, r_begin, n_tiles, flags, r_begin, r_end);
+    typename F::Operand dS_v, dS_h;
+    dS_v.load(op1, L);
+    dS_h.load(op0, L);
+    bwd_kv_pass<F>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps, first,
+                   dS_v, dS_h);
+  }
+}
+
+// ---- host side ----------------------------------------------------------------------------------
+
+// Dynamic LDS above 64 KB has to be granted per kernel first; two workgroups share a
+// compute unit's 160 KB.
+constexpr int kMaxLdsBytes = 80 * 1024;
+template <typename Kern>
+hipError_t allow_lds(Kern kern, size_t bytes) {
+  if (bytes > static_cast<size_t>(kMaxLdsBytes)) return hipErrorInvalidValue;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+}
+
+template <class F>
+size_t lds_bytes(int flag_rows) {
+  return static_cast<size_t>(Layout<F>::kFlags) + static_cast<size_t>(flag_rows) + 16;
+}
+
+Args make_args(const Problem& p, const Plan& plan) {
+  Args a{};
+  a.Q = static_cast<const unsigned char*>(p.Q);
+  a.K = static_cast<const unsigned char*>(p.K);
+  a.V = static_cast<const unsigned char*>(p.V);
+  a.dO = static_cast<const unsigned char*>(p.dO);
+  a.mask = p.mask;
+  a.O = static_cast<unsigned char*>(p.O);
+  a.dQ = static_cast<unsigned char*>(p.dQ);
+  a.dK = static_cast<unsigned char*>(p.dK);
+  a.dV = static_cast<unsigned char*>(p.dV);
+  a.ws = p.workspace;
+  a.H = p.H;
+  a.N = p.N;
+  a.splits = plan.splits;
+  a.rows_per_split = plan.rows_per_split;
+  a.scale = p.scale;
+  a.eps = p.eps;
+  return a;
+}
+
+template <class F>
+hipError_t run_fwd(const Problem& p, const Plan& plan) {
+  Args a = make_args(p, plan);
+  const unsigned BH = static_cast<unsigned>(p.B) * p.H;
+  hipError_t err;
+  if (plan.path == Plan::kFused) {
+    const size_t lds = lds_bytes<F>((p.N + TR - 1) / TR * TR);
+    if ((err = allow_lds(fused_fwd_kernel<F>, lds)) != hipSuccess) return err;
+    hipLaunchKernelGGL(fused_fwd_kernel<F>, dim3(BH), dim3(kThreads), lds, p.stream, a);
+    return hipGetLastError();
+  }
+  const size_t lds = lds_bytes<F>(plan.rows_per_split);
+  if ((err = allow_lds(split_state_kernel<F>, lds)) != hipSuccess) return err;
+  if ((err = allow_lds(split_apply_fwd_kernel<F>, lds)) != hipSuccess) return err;
+  const dim3 grid(BH * plan.splits, 1, 1);
+  hipLaunchKernelGGL(split_state_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  a.states = launch_reduce_states(p, plan, 1);
+  hipLaunchKernelGGL(split_apply_fwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  return hipGetLastError();
+}
+
+template <class F>
+hipError_t run_bwd(const Problem& p, const Plan& plan) {
+  Args a = make_args(p, plan);
+  const unsigned BH = static_cast<unsigned>(p.B) * p.H;
+  hipError_t err;
+  if (plan.path == Plan::kFused) {
+    const size_t lds = lds_bytes<F>((p.N + TR - 1) / TR * TR);
+    if ((err = allow_lds(fused_bwd_kernel<F>, lds)) != hipSuccess) return err;
+    hipLaunchKernelGGL(fused_bwd_kernel<F>, dim3(BH), dim3(kThreads), lds, p.stream, a);
+    return hipGetLastError();
+  }
+  const size_t lds = lds_bytes<F>(plan.rows_per_split);
+  if ((err = allow_lds(split_state_kernel<F>, lds)) != hipSuccess) return err;
+  if ((err = allow_lds(split_apply_bwd_kernel<F>, lds)) != hipSuccess) return err;
+  const dim3 grid(BH * plan.splits, 2, 1);
+  const size_t dd = static_cast<size_t>(F::D) * F::D;
+  a.second_offset = static_cast<size_t>(BH) * plan.splits * dd;
+  hipLaunchKernelGGL(split_state_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  a.states = launch_reduce_states(p, plan, 2);
+  a.dstates = a.states + (plan.splits == 1 ? a.second_offset : static_cast<size_t>(BH) * dd);
+  hipLaunchKernelGGL(split_apply_bwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_supports(int dtype, int D) { return (dtype == 1 && D == 64) || (dtype == 0 && D == 32); }
+
+hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan) {
+  return p.dtype == 1 ? run_fwd<Bf16x64>(p, plan) : run_fwd<F32x32>(p, plan);
+}
+
+hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan) {
+  return p.dtype == 1 ? run_bwd<Bf16x64>(p, plan) : run_bwd<F32x32>(p, plan);
+}
+
+}  // namespace cotten
