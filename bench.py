@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of 64 MiB (reference for HBM byte counters)")
     ap.add_argument("--warm-cache", action="store_true", help="one buffer set only (cache-resident)")
     return ap.parse_args()
 
@@ -134,6 +136,23 @@ def measure(db, binding, torch, steps, warmup, use_graph=True):
     }
 
 
+def measured_traffic(workload, kernel_tag):
+    """HBM bytes per launch of the kernel whose name contains `kernel_tag`, from the committed
+    rocprofv3 counter summary of this workload (FETCH_SIZE + WRITE_SIZE, scaled by the copy
+    kernel's reading); None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"mfma_path_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    total, seen = 0.0, 0
+    for line in open(path):
+        parts = line.strip().split(",")
+        if len(parts) == 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") and kernel_tag in parts[1] \
+                and parts[2].endswith("MB per launch"):
+            total += float(parts[2].split()[0]) * 1e6
+            seen += 1
+    return int(total) if seen else None
+
+
 def cpu_baseline(batch, budget_s=12.0):
     """The fp64 oracle (forward + backward, linear form) on the host cores, on a bounded
     sample: the first `nb` batch rows of the same workload, sized for ~budget_s seconds."""
@@ -204,6 +223,14 @@ def main():
             del odb, ob
             torch.cuda.empty_cache()
 
+    if args.copy_calibration:
+        # a plain copy of known size: 64 MiB read + 64 MiB written per launch
+        src = [torch.empty(16 << 20, dtype=torch.float32, device="cuda").normal_() for _ in range(6)]
+        dst = [torch.empty_like(x) for x in src]
+        for i in range(24):
+            dst[i % 6].copy_(src[i % 6])
+        torch.cuda.synchronize()
+
     cpu = None if args.no_cpu else cpu_baseline(batch)
 
     out = {
@@ -233,7 +260,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(res["bwd_gbs"] / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(w.name, "bwd_kernel"),
             "launch_us": round(res["bwd_us"], 2),
             "algorithmic_bytes_per_launch": int(db.bytes_bwd),
             "forward": {"achieved": round(res["fwd_gbs"], 1), "frac": round(res["fwd_gbs"] / HBM_PEAK_GBS, 4),
