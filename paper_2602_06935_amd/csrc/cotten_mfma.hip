@@ -112,6 +112,8 @@ struct Lane {
 struct Bf16x64 {
   typedef bf16 io_t;
   static constexpr int D = 64, EPL = 8, NT = 4;
+  // tiles in flight ahead of the one being processed, per pass (register budget permitting)
+  static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 2, kDepthKV = 2, kDepthQAccum = 1;
   static constexpr int kImageStride = 72;                 // elements per image row
   static constexpr int kImageBytes = D * kImageStride * 2;
 
@@ -217,6 +219,7 @@ struct Bf16x64 {
 struct F32x32 {
   typedef float io_t;
   static constexpr int D = 32, EPL = 4, NT = 2;
+  static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 3, kDepthKV = 2, kDepthQAccum = 2;
   static constexpr int kImageStride = 36;
   static constexpr int kImageBytes = D * kImageStride * 4;
 
@@ -338,6 +341,17 @@ struct WaveLds {
 
 // ---- tiles --------------------------------------------------------------------------------
 
+// The tiles one workgroup walks: local tile lt = 0 .. n_tiles-1 is tile (tile0 + lt * stride)
+// of the slice, i.e. rows 16*(tile0 + lt*stride) .. +15.  A fused workgroup has stride 1; in
+// the split path the tiles of a slice are dealt round-robin to its `splits` workgroups, so
+// that padding (which sits at one end of the sequence) is shared evenly.  Rows >= limit do
+// not exist; `flags`, if given, is the LDS copy of the key mask: flags[16*lt + r].
+struct Rows {
+  int tile0, stride, n_tiles, limit;
+  const uint8_t* flags;
+  __device__ __forceinline__ int row0(int lt) const { return (tile0 + lt * stride) * TR; }
+};
+
 // Raw 16-row tile in the load layout: x[h], y[h] hold row r8 + 8h; `live` bit h says the
 // row takes part (in range and, where a mask applies, a valid key).
 struct Raw {
@@ -345,18 +359,19 @@ struct Raw {
   int live;
 };
 
-// Loads tile rows row0 .. row0+15.  A row takes part when it is below `row_limit` and, if
-// `flags` is given, flags[row - m_base] != 0 (LDS copy of the key mask).  USE_Y: second tensor.
+// Loads local tile lt.  A row takes part when it is below rows.limit and, if rows.flags is
+// given, its flag is set.  USE_Y: second tensor.
 template <bool USE_Y>
 __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const unsigned char* __restrict__ X,
-                                         const unsigned char* __restrict__ Y, int row0,
-                                         const uint8_t* flags, int m_base, int row_limit) {
+                                         const unsigned char* __restrict__ Y, const Rows& rows,
+                                         int lt) {
   r.live = 0;
+  const int row0 = rows.row0(lt);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int row = row0 + L.r8 + 8 * h;
-    bool live = row < row_limit;
-    if (flags != nullptr) live = flags[row - m_base] != 0;
+    bool live = row < rows.limit;
+    if (rows.flags != nullptr) live = rows.flags[lt * TR + L.r8 + 8 * h] != 0;
     r.x[h] = u32x4_t{0, 0, 0, 0};
     r.y[h] = u32x4_t{0, 0, 0, 0};
     if (live) {
@@ -426,69 +441,65 @@ __device__ __forceinline__ void store_row(unsigned char* __restrict__ dst, int r
   *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 16 * L.ch) = F::pack(f);
 }
 
-// Copies the key mask of rows [m_base, m_base + count) into LDS as "takes part" flags.
+// Copies the key mask of the workgroup's tiles into LDS as "takes part" flags.
 __device__ __forceinline__ void fill_flags(uint8_t* flags, const uint8_t* __restrict__ mask,
-                                           int m_base, int count, int row_limit) {
-  for (int i = threadIdx.x; i < count; i += kThreads) {
-    const int row = m_base + i;
+                                           const Rows& rows) {
+  for (int i = threadIdx.x; i < rows.n_tiles * TR; i += kThreads) {
+    const int row = rows.row0(i / TR) + (i % TR);
     uint8_t f = 0;
-    if (row < row_limit) f = mask[row] != 0;
+    if (row < rows.limit) f = mask[row] != 0;
     flags[i] = f;
   }
 }
 
-// First tile of this wave (tile index = wave), issued early by the caller.
+// First tile of this wave (local tile index = wave), issued early by the caller.
 template <bool USE_Y>
 __device__ __forceinline__ void load_first(Raw& a, const Lane& L, const unsigned char* __restrict__ X,
-                                           const unsigned char* __restrict__ Y, int row_begin,
-                                           int n_tiles, const uint8_t* flags, int m_base,
-                                           int row_limit) {
+                                           const unsigned char* __restrict__ Y, const Rows& rows) {
   a.live = 0;
-  if (L.wave < n_tiles)
-    load_raw<USE_Y>(a, L, X, Y, row_begin + L.wave * TR, flags, m_base, row_limit);
+  if (L.wave < rows.n_tiles) load_raw<USE_Y>(a, L, X, Y, rows, L.wave);
 }
 
-// Walks the tiles wave, wave+kWaves, ... < n_tiles owned by this wave with the next tile's
-// global loads in flight while the current one is processed.  `a` holds the first tile.
-template <bool USE_Y, typename Body>
+// Walks the local tiles wave, wave+kWaves, ... owned by this wave with the global loads of
+// the next DEPTH tiles in flight while the current one is processed.  `first` holds the
+// wave's first tile, already loaded (or being loaded) by the caller.  body(raw, row0).
+template <bool USE_Y, int DEPTH, typename Body>
 __device__ __forceinline__ void for_each_tile(const Lane& L, const unsigned char* __restrict__ X,
-                                              const unsigned char* __restrict__ Y, int row_begin,
-                                              int n_tiles, const uint8_t* flags, int m_base,
-                                              int row_limit, Raw& a, Body&& body) {
-  int t = L.wave;
-  if (t >= n_tiles) return;
-  Raw b;
-  while (true) {
-    bool more = t + kWaves < n_tiles;
-    if (more) load_raw<USE_Y>(b, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
-    body(a, row_begin + t * TR);
-    if (!more) break;
-    t += kWaves;
-    more = t + kWaves < n_tiles;
-    if (more) load_raw<USE_Y>(a, L, X, Y, row_begin + (t + kWaves) * TR, flags, m_base, row_limit);
-    body(b, row_begin + t * TR);
-    if (!more) break;
-    t += kWaves;
+                                              const unsigned char* __restrict__ Y, const Rows& rows,
+                                              Raw& first, Body&& body) {
+  static_assert(DEPTH >= 1 && DEPTH <= 3, "prefetch depth");
+  const int n_tiles = rows.n_tiles;
+  if (L.wave >= n_tiles) return;
+  Raw ring[DEPTH + 1];
+  ring[0] = first;
+#pragma unroll
+  for (int i = 1; i < DEPTH; ++i) {
+    const int t = L.wave + i * kWaves;
+    ring[i].live = 0;
+    if (t < n_tiles) load_raw<USE_Y>(ring[i], L, X, Y, rows, t);
+  }
+  for (int t0 = L.wave;; t0 += (DEPTH + 1) * kWaves) {
+#pragma unroll
+    for (int j = 0; j <= DEPTH; ++j) {
+      const int t = t0 + j * kWaves;
+      if (t >= n_tiles) return;
+      const int ahead = t + DEPTH * kWaves;
+      if (ahead < n_tiles) load_raw<USE_Y>(ring[(j + DEPTH) % (DEPTH + 1)], L, X, Y, rows, ahead);
+      body(ring[j], rows.row0(t));
+    }
   }
 }
 
 // ---- passes -------------------------------------------------------------------------------
 // Every pass takes the wave's first tile already loaded in `first`.
 
-// Range of rows a pass walks, with the optional LDS flags of the key mask.
-struct Rows {
-  int begin, n_tiles, limit;   // rows [begin, limit), in n_tiles tiles of 16
-  const uint8_t* flags;        // flags[row - begin], or nullptr: every row below limit
-};
-
 // acc += sum over live rows of xhat^T y
-template <class F>
+template <class F, int DEPTH>
 __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
                                            const unsigned char* __restrict__ X,
                                            const unsigned char* __restrict__ Y, const Rows rows,
                                            float eps, Raw& first, typename F::Acc& acc) {
-  for_each_tile<true>(L, X, Y, rows.begin, rows.n_tiles, rows.flags, rows.begin, rows.limit, first,
-                      [&](const Raw& r, int) {
+  for_each_tile<true, DEPTH>(L, X, Y, rows, first, [&](const Raw& r, int) {
     if (__ballot(r.live != 0) == 0) return;  // no live row in this tile (uniform)
     float inv[2];
     stage<F, kXNormalized, true>(r, L, eps, W.Xt, W.Yt, inv);
@@ -499,14 +510,13 @@ __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
 }
 
 // O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
-template <class F>
+template <class F, int DEPTH>
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
                                                const unsigned char* __restrict__ Q,
                                                unsigned char* __restrict__ O, const Rows rows,
                                                float eps, Raw& first,
                                                const typename F::Operand& Sop) {
-  for_each_tile<false>(L, Q, Q, rows.begin, rows.n_tiles, nullptr, 0, rows.limit, first,
-                       [&](const Raw& r, int row0) {
+  for_each_tile<false, DEPTH>(L, Q, Q, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
     stage<F, kXRaw, false>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
@@ -527,7 +537,7 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
 }
 
 // dQ rows from (Q, dO) and W = scale * S (image op[a][c]); with ACCUM also dsacc += qhat^T dO.
-template <class F, bool ACCUM>
+template <class F, bool ACCUM, int DEPTH>
 __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
                                            const unsigned char* __restrict__ Q,
                                            const unsigned char* __restrict__ dO,
@@ -539,8 +549,7 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
   constexpr bool kHold = !ACCUM || sizeof(typename F::Operand) <= 16 * 4;
   typename F::Operand held;
   if (kHold) held.load(Simage, L);
-  for_each_tile<true>(L, Q, dO, rows.begin, rows.n_tiles, nullptr, 0, rows.limit, first,
-                      [&](const Raw& r, int row0) {
+  for_each_tile<true, DEPTH>(L, Q, dO, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
     stage<F, ACCUM ? kXNormalized : kXNone, true>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
@@ -577,7 +586,7 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
 
 // dK, dV rows from (K, V) and scale * dS: dV = (k dS)/r (image op[c][a]),
 // h = v dS^T (image op[a][c]).  Rows below the limit that are masked get zeros.
-template <class F>
+template <class F, int DEPTH>
 __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
                                             const unsigned char* __restrict__ K,
                                             const unsigned char* __restrict__ V,
@@ -586,8 +595,7 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
                                             float eps, Raw& first,
                                             const typename F::Operand& dSop_v,
                                             const typename F::Operand& dSop_h) {
-  for_each_tile<true>(L, K, V, rows.begin, rows.n_tiles, rows.flags, rows.begin, rows.limit, first,
-                      [&](const Raw& r, int row0) {
+  for_each_tile<true, DEPTH>(L, K, V, rows, first, [&](const Raw& r, int row0) {
     if (__ballot(r.live != 0) == 0) {  // nothing live: only the zero rows are due
       float zeros[F::EPL];
 #pragma unroll
@@ -739,7 +747,7 @@ struct Args {
   const float* states;       // reduced S (split path)
   const float* dstates;      // reduced dS (split path)
   size_t second_offset;      // where the dS partials start in ws
-  int H, N, splits, rows_per_split;
+  int H, N, splits;
   float scale, eps;
 };
 
@@ -752,19 +760,19 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   const int n_tiles = (N + TR - 1) / TR;
   uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   unsigned char* op0 = smem + Layout<F>::kImage0;
-  const Rows keys{0, n_tiles, N, kflags}, all{0, n_tiles, N, nullptr};
+  const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
 
   Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
-  load_first<false>(qfirst, L, a.Q + base, a.Q + base, 0, n_tiles, nullptr, 0, N);
+  load_first<false>(qfirst, L, a.Q + base, a.Q + base, all);
   if (kflags != nullptr) {
-    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, 0, n_tiles * TR, N);
+    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
-  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
 
   typename F::Acc acc;
   acc.zero();
-  state_pass<F>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  state_pass<F, F::kDepthState>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
   wg_reduce<F>(L, smem, acc);
   // O = qhat S: contraction over rows of S
   make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), nullptr}, a.scale, nullptr,
@@ -772,7 +780,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F>(L, W, a.Q + base, a.O + base, all, a.eps, qfirst, Sop);
+  fwd_apply_pass<F, F::kDepthFwd>(L, W, a.Q + base, a.O + base, all, a.eps, qfirst, Sop);
 }
 
 template <class F>
@@ -786,21 +794,21 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
   const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
-  const Rows keys{0, n_tiles, N, kflags}, all{0, n_tiles, N, nullptr};
+  const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
 
   COTTEN_TRACE_POINT(0);
   Raw qfirst, kfirst;
-  load_first<true>(qfirst, L, a.Q + base, a.dO + base, 0, n_tiles, nullptr, 0, N);
+  load_first<true>(qfirst, L, a.Q + base, a.dO + base, all);
   if (kflags != nullptr) {
-    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, 0, n_tiles * TR, N);
+    fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
   COTTEN_TRACE_POINT(1);
-  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
 
   typename F::Acc acc;
   acc.zero();
-  state_pass<F>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  state_pass<F, F::kDepthState>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
   COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(3);
@@ -808,10 +816,11 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   __syncthreads();
   acc.zero();
   COTTEN_TRACE_POINT(4);
-  bwd_q_pass<F, true>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, qfirst, op0, acc);
+  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps,
+                                       qfirst, op0, acc);
   COTTEN_TRACE_POINT(5);
   // the key/value tiles are walked again: get the first one moving before the reduction
-  load_first<true>(kfirst, L, a.K + base, a.V + base, 0, n_tiles, kflags, 0, N);
+  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(6);
   make_operands<F>(reduced, a.scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
@@ -820,13 +829,20 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
   dS_h.load(op0, L);  // h = v dS^T: contraction over columns of dS
   COTTEN_TRACE_POINT(7);
-  bwd_kv_pass<F>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps, kfirst, dS_v,
-                 dS_h);
+  bwd_kv_pass<F, F::kDepthKV>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps,
+                              kfirst, dS_v, dS_h);
   COTTEN_TRACE_POINT(8);
 }
 
-// Split path, step 1: partial states of a block of rows.  blockIdx.y = 0: (K,V) under
-// the key mask -> partial S;  blockIdx.y = 1: (Q,dO) -> partial dS.
+// The tiles of slice bh dealt to workgroup `split` of `splits`.
+__device__ __forceinline__ Rows split_rows(int N, int split, int splits, const uint8_t* flags) {
+  const int total = (N + TR - 1) / TR;
+  const int mine = split < total ? (total - split + splits - 1) / splits : 0;
+  return Rows{split, splits, mine, N, flags};
+}
+
+// Split path, step 1: partial states of this workgroup's tiles.  blockIdx.y = 0: (K,V)
+// under the key mask -> partial S;  blockIdx.y = 1: (Q,dO) -> partial dS.
 template <class F>
 __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) {
   constexpr int D = F::D;
@@ -835,27 +851,28 @@ __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) 
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
   const bool second = blockIdx.y == 1;
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
-  const int r_begin = split * a.rows_per_split;
-  const int r_end = min(N, r_begin + a.rows_per_split);
-  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
+  COTTEN_TRACE_POINT(0);
   const bool masked = !second && a.mask != nullptr;
-  uint8_t* flags = masked ? smem + Layout<F>::kFlags : nullptr;
+  const Rows rows = split_rows(N, split, a.splits, masked ? smem + Layout<F>::kFlags : nullptr);
   const unsigned char* X = (second ? a.Q : a.K) + base;
   const unsigned char* Y = (second ? a.dO : a.V) + base;
   if (masked) {
-    fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, r_begin, n_tiles * TR, r_end);
+    fill_flags(smem + Layout<F>::kFlags, a.mask + static_cast<size_t>(bh / a.H) * N, rows);
     __syncthreads();
   }
-  const Rows rows{r_begin, n_tiles, r_end, flags};
+  COTTEN_TRACE_POINT(1);
   Raw first;
-  load_first<true>(first, L, X, Y, r_begin, n_tiles, flags, r_begin, r_end);
+  load_first<true>(first, L, X, Y, rows);
   typename F::Acc acc;
   acc.zero();
-  state_pass<F>(L, W, X, Y, rows, a.eps, first, acc);
+  state_pass<F, F::kDepthState>(L, W, X, Y, rows, a.eps, first, acc);
+  COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
+  COTTEN_TRACE_POINT(3);
   const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
   float* out = a.ws + (second ? a.second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
   for (int e = threadIdx.x; e < D * D; e += kThreads) out[e] = reduced.at(e / D, e % D);
+  COTTEN_TRACE_POINT(4);
 }
 
 template <class F>
@@ -865,22 +882,19 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
-  const int r_begin = split * a.rows_per_split;
-  const int r_end = min(N, r_begin + a.rows_per_split);
-  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
   unsigned char* op0 = smem + Layout<F>::kImage0;
-  const Rows all{r_begin, n_tiles, r_end, nullptr};
+  const Rows all = split_rows(N, split, a.splits, nullptr);
   Raw first;
-  load_first<false>(first, L, a.Q + base, a.Q + base, r_begin, n_tiles, nullptr, 0, r_end);
+  load_first<false>(first, L, a.Q + base, a.Q + base, all);
   make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
                    nullptr, op0);
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F>(L, W, a.Q + base, a.O + base, all, a.eps, first, Sop);
+  fwd_apply_pass<F, F::kDepthFwd>(L, W, a.Q + base, a.O + base, all, a.eps, first, Sop);
 }
 
-// blockIdx.y = 0: dQ of a block of rows;  blockIdx.y = 1: dK, dV of a block of rows.
+// blockIdx.y = 0: dQ of this workgroup's tiles;  blockIdx.y = 1: their dK, dV.
 template <class F>
 __global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(const Args a) {
   constexpr int D = F::D;
@@ -888,35 +902,31 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(const Args
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
-  const int r_begin = split * a.rows_per_split;
-  const int r_end = min(N, r_begin + a.rows_per_split);
-  const int n_tiles = (r_end - r_begin + TR - 1) / TR;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
   Raw first;
   if (blockIdx.y == 0) {
-    const Rows all{r_begin, n_tiles, r_end, nullptr};
-    load_first<true>(first, L, a.Q + base, a.dO + base, r_begin, n_tiles, nullptr, 0, r_end);
+    const Rows all = split_rows(N, split, a.splits, nullptr);
+    load_first<true>(first, L, a.Q + base, a.dO + base, all);
     make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
                      op0, nullptr);
     __syncthreads();
     typename F::Acc unused;
-    bwd_q_pass<F, false>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, first, op0,
-                         unused);
+    bwd_q_pass<F, false, F::kDepthQ>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, first,
+                                     op0, unused);
   } else {
     uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
-    if (flags != nullptr)
-      fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, r_begin, n_tiles * TR, r_end);
+    const Rows keys = split_rows(N, split, a.splits, flags);
+    if (flags != nullptr) fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     make_operands<F>(StateSource<F>{nullptr, a.dstates + static_cast<size_t>(bh) * D * D}, a.scale,
                      op0, op1);
     __syncthreads();
-    const Rows keys{r_begin, n_tiles, r_end, flags};
-    load_first<true>(first, L, a.K + base, a.V + base, r_begin, n_tiles, flags, r_begin, r_end);
+    load_first<true>(first, L, a.K + base, a.V + base, keys);
     typename F::Operand dS_v, dS_h;
     dS_v.load(op1, L);
     dS_h.load(op0, L);
-    bwd_kv_pass<F>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps, first,
-                   dS_v, dS_h);
+    bwd_kv_pass<F, F::kDepthKV>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys,
+                                a.eps, first, dS_v, dS_h);
   }
 }
 
@@ -952,7 +962,6 @@ Args make_args(const Problem& p, const Plan& plan) {
   a.H = p.H;
   a.N = p.N;
   a.splits = plan.splits;
-  a.rows_per_split = plan.rows_per_split;
   a.scale = p.scale;
   a.eps = p.eps;
   return a;
