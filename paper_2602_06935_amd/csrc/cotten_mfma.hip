@@ -359,27 +359,39 @@ struct Raw {
   int live;
 };
 
-// Loads local tile lt.  A row takes part when it is below rows.limit and, if rows.flags is
-// given, its flag is set.  USE_Y: second tensor.
+// The two tensors a pass reads, as buffer resources over one slice each.  Buffer loads are
+// used instead of flat loads because a lane whose offset lies outside the buffer gets zeros
+// and causes no memory traffic: rows that do not take part are skipped without a branch, so
+// every tile issues the same number of load instructions and the hardware's in-order load
+// counter can tell "this tile has arrived" from "the tiles prefetched after it have not".
+struct Src {
+  __amdgpu_buffer_rsrc_t x, y;
+  __device__ __forceinline__ Src(const unsigned char* X, const unsigned char* Y, int N) {
+    const int bytes = N * kRowBytes;
+    x = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(X), 0, bytes, 0x00020000);
+    y = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Y), 0, bytes, 0x00020000);
+  }
+};
+constexpr uint32_t kOutOfBuffer = 0x80000000u;
+
+// Loads local tile lt (all zeros, and no traffic, if lt is not one of the workgroup's tiles).
+// A row takes part when it is below rows.limit and, if rows.flags is given, its flag is set.
 template <bool USE_Y>
-__device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const unsigned char* __restrict__ X,
-                                         const unsigned char* __restrict__ Y, const Rows& rows,
+__device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const Src& src, const Rows& rows,
                                          int lt) {
   r.live = 0;
+  const bool tile_ok = lt < rows.n_tiles;
   const int row0 = rows.row0(lt);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int row = row0 + L.r8 + 8 * h;
-    bool live = row < rows.limit;
-    if (rows.flags != nullptr) live = rows.flags[lt * TR + L.r8 + 8 * h] != 0;
-    r.x[h] = u32x4_t{0, 0, 0, 0};
-    r.y[h] = u32x4_t{0, 0, 0, 0};
-    if (live) {
-      const size_t off = static_cast<size_t>(row) * kRowBytes + L.ch * 16;
-      r.x[h] = *reinterpret_cast<const u32x4_t*>(X + off);
-      if (USE_Y) r.y[h] = *reinterpret_cast<const u32x4_t*>(Y + off);
-      r.live |= 1 << h;
-    }
+    bool live = tile_ok && row < rows.limit;
+    if (rows.flags != nullptr) live = live && rows.flags[tile_ok ? lt * TR + L.r8 + 8 * h : 0] != 0;
+    const uint32_t off = live ? static_cast<uint32_t>(row) * kRowBytes + L.ch * 16 : kOutOfBuffer;
+    r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
+    if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
+    else r.y[h] = u32x4_t{0, 0, 0, 0};
+    r.live |= static_cast<int>(live) << h;
   }
 }
 
@@ -454,18 +466,15 @@ __device__ __forceinline__ void fill_flags(uint8_t* flags, const uint8_t* __rest
 
 // First tile of this wave (local tile index = wave), issued early by the caller.
 template <bool USE_Y>
-__device__ __forceinline__ void load_first(Raw& a, const Lane& L, const unsigned char* __restrict__ X,
-                                           const unsigned char* __restrict__ Y, const Rows& rows) {
-  a.live = 0;
-  if (L.wave < rows.n_tiles) load_raw<USE_Y>(a, L, X, Y, rows, L.wave);
+__device__ __forceinline__ void load_first(Raw& a, const Lane& L, const Src& src, const Rows& rows) {
+  load_raw<USE_Y>(a, L, src, rows, L.wave);
 }
 
 // Walks the local tiles wave, wave+kWaves, ... owned by this wave with the global loads of
 // the next DEPTH tiles in flight while the current one is processed.  `first` holds the
 // wave's first tile, already loaded (or being loaded) by the caller.  body(raw, row0).
 template <bool USE_Y, int DEPTH, typename Body>
-__device__ __forceinline__ void for_each_tile(const Lane& L, const unsigned char* __restrict__ X,
-                                              const unsigned char* __restrict__ Y, const Rows& rows,
+__device__ __forceinline__ void for_each_tile(const Lane& L, const Src& src, const Rows& rows,
                                               Raw& first, Body&& body) {
   static_assert(DEPTH >= 1 && DEPTH <= 3, "prefetch depth");
   const int n_tiles = rows.n_tiles;
@@ -473,18 +482,13 @@ __device__ __forceinline__ void for_each_tile(const Lane& L, const unsigned char
   Raw ring[DEPTH + 1];
   ring[0] = first;
 #pragma unroll
-  for (int i = 1; i < DEPTH; ++i) {
-    const int t = L.wave + i * kWaves;
-    ring[i].live = 0;
-    if (t < n_tiles) load_raw<USE_Y>(ring[i], L, X, Y, rows, t);
-  }
+  for (int i = 1; i < DEPTH; ++i) load_raw<USE_Y>(ring[i], L, src, rows, L.wave + i * kWaves);
   for (int t0 = L.wave;; t0 += (DEPTH + 1) * kWaves) {
 #pragma unroll
     for (int j = 0; j <= DEPTH; ++j) {
       const int t = t0 + j * kWaves;
       if (t >= n_tiles) return;
-      const int ahead = t + DEPTH * kWaves;
-      if (ahead < n_tiles) load_raw<USE_Y>(ring[(j + DEPTH) % (DEPTH + 1)], L, X, Y, rows, ahead);
+      load_raw<USE_Y>(ring[(j + DEPTH) % (DEPTH + 1)], L, src, rows, t + DEPTH * kWaves);
       body(ring[j], rows.row0(t));
     }
   }
@@ -496,10 +500,9 @@ __device__ __forceinline__ void for_each_tile(const Lane& L, const unsigned char
 // acc += sum over live rows of xhat^T y
 template <class F, int DEPTH>
 __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
-                                           const unsigned char* __restrict__ X,
-                                           const unsigned char* __restrict__ Y, const Rows rows,
-                                           float eps, Raw& first, typename F::Acc& acc) {
-  for_each_tile<true, DEPTH>(L, X, Y, rows, first, [&](const Raw& r, int) {
+                                           const Src& src, const Rows rows, float eps, Raw& first,
+                                           typename F::Acc& acc) {
+  for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int) {
     if (__ballot(r.live != 0) == 0) return;  // no live row in this tile (uniform)
     float inv[2];
     stage<F, kXNormalized, true>(r, L, eps, W.Xt, W.Yt, inv);
@@ -512,11 +515,10 @@ __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
 // O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
 template <class F, int DEPTH>
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
-                                               const unsigned char* __restrict__ Q,
-                                               unsigned char* __restrict__ O, const Rows rows,
-                                               float eps, Raw& first,
+                                               const Src& src, unsigned char* __restrict__ O,
+                                               const Rows rows, float eps, Raw& first,
                                                const typename F::Operand& Sop) {
-  for_each_tile<false, DEPTH>(L, Q, Q, rows, first, [&](const Raw& r, int row0) {
+  for_each_tile<false, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
     stage<F, kXRaw, false>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
@@ -539,9 +541,8 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
 // dQ rows from (Q, dO) and W = scale * S (image op[a][c]); with ACCUM also dsacc += qhat^T dO.
 template <class F, bool ACCUM, int DEPTH>
 __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
-                                           const unsigned char* __restrict__ Q,
-                                           const unsigned char* __restrict__ dO,
-                                           unsigned char* __restrict__ dQ, const Rows rows,
+                                           const Src& src, unsigned char* __restrict__ dQ,
+                                           const Rows rows,
                                            float eps, Raw& first, const unsigned char* Simage,
                                            typename F::Acc& dsacc) {
   // With the state accumulators live, a large operand is re-read from LDS for every tile;
@@ -549,7 +550,7 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
   constexpr bool kHold = !ACCUM || sizeof(typename F::Operand) <= 16 * 4;
   typename F::Operand held;
   if (kHold) held.load(Simage, L);
-  for_each_tile<true, DEPTH>(L, Q, dO, rows, first, [&](const Raw& r, int row0) {
+  for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
     stage<F, ACCUM ? kXNormalized : kXNone, true>(r, L, eps, W.Xt, W.Yt, inv);
     wave_lds_fence();
@@ -588,14 +589,12 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
 // h = v dS^T (image op[a][c]).  Rows below the limit that are masked get zeros.
 template <class F, int DEPTH>
 __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
-                                            const unsigned char* __restrict__ K,
-                                            const unsigned char* __restrict__ V,
-                                            unsigned char* __restrict__ dK,
+                                            const Src& src, unsigned char* __restrict__ dK,
                                             unsigned char* __restrict__ dV, const Rows rows,
                                             float eps, Raw& first,
                                             const typename F::Operand& dSop_v,
                                             const typename F::Operand& dSop_h) {
-  for_each_tile<true, DEPTH>(L, K, V, rows, first, [&](const Raw& r, int row0) {
+  for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     if (__ballot(r.live != 0) == 0) {  // nothing live: only the zero rows are due
       float zeros[F::EPL];
 #pragma unroll
@@ -761,18 +760,19 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
+  const Src q_src(a.Q + base, a.Q + base, N), kv_src(a.K + base, a.V + base, N);
 
   Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
-  load_first<false>(qfirst, L, a.Q + base, a.Q + base, all);
+  load_first<false>(qfirst, L, q_src, all);
   if (kflags != nullptr) {
     fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
-  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
+  load_first<true>(kfirst, L, kv_src, keys);
 
   typename F::Acc acc;
   acc.zero();
-  state_pass<F, F::kDepthState>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  state_pass<F, F::kDepthState>(L, W, kv_src, keys, a.eps, kfirst, acc);
   wg_reduce<F>(L, smem, acc);
   // O = qhat S: contraction over rows of S
   make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), nullptr}, a.scale, nullptr,
@@ -780,7 +780,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F, F::kDepthFwd>(L, W, a.Q + base, a.O + base, all, a.eps, qfirst, Sop);
+  fwd_apply_pass<F, F::kDepthFwd>(L, W, q_src, a.O + base, all, a.eps, qfirst, Sop);
 }
 
 template <class F>
@@ -795,20 +795,21 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   unsigned char* op1 = smem + Layout<F>::kImage1;
   const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
+  const Src q_src(a.Q + base, a.dO + base, N), kv_src(a.K + base, a.V + base, N);
 
   COTTEN_TRACE_POINT(0);
   Raw qfirst, kfirst;
-  load_first<true>(qfirst, L, a.Q + base, a.dO + base, all);
+  load_first<true>(qfirst, L, q_src, all);
   if (kflags != nullptr) {
     fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
   COTTEN_TRACE_POINT(1);
-  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
+  load_first<true>(kfirst, L, kv_src, keys);
 
   typename F::Acc acc;
   acc.zero();
-  state_pass<F, F::kDepthState>(L, W, a.K + base, a.V + base, keys, a.eps, kfirst, acc);
+  state_pass<F, F::kDepthState>(L, W, kv_src, keys, a.eps, kfirst, acc);
   COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(3);
@@ -816,11 +817,11 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   __syncthreads();
   acc.zero();
   COTTEN_TRACE_POINT(4);
-  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps,
+  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, q_src, a.dQ + base, all, a.eps,
                                        qfirst, op0, acc);
   COTTEN_TRACE_POINT(5);
   // the key/value tiles are walked again: get the first one moving before the reduction
-  load_first<true>(kfirst, L, a.K + base, a.V + base, keys);
+  load_first<true>(kfirst, L, kv_src, keys);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(6);
   make_operands<F>(reduced, a.scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
@@ -829,7 +830,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
   dS_h.load(op0, L);  // h = v dS^T: contraction over columns of dS
   COTTEN_TRACE_POINT(7);
-  bwd_kv_pass<F, F::kDepthKV>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys, a.eps,
+  bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps,
                               kfirst, dS_v, dS_h);
   COTTEN_TRACE_POINT(8);
 }
@@ -854,18 +855,17 @@ __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) 
   COTTEN_TRACE_POINT(0);
   const bool masked = !second && a.mask != nullptr;
   const Rows rows = split_rows(N, split, a.splits, masked ? smem + Layout<F>::kFlags : nullptr);
-  const unsigned char* X = (second ? a.Q : a.K) + base;
-  const unsigned char* Y = (second ? a.dO : a.V) + base;
+  const Src src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, N);
   if (masked) {
     fill_flags(smem + Layout<F>::kFlags, a.mask + static_cast<size_t>(bh / a.H) * N, rows);
     __syncthreads();
   }
   COTTEN_TRACE_POINT(1);
   Raw first;
-  load_first<true>(first, L, X, Y, rows);
+  load_first<true>(first, L, src, rows);
   typename F::Acc acc;
   acc.zero();
-  state_pass<F, F::kDepthState>(L, W, X, Y, rows, a.eps, first, acc);
+  state_pass<F, F::kDepthState>(L, W, src, rows, a.eps, first, acc);
   COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(3);
@@ -884,14 +884,15 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows all = split_rows(N, split, a.splits, nullptr);
+  const Src q_src(a.Q + base, a.Q + base, N);
   Raw first;
-  load_first<false>(first, L, a.Q + base, a.Q + base, all);
+  load_first<false>(first, L, q_src, all);
   make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
                    nullptr, op0);
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F, F::kDepthFwd>(L, W, a.Q + base, a.O + base, all, a.eps, first, Sop);
+  fwd_apply_pass<F, F::kDepthFwd>(L, W, q_src, a.O + base, all, a.eps, first, Sop);
 }
 
 // blockIdx.y = 0: dQ of this workgroup's tiles;  blockIdx.y = 1: their dK, dV.
@@ -907,25 +908,27 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(const Args
   Raw first;
   if (blockIdx.y == 0) {
     const Rows all = split_rows(N, split, a.splits, nullptr);
-    load_first<true>(first, L, a.Q + base, a.dO + base, all);
+    const Src q_src(a.Q + base, a.dO + base, N);
+    load_first<true>(first, L, q_src, all);
     make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
                      op0, nullptr);
     __syncthreads();
     typename F::Acc unused;
-    bwd_q_pass<F, false, F::kDepthQ>(L, W, a.Q + base, a.dO + base, a.dQ + base, all, a.eps, first,
+    bwd_q_pass<F, false, F::kDepthQ>(L, W, q_src, a.dQ + base, all, a.eps, first,
                                      op0, unused);
   } else {
     uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
     const Rows keys = split_rows(N, split, a.splits, flags);
+    const Src kv_src(a.K + base, a.V + base, N);
     if (flags != nullptr) fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     make_operands<F>(StateSource<F>{nullptr, a.dstates + static_cast<size_t>(bh) * D * D}, a.scale,
                      op0, op1);
     __syncthreads();
-    load_first<true>(first, L, a.K + base, a.V + base, keys);
+    load_first<true>(first, L, kv_src, keys);
     typename F::Operand dS_v, dS_h;
     dS_v.load(op1, L);
     dS_h.load(op0, L);
-    bwd_kv_pass<F, F::kDepthKV>(L, W, a.K + base, a.V + base, a.dK + base, a.dV + base, keys,
+    bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys,
                                 a.eps, first, dS_v, dS_h);
   }
 }
