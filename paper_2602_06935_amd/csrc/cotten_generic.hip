@@ -97,18 +97,17 @@ __global__ __launch_bounds__(kThreads) void state_kernel(
 }
 
 // Sums the partial states of every slice in split order (fixed order => results do
-// not depend on scheduling).  One thread per state element; grid.y selects S or dS.
+// not depend on scheduling).  One thread per state element.
 __global__ __launch_bounds__(kThreads) void reduce_states_kernel(
     const float* __restrict__ partial, float* __restrict__ reduced, int splits, int dd,
-    size_t total, size_t partial_second_offset) {
+    size_t total) {
   const size_t e = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (e >= total) return;
   const size_t bh = e / dd, k = e % dd;
-  const float* __restrict__ src =
-      partial + (blockIdx.y ? partial_second_offset : 0) + bh * splits * dd + k;
+  const float* __restrict__ src = partial + bh * splits * dd + k;
   float s = 0.0f;
   for (int p = 0; p < splits; ++p) s += src[static_cast<size_t>(p) * dd];
-  reduced[(blockIdx.y ? total : 0) + e] = s;
+  reduced[e] = s;
 }
 
 // Copies the reduced state of one slice into LDS, times `scale`, either as is
@@ -291,6 +290,18 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
   }
 }
 
+// Where the reduced states of the generic path live: behind the partials when a reduction
+// is needed, otherwise the single partial of each slice already is the state.
+const float* reduce_generic(const Problem& p, const Plan& plan, int nstates) {
+  if (plan.splits == 1) return p.workspace;
+  const size_t BH = static_cast<size_t>(p.B) * p.H;
+  const int dd = p.D * p.D;
+  float* reduced = p.workspace + BH * plan.splits * dd * nstates;
+  // S and dS partials are contiguous [nstates][BH*splits][dd]: one launch covers both
+  launch_reduce_states(p.workspace, reduced, plan.splits, dd, BH * nstates, p.stream);
+  return reduced;
+}
+
 template <typename T, int D>
 hipError_t run_fwd(const Problem& p, const Plan& plan) {
   const int BH = p.B * p.H;
@@ -299,7 +310,7 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(nullptr), p.mask,
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps);
-  const float* states = launch_reduce_states(p, plan, 1);
+  const float* states = reduce_generic(p, plan, 1);
   hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.N,
                      plan.splits, plan.rows_per_split, p.scale, p.eps);
@@ -315,7 +326,7 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask,
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps);
-  const float* states = launch_reduce_states(p, plan, 2);
+  const float* states = reduce_generic(p, plan, 2);
   const float* dstates = states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * D * D);
   hipLaunchKernelGGL((apply_bwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
@@ -338,16 +349,12 @@ hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
 
 }  // namespace
 
-const float* launch_reduce_states(const Problem& p, const Plan& plan, int nstates) {
-  if (plan.splits == 1) return p.workspace;
-  const size_t BH = static_cast<size_t>(p.B) * p.H;
-  const int dd = p.D * p.D;
-  const size_t total = BH * dd;
-  float* reduced = p.workspace + BH * plan.splits * dd * nstates;
-  const dim3 grid(static_cast<unsigned>((total + kThreads - 1) / kThreads), nstates, 1);
-  hipLaunchKernelGGL(reduce_states_kernel, grid, dim3(kThreads), 0, p.stream, p.workspace, reduced,
-                     plan.splits, dd, total, BH * plan.splits * dd);
-  return reduced;
+void launch_reduce_states(const float* partial, float* reduced, int splits, int dd, size_t slices,
+                          hipStream_t stream) {
+  const size_t total = slices * dd;
+  const dim3 grid(static_cast<unsigned>((total + kThreads - 1) / kThreads), 1, 1);
+  hipLaunchKernelGGL(reduce_states_kernel, grid, dim3(kThreads), 0, stream, partial, reduced,
+                     splits, dd, total);
 }
 
 Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
@@ -357,7 +364,8 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
   long splits, rows;
   if (mfma_supports(dtype, D)) {
     // One workgroup per slice while that fills the chip or the slice is short; otherwise
-    // cut the sequence so that about 512 workgroups exist, in blocks of 64 rows.
+    // cut the sequence so that about 256 workgroups exist (one per compute unit: measured best,
+    // the fixed cost per workgroup outweighs the extra overlap of a second one), in blocks of 64 rows.
     constexpr long kFusedMaxN = 2048, kBlock = 64;
     if (N <= kFusedMaxN && (BH >= 256 || N <= 256)) {
       plan.path = Plan::kFused;
@@ -367,7 +375,7 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
       return plan;
     }
     plan.path = Plan::kSplit;
-    splits = (512 + BH - 1) / BH;
+    splits = (256 + BH - 1) / BH;
     const long by_len = (N + kFusedMaxN - 1) / kFusedMaxN;
     if (splits < by_len) splits = by_len;
     const long max_splits = (N + kBlock - 1) / kBlock;
@@ -388,9 +396,13 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
   splits = (N + rows - 1) / rows;
   plan.splits = static_cast<int>(splits);
   plan.rows_per_split = static_cast<int>(rows);
-  // partial states, plus the reduced states when there is more than one partial
-  plan.workspace_floats =
-      static_cast<size_t>(BH) * D * D * nstates * (splits + (splits > 1 ? 1 : 0));
+  if (plan.path == Plan::kSplit) {
+    plan.workspace_floats = static_cast<size_t>(BH) * D * D * splits * nstates;
+  } else {
+    // partial states, plus the reduced states when there is more than one partial
+    plan.workspace_floats =
+        static_cast<size_t>(BH) * D * D * nstates * (splits + (splits > 1 ? 1 : 0));
+  }
   return plan;
 }
 

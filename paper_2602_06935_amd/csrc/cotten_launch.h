@@ -20,7 +20,7 @@ struct Problem {
   int B, H, N, D;
   int dtype;            // 0 = f32, 1 = bf16
   float scale, eps;
-  float* workspace;     // partial states, see Plan
+  float* workspace;     // partial and reduced states, see Plan
   hipStream_t stream;
 };
 
@@ -30,8 +30,10 @@ struct Problem {
 //                 kGeneric vector-ALU kernels for shapes the MFMA kernels do not cover
 //   splits      : workgroups per slice in the state-reduction kernel; each reduces
 //                 `rows_per_split` consecutive rows to one partial d x d state
-//   workspace   : floats; partial states [nstates][B*H*splits][D*D], followed, when
-//                 splits > 1, by the reduced states [nstates][B*H][D*D]
+//   workspace   : floats.  kGeneric: partial states [nstates][B*H*splits][D*D], followed, when
+//                 splits > 1, by the reduced states [nstates][B*H][D*D].  kSplit: partial
+//                 states [nstates][B*H][splits][D*D]; every consumer workgroup sums the
+//                 partials of its slice itself, in split order
 struct Plan {
   enum Path { kGeneric = 0, kFused = 1, kSplit = 2 };
   Path path;
@@ -42,9 +44,10 @@ struct Plan {
 
 Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd);
 
-// Sums the partial states in split order; returns where the reduced states are
-// (the partials themselves when splits == 1).  nstates = 1 (S) or 2 (S and dS).
-const float* launch_reduce_states(const Problem& p, const Plan& plan, int nstates);
+// reduced[s][e] = partial[s][0][e] + partial[s][1][e] + ... in split order, for `slices`
+// slices of dd floats each.
+void launch_reduce_states(const float* partial, float* reduced, int splits, int dd, size_t slices,
+                          hipStream_t stream);
 
 // Vector-ALU path (state reduction, then apply) for any supported shape.
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);

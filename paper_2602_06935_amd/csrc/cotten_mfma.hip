@@ -677,17 +677,52 @@ __device__ __forceinline__ void wg_reduce(const Lane& L, unsigned char* smem,
   __syncthreads();
 }
 
-// Element (m, n) of the reduced state: from LDS (R0 + R1) or from a row-major global array.
+// Element (m, n) of a complete state held in LDS: either as the two reduction images
+// R0 + R1 (column-major, padded), or as one row-major D x D array (after gather_partials).
 template <class F>
 struct StateSource {
-  const float* lds;     // R0 (R1 follows) or nullptr
-  const float* global;  // row-major D x D or nullptr
+  const float* lds;
+  bool row_major;
   __device__ __forceinline__ float at(int m, int n) const {
-    if (lds != nullptr)
-      return lds[n * Layout<F>::kRStride + m] + lds[Layout<F>::kRFloats + n * Layout<F>::kRStride + m];
-    return global[m * F::D + n];
+    if (row_major) return lds[m * F::D + n];
+    return lds[n * Layout<F>::kRStride + m] + lds[Layout<F>::kRFloats + n * Layout<F>::kRStride + m];
   }
 };
+
+// Split path: sums, in split order, the `splits` row-major partial states a slice has in
+// global memory (written by an earlier kernel) into a row-major LDS array.  Every consumer
+// workgroup repeats the same fixed-order sum, so there is no separate reduction launch and
+// no cross-workgroup synchronisation.  Loads of four splits are kept in flight together.
+template <class F>
+__device__ __forceinline__ void gather_partials(const float* __restrict__ partials, int splits,
+                                                float* dst) {
+  constexpr int DD = F::D * F::D, kPer = DD / kThreads;
+  float sum[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) sum[i] = 0.0f;
+  int p = 0;
+  for (; p + 4 <= splits; p += 4) {
+    float v[4][kPer];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < kPer; ++i)
+        v[q][i] = partials[static_cast<size_t>(p + q) * DD + threadIdx.x + i * kThreads];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) sum[i] += v[q][i];
+  }
+  for (; p < splits; ++p) {
+    float v[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) v[i] = partials[static_cast<size_t>(p) * DD + threadIdx.x + i * kThreads];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) sum[i] += v[i];
+  }
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) dst[threadIdx.x + i * kThreads] = sum[i];
+}
 
 // Builds operand images of scale * M for the apply products:
 //   natural    op[m][n] = M[m][n]   (products contracting over n)
@@ -697,17 +732,19 @@ __device__ __forceinline__ void make_operands(const StateSource<F> src, float sc
                                               unsigned char* natural, unsigned char* transposed) {
   constexpr int D = F::D;
   constexpr int kPer = D * D / 2 / kThreads;  // element pairs per thread
+  // Thread -> element maps chosen so that consecutive lanes walk consecutive state rows m,
+  // which are contiguous in the column-major reduction images.
   if (natural != nullptr) {
     float lo[kPer], hi[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = e / (D / 2), n = (e % (D / 2)) * 2;
+      const int e = threadIdx.x + i * kThreads, m = e % D, n = (e / D) * 2;
       lo[i] = src.at(m, n);
       hi[i] = src.at(m, n + 1);
     }
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = e / (D / 2), n = (e % (D / 2)) * 2;
+      const int e = threadIdx.x + i * kThreads, m = e % D, n = (e / D) * 2;
       F::write_image_pair(natural, m, n, lo[i] * scale, hi[i] * scale);
     }
   }
@@ -715,13 +752,13 @@ __device__ __forceinline__ void make_operands(const StateSource<F> src, float sc
     float lo[kPer], hi[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, n = e % D, m = (e / D) * 2;
+      const int e = threadIdx.x + i * kThreads, m = (e % (D / 2)) * 2, n = e / (D / 2);
       lo[i] = src.at(m, n);
       hi[i] = src.at(m + 1, n);
     }
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, n = e % D, m = (e / D) * 2;
+      const int e = threadIdx.x + i * kThreads, m = (e % (D / 2)) * 2, n = e / (D / 2);
       F::write_image_pair(transposed, n, m, lo[i] * scale, hi[i] * scale);
     }
   }
@@ -742,10 +779,9 @@ struct Args {
   unsigned char* dQ;
   unsigned char* dK;
   unsigned char* dV;
-  float* ws;                 // partial states (split path)
-  const float* states;       // reduced S (split path)
-  const float* dstates;      // reduced dS (split path)
-  size_t second_offset;      // where the dS partials start in ws
+  // split path: partial states in the workspace, [B*H][splits][D*D] floats each
+  float* s_partials;
+  float* ds_partials;
   int H, N, splits;
   float scale, eps;
 };
@@ -775,7 +811,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   state_pass<F, F::kDepthState>(L, W, kv_src, keys, a.eps, kfirst, acc);
   wg_reduce<F>(L, smem, acc);
   // O = qhat S: contraction over rows of S
-  make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), nullptr}, a.scale, nullptr,
+  make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), false}, a.scale, nullptr,
                    op0);
   __syncthreads();
   typename F::Operand Sop;
@@ -793,7 +829,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
-  const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
+  const StateSource<F> reduced{reinterpret_cast<const float*>(smem), false};
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
   const Src q_src(a.Q + base, a.dO + base, N), kv_src(a.K + base, a.V + base, N);
 
@@ -842,22 +878,29 @@ __device__ __forceinline__ Rows split_rows(int N, int split, int splits, const u
   return Rows{split, splits, mine, N, flags};
 }
 
-// Split path, step 1: partial states of this workgroup's tiles.  blockIdx.y = 0: (K,V)
-// under the key mask -> partial S;  blockIdx.y = 1: (Q,dO) -> partial dS.
+// Split path: the workgroup's partial state (R0 + R1 in LDS) goes to its slot in global memory.
+template <class F>
+__device__ __forceinline__ void publish_partial(float* partials, int bh, int split, int splits) {
+  constexpr int DD = F::D * F::D;
+  const StateSource<F> mine{reinterpret_cast<const float*>(smem), false};
+  float* out = partials + (static_cast<size_t>(bh) * splits + split) * DD;
+  for (int e = threadIdx.x; e < DD; e += kThreads) out[e] = mine.at(e / F::D, e % F::D);
+}
+
+// Split path, step 1 (both directions): partial S of this workgroup's (K,V) tiles.
 template <class F>
 __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) {
-  constexpr int D = F::D;
+  constexpr int DD = F::D * F::D;
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
-  const bool second = blockIdx.y == 1;
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
   COTTEN_TRACE_POINT(0);
-  const bool masked = !second && a.mask != nullptr;
-  const Rows rows = split_rows(N, split, a.splits, masked ? smem + Layout<F>::kFlags : nullptr);
-  const Src src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, N);
-  if (masked) {
-    fill_flags(smem + Layout<F>::kFlags, a.mask + static_cast<size_t>(bh / a.H) * N, rows);
+  uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
+  const Rows rows = split_rows(N, split, a.splits, flags);
+  const Src src(a.K + base, a.V + base, N);
+  if (flags != nullptr) {
+    fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, rows);
     __syncthreads();
   }
   COTTEN_TRACE_POINT(1);
@@ -869,9 +912,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) 
   COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(3);
-  const StateSource<F> reduced{reinterpret_cast<const float*>(smem), nullptr};
-  float* out = a.ws + (second ? a.second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
-  for (int e = threadIdx.x; e < D * D; e += kThreads) out[e] = reduced.at(e / D, e % D);
+  publish_partial<F>(a.s_partials, bh, split, a.splits);
   COTTEN_TRACE_POINT(4);
 }
 
@@ -887,50 +928,68 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   const Src q_src(a.Q + base, a.Q + base, N);
   Raw first;
   load_first<false>(first, L, q_src, all);
-  make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
-                   nullptr, op0);
+  float* gathered = reinterpret_cast<float*>(smem);
+  gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * D * D, a.splits, gathered);
+  __syncthreads();
+  make_operands<F>(StateSource<F>{gathered, true}, a.scale, nullptr, op0);
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
   fwd_apply_pass<F, F::kDepthFwd>(L, W, q_src, a.O + base, all, a.eps, first, Sop);
 }
 
-// blockIdx.y = 0: dQ of this workgroup's tiles;  blockIdx.y = 1: their dK, dV.
+// Backward, step 2: one pass over this workgroup's (Q,dO) tiles writes dQ (S is complete)
+// and accumulates the partial dS.
 template <class F>
-__global__ __launch_bounds__(kThreads, 2) void split_apply_bwd_kernel(const Args a) {
-  constexpr int D = F::D;
+__global__ __launch_bounds__(kThreads, 2) void split_q_kernel(const Args a) {
+  constexpr int DD = F::D * F::D;
+  const Lane L;
+  const WaveLds<F> W(smem, L.wave);
+  const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
+  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  unsigned char* op0 = smem + Layout<F>::kImage0;
+  const Rows all = split_rows(N, split, a.splits, nullptr);
+  const Src q_src(a.Q + base, a.dO + base, N);
+  Raw first;
+  load_first<true>(first, L, q_src, all);
+  float* gathered = reinterpret_cast<float*>(smem);
+  gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
+  __syncthreads();
+  make_operands<F>(StateSource<F>{gathered, true}, a.scale, op0, nullptr);
+  __syncthreads();
+  typename F::Acc acc;
+  acc.zero();
+  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, q_src, a.dQ + base, all, a.eps, first, op0, acc);
+  wg_reduce<F>(L, smem, acc);
+  publish_partial<F>(a.ds_partials, bh, split, a.splits);
+}
+
+// Backward, step 3: dK, dV of this workgroup's (K,V) tiles from the complete dS.
+template <class F>
+__global__ __launch_bounds__(kThreads, 2) void split_kv_kernel(const Args a) {
+  constexpr int DD = F::D * F::D;
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
   const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
+  uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
+  const Rows keys = split_rows(N, split, a.splits, flags);
+  const Src kv_src(a.K + base, a.V + base, N);
+  if (flags != nullptr) fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
+  float* gathered = reinterpret_cast<float*>(smem);
+  gather_partials<F>(a.ds_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
+  __syncthreads();
+  make_operands<F>(StateSource<F>{gathered, true}, a.scale, op0, op1);
+  __syncthreads();
   Raw first;
-  if (blockIdx.y == 0) {
-    const Rows all = split_rows(N, split, a.splits, nullptr);
-    const Src q_src(a.Q + base, a.dO + base, N);
-    load_first<true>(first, L, q_src, all);
-    make_operands<F>(StateSource<F>{nullptr, a.states + static_cast<size_t>(bh) * D * D}, a.scale,
-                     op0, nullptr);
-    __syncthreads();
-    typename F::Acc unused;
-    bwd_q_pass<F, false, F::kDepthQ>(L, W, q_src, a.dQ + base, all, a.eps, first,
-                                     op0, unused);
-  } else {
-    uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
-    const Rows keys = split_rows(N, split, a.splits, flags);
-    const Src kv_src(a.K + base, a.V + base, N);
-    if (flags != nullptr) fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
-    make_operands<F>(StateSource<F>{nullptr, a.dstates + static_cast<size_t>(bh) * D * D}, a.scale,
-                     op0, op1);
-    __syncthreads();
-    load_first<true>(first, L, kv_src, keys);
-    typename F::Operand dS_v, dS_h;
-    dS_v.load(op1, L);
-    dS_h.load(op0, L);
-    bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys,
-                                a.eps, first, dS_v, dS_h);
-  }
+  load_first<true>(first, L, kv_src, keys);
+  typename F::Operand dS_v, dS_h;
+  dS_v.load(op1, L);
+  dS_h.load(op0, L);
+  bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps, first, dS_v,
+                              dS_h);
 }
 
 // ---- host side ----------------------------------------------------------------------------------
@@ -950,7 +1009,7 @@ size_t lds_bytes(int flag_rows) {
   return static_cast<size_t>(Layout<F>::kFlags) + static_cast<size_t>(flag_rows) + 16;
 }
 
-Args make_args(const Problem& p, const Plan& plan) {
+Args make_args(const Problem& p, const Plan& plan, int D) {
   Args a{};
   a.Q = static_cast<const unsigned char*>(p.Q);
   a.K = static_cast<const unsigned char*>(p.K);
@@ -961,7 +1020,10 @@ Args make_args(const Problem& p, const Plan& plan) {
   a.dQ = static_cast<unsigned char*>(p.dQ);
   a.dK = static_cast<unsigned char*>(p.dK);
   a.dV = static_cast<unsigned char*>(p.dV);
-  a.ws = p.workspace;
+  if (plan.path == Plan::kSplit) {
+    a.s_partials = p.workspace;
+    a.ds_partials = p.workspace + static_cast<size_t>(p.B) * p.H * plan.splits * D * D;
+  }
   a.H = p.H;
   a.N = p.N;
   a.splits = plan.splits;
@@ -972,7 +1034,7 @@ Args make_args(const Problem& p, const Plan& plan) {
 
 template <class F>
 hipError_t run_fwd(const Problem& p, const Plan& plan) {
-  Args a = make_args(p, plan);
+  const Args a = make_args(p, plan, F::D);
   const unsigned BH = static_cast<unsigned>(p.B) * p.H;
   hipError_t err;
   if (plan.path == Plan::kFused) {
@@ -986,14 +1048,13 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
   if ((err = allow_lds(split_apply_fwd_kernel<F>, lds)) != hipSuccess) return err;
   const dim3 grid(BH * plan.splits, 1, 1);
   hipLaunchKernelGGL(split_state_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
-  a.states = launch_reduce_states(p, plan, 1);
   hipLaunchKernelGGL(split_apply_fwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
   return hipGetLastError();
 }
 
 template <class F>
 hipError_t run_bwd(const Problem& p, const Plan& plan) {
-  Args a = make_args(p, plan);
+  const Args a = make_args(p, plan, F::D);
   const unsigned BH = static_cast<unsigned>(p.B) * p.H;
   hipError_t err;
   if (plan.path == Plan::kFused) {
@@ -1004,14 +1065,12 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
   }
   const size_t lds = lds_bytes<F>(plan.rows_per_split);
   if ((err = allow_lds(split_state_kernel<F>, lds)) != hipSuccess) return err;
-  if ((err = allow_lds(split_apply_bwd_kernel<F>, lds)) != hipSuccess) return err;
-  const dim3 grid(BH * plan.splits, 2, 1);
-  const size_t dd = static_cast<size_t>(F::D) * F::D;
-  a.second_offset = static_cast<size_t>(BH) * plan.splits * dd;
+  if ((err = allow_lds(split_q_kernel<F>, lds)) != hipSuccess) return err;
+  if ((err = allow_lds(split_kv_kernel<F>, lds)) != hipSuccess) return err;
+  const dim3 grid(BH * plan.splits, 1, 1);
   hipLaunchKernelGGL(split_state_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
-  a.states = launch_reduce_states(p, plan, 2);
-  a.dstates = a.states + (plan.splits == 1 ? a.second_offset : static_cast<size_t>(BH) * dd);
-  hipLaunchKernelGGL(split_apply_bwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  hipLaunchKernelGGL(split_q_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  hipLaunchKernelGGL(split_kv_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
   return hipGetLastError();
 }
 

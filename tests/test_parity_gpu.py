@@ -183,6 +183,29 @@ def test_deterministic_bits_and_caller_workspace():
         assert np.array_equal(a, c)
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 64)])
+def test_long_sequence_split_path(oracle, dtype, d):
+    """Few slices, long sequence: the sequence is cut over several workgroups per slice, and
+    the partial states travel through the workspace (the library's own or the caller's)."""
+    B, H, N = 2, 2, 1030
+    Q, K, V, dO = _case(77, B, H, N, d, dtype)
+    mask = np.zeros((B, N), np.uint8)
+    mask[0, 400:] = 1
+    mask[1, ::2] = 1
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"split path d={d}")
+    code = binding.COTTEN_F32 if dtype == "f32" else binding.COTTEN_BF16
+    need = binding.cotten_attn_workspace_bytes(B, H, N, d, code, True)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        assert np.array_equal(gpu_fwd(Q, K, V, mask, dtype), got_o)
+        for a, c in zip(gpu_bwd(Q, K, V, dO, mask, dtype), got_g):
+            assert np.array_equal(a, c)
+    assert np.array_equal(gpu_fwd(Q, K, V, mask, dtype, workspace=ws), got_o)
+    for a, c in zip(gpu_bwd(Q, K, V, dO, mask, dtype, workspace=ws), got_g):
+        assert np.array_equal(a, c)
+
+
 def test_binding_reports_library_errors():
     x = torch.zeros(1, 1, 8, 48, device="cuda")
     with pytest.raises(binding.CottenError) as ei:
