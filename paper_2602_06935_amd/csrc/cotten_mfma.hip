@@ -193,7 +193,8 @@ struct Bf16x64 {
     }
   };
 
-  // out[nt] (16 rows x 16 columns, fp32) = (tile rows) x W
+  // (tile rows) x W, computed transposed (W^T X^T) so that each lane ends up with four
+  // neighbouring columns of one row: out[nt][v] = T[row lane%16][column 16*nt + 4*(lane/16) + v]
   static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
                                                const Lane& L, f32x4_t (&out)[4]) {
     bf16x8_t a[2];
@@ -205,7 +206,7 @@ struct Bf16x64 {
       out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
-        out[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], W.frag[nt][ks], out[nt], 0, 0, 0);
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W.frag[nt][ks], a[ks], out[nt], 0, 0, 0);
     }
   }
 
@@ -294,7 +295,7 @@ struct F32x32 {
       out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < 8; ++s)
-        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], W.frag[nt][s], out[nt], 0, 0, 0);
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(W.frag[nt][s], a[s], out[nt], 0, 0, 0);
     }
   }
 
@@ -423,14 +424,12 @@ __device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, un
   }
 }
 
-// MFMA result layout -> scratch tile (row 4*(lane/16)+v, column 16*nt + lane%16)
+// Apply result -> scratch tile: row lane%16, columns 16*nt + 4*(lane/16) .. +3 (one 128-bit write)
 template <class F>
 __device__ __forceinline__ void to_scratch(const f32x4_t (&out)[F::NT], float* Sc, const Lane& L) {
 #pragma unroll
   for (int nt = 0; nt < F::NT; ++nt)
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-      Sc[(4 * L.g16 + v) * Layout<F>::kScratchStride + 16 * nt + L.i16] = out[nt][v];
+    *reinterpret_cast<f32x4_t*>(Sc + L.i16 * Layout<F>::kScratchStride + 16 * nt + 4 * L.g16) = out[nt];
 }
 
 // scratch tile -> load layout: the EPL columns of row r8 + 8h this lane owns
