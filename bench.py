@@ -136,21 +136,26 @@ def measure(db, binding, torch, steps, warmup, use_graph=True):
     }
 
 
-def measured_traffic(workload, kernel_tag):
-    """HBM bytes per launch of the kernel whose name contains `kernel_tag`, from the committed
-    rocprofv3 counter summary of this workload (FETCH_SIZE + WRITE_SIZE, scaled by the copy
-    kernel's reading); None when no summary is there."""
+def measured_traffic(workload, kernel_tags):
+    """HBM bytes per backward call, from the committed rocprofv3 counter summary of this
+    workload: FETCH_SIZE + WRITE_SIZE (scaled by the copy kernel's reading) summed over the
+    kernels of the call, i.e. those whose name contains one of `kernel_tags`.  None when no
+    summary is there."""
     path = os.path.join(ROOT, "profiles", f"mfma_path_{workload}.txt")
     if not os.path.exists(path):
         return None
     total, seen = 0.0, 0
     for line in open(path):
         parts = line.strip().split(",")
-        if len(parts) == 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") and kernel_tag in parts[1] \
-                and parts[2].endswith("MB per launch"):
+        if len(parts) == 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") \
+                and any(t in parts[1] for t in kernel_tags) and parts[2].endswith("MB per launch"):
             total += float(parts[2].split()[0]) * 1e6
             seen += 1
     return int(total) if seen else None
+
+
+# kernels one backward call launches (fused: one; long sequences: three)
+BWD_KERNELS = ("fused_bwd_kernel", "split_state_kernel", "split_q_kernel", "split_kv_kernel")
 
 
 def cpu_baseline(batch, budget_s=12.0):
@@ -260,7 +265,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(res["bwd_gbs"] / HBM_PEAK_GBS, 4),
-            "traffic": measured_traffic(w.name, "bwd_kernel"),
+            "traffic": measured_traffic(w.name, BWD_KERNELS),
             "launch_us": round(res["bwd_us"], 2),
             "algorithmic_bytes_per_launch": int(db.bytes_bwd),
             "forward": {"achieved": round(res["fwd_gbs"], 1), "frac": round(res["fwd_gbs"] / HBM_PEAK_GBS, 4),
