@@ -98,6 +98,8 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   hipError_t err;
   if (plan.path == cotten::Plan::kGeneric)
     err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
+  else if (plan.path == cotten::Plan::kResident)
+    err = bwd ? cotten::launch_resident_bwd(p) : cotten::launch_resident_fwd(p);
   else
     err = bwd ? cotten::launch_mfma_bwd(p, plan) : cotten::launch_mfma_fwd(p, plan);
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;

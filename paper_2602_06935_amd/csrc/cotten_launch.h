@@ -25,7 +25,8 @@ struct Problem {
 };
 
 // How a call is cut into workgroups.
-//   path        : kFused   one workgroup per slice runs every phase in one launch (no workspace)
+//   path        : kResident one 16-wave workgroup keeps a short slice in LDS (no workspace)
+//                 kFused   one workgroup per slice runs every phase in one launch (no workspace)
 //                 kSplit   MFMA kernels, `splits` workgroups per slice, states via the workspace
 //                 kGeneric vector-ALU kernels for shapes the MFMA kernels do not cover
 //   splits      : workgroups per slice in the state-reduction kernel; each reduces
@@ -35,7 +36,7 @@ struct Problem {
 //                 states [nstates][B*H][splits][D*D]; every consumer workgroup sums the
 //                 partials of its slice itself, in split order
 struct Plan {
-  enum Path { kGeneric = 0, kFused = 1, kSplit = 2 };
+  enum Path { kGeneric = 0, kFused = 1, kSplit = 2, kResident = 3 };
   Path path;
   int splits;
   int rows_per_split;
@@ -57,5 +58,10 @@ hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 bool mfma_supports(int dtype, int D);
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
+
+// Resident kernels: short sequences (N <= resident_max_rows()) of the same two formats.
+int resident_max_rows();
+hipError_t launch_resident_fwd(const Problem& p);
+hipError_t launch_resident_bwd(const Problem& p);
 
 }  // namespace cotten

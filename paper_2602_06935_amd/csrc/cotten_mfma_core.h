@@ -1,0 +1,612 @@
+// Device code shared by the MFMA kernels for 128-byte rows (bf16 d_h = 64, fp32 d_h = 32):
+// lane geometry, the two element formats with their MFMA products, tile loads through
+// buffer resources, staging into LDS tiles, and the scratch-tile epilogue helpers.
+#pragma once
+#include "cotten_device.h"
+
+namespace cotten {
+namespace mfma {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int TR = 16;               // rows per wave tile
+constexpr int kRowBytes = 128;       // one row of Q, K, V ... in global memory
+constexpr int kTileStride = 144;     // bytes per row of an LDS tile (128 + 16 of padding)
+constexpr int kTileBytes = TR * kTileStride;
+
+// Sum over the 8 consecutive lanes that share one row, by lane-permuting adds (no LDS).
+__device__ __forceinline__ float row_sum8(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // other quad of the 8
+  return x;
+}
+
+// 1/sqrt(ss + eps) for a live row (hardware reciprocal square root, about 1 ulp), 0 otherwise.
+__device__ __forceinline__ float inv_norm_or_zero(float ss, float eps, bool live) {
+  return live ? __builtin_amdgcn_rsqf(ss + eps) : 0.0f;
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2_t v;
+  v[0] = static_cast<__bf16>(lo);
+  v[1] = static_cast<__bf16>(hi);
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ f32x4_t quad(const f32x16_t& a, int j) {
+  return f32x4_t{a[4 * j], a[4 * j + 1], a[4 * j + 2], a[4 * j + 3]};
+}
+
+// Lane geometry shared by every pass.
+struct Lane {
+  int lane, wave;
+  int r8, ch;    // load layout: tile rows r8 and r8+8, bytes 16*ch .. 16*ch+15 of the row
+  int i16, g16;  // MFMA 16-lane groups: lane%16, lane/16
+  __device__ __forceinline__ Lane() {
+    set(threadIdx.x & 63);
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
+  }
+  // The same geometry, recomputed from scratch where it is used: in a long kernel this keeps
+  // the per-lane offsets derived from it from being carried (and spilled) across phases.
+  __device__ __forceinline__ Lane again() const {
+    Lane l = *this;
+    int id = lane;
+    asm volatile("" : "+v"(id));
+    l.set(id);
+    return l;
+  }
+  __device__ __forceinline__ void set(int id) {
+    lane = id;
+    r8 = lane >> 3;
+    ch = lane & 7;
+    i16 = lane & 15;
+    g16 = lane >> 4;
+  }
+};
+
+// ---- the two element formats ----------------------------------------------------------
+//
+// Common vocabulary of a format F:
+//   F::D                  head dimension;  F::EPL = D/8 elements per lane in the load layout
+//   F::unpack / F::pack   128-bit register group <-> EPL floats
+//   F::Acc                accumulators of one D x D state per wave, with mfma() and the
+//                         column-major image R[n*(D+4)+m] used for the cross-wave sum
+//   F::Operand            a D x D matrix W held in registers for apply products, loaded from
+//                         an LDS image op[n][k] (k contiguous); F::apply(tile, W, out)
+//   F::write_image        builds such images from a reduced state
+
+struct Bf16x64 {
+  typedef bf16 io_t;
+  static constexpr int D = 64, EPL = 8, NT = 4;
+  // tiles in flight ahead of the one being processed, per pass (register budget permitting)
+  static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 2, kDepthKV = 2, kDepthQAccum = 1;
+  static constexpr int kImageStride = 72;                 // elements per image row
+  static constexpr int kImageBytes = D * kImageStride * 2;
+  // Apply products leave lane (i16, g16) with the columns 32j + 8*g16 .. +7 (j = 0, 1) of tile
+  // row i16: value 4*nt + v of the lane is column out_col(nt, g16) + v.  Image row n (an
+  // output column of the product) is therefore kept at position image_row(n), which puts the
+  // 16 rows one MFMA operand needs next to each other.
+  static __device__ __forceinline__ int out_col(int nt, int g16) {
+    return 32 * (nt >> 1) + 8 * g16 + 4 * (nt & 1);
+  }
+  static __device__ __forceinline__ int image_row(int n) {
+    return 16 * (2 * (n >> 5) + ((n >> 2) & 1)) + 4 * ((n >> 3) & 3) + (n & 3);
+  }
+
+  static __device__ __forceinline__ void unpack(const u32x4_t r, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(r[i] << 16);
+      f[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ u32x4_t pack(const float (&f)[8]) {
+    u32x4_t r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    return r;
+  }
+
+  // Operand of the 32x32x16 MFMA for a contraction over the 16 tile rows: lane gets, for
+  // column cbase + lane%32, the 8 rows 8*(lane/32) .. +7 (two transposing reads of 4 rows).
+  static __device__ __forceinline__ bf16x8_t rows_operand(const unsigned char* T, const Lane& L,
+                                                          int cbase) {
+    const int s = L.i16;
+    const int row = 8 * (L.g16 >> 1) + (s >> 2);
+    const int col = cbase + 16 * (L.g16 & 1) + 4 * (s & 3);
+    typedef bf16x4_t __attribute__((address_space(3))) * lds_v4;
+    const unsigned char* p = T + row * kTileStride + col * 2;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p));
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p + 4 * kTileStride));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+
+  struct Acc {
+    f32x16_t v[2][2];  // [row block of 32][column block of 32]
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[a][c][i] = 0.0f;
+    }
+    // += (X tile)^T (Y tile)
+    __device__ __forceinline__ void mfma(const unsigned char* Xt, const unsigned char* Yt,
+                                         const Lane& L) {
+      bf16x8_t a[2], b[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        a[t] = rows_operand(Xt, L, 32 * t);
+        b[t] = rows_operand(Yt, L, 32 * t);
+      }
+#pragma unroll
+      for (int at = 0; at < 2; ++at)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+          v[at][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[at], b[ct], v[at][ct], 0, 0, 0);
+    }
+    // group g = 0..15 of four consecutive state rows held by this lane, and where it lives
+    __device__ __forceinline__ f32x4_t group(int g) const { return quad(v[g >> 3][(g >> 2) & 1], g & 3); }
+    static __device__ __forceinline__ int group_row(int g, const Lane& L) {
+      return 32 * (g >> 3) + 8 * (g & 3) + 4 * (L.lane >> 5);
+    }
+    static __device__ __forceinline__ int group_col(int g, const Lane& L) {
+      return 32 * ((g >> 2) & 1) + (L.lane & 31);
+    }
+    static constexpr int kGroups = 16;
+  };
+
+  struct Operand {
+    bf16x8_t frag[4][2];
+    __device__ __forceinline__ void load(const unsigned char* image, const Lane& L) {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          frag[nt][ks] = *reinterpret_cast<const bf16x8_t*>(
+              image + ((16 * nt + L.i16) * kImageStride + 8 * L.g16 + 32 * ks) * 2);
+    }
+  };
+
+  // The 16 rows of an LDS tile as the other operand of an apply product: lane (i16, g16)
+  // holds bytes 64j + 16*g16 .. +15 (j = 0, 1) of row i16, the same columns an apply product
+  // leaves it with, so a tile fetched this way also serves as the epilogue's row operand.
+  struct TileRows {
+    bf16x8_t a[2];
+    __device__ __forceinline__ void load(const unsigned char* T, const Lane& L) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        a[ks] = *reinterpret_cast<const bf16x8_t*>(T + L.i16 * kTileStride + (8 * L.g16 + 32 * ks) * 2);
+    }
+    __device__ __forceinline__ void unpack(float (&f)[16]) const {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        float h[8];
+        Bf16x64::unpack(__builtin_bit_cast(u32x4_t, a[ks]), h);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[8 * ks + i] = h[i];
+      }
+    }
+    // Makes the next unpack() a fresh computation, so that the 16 floats of the previous
+    // one need not stay in registers in between.
+    __device__ __forceinline__ void forget_unpacked() {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        u32x4_t r = __builtin_bit_cast(u32x4_t, a[ks]);
+        asm volatile("" : "+v"(r));
+        a[ks] = __builtin_bit_cast(bf16x8_t, r);
+      }
+    }
+  };
+  // (tile rows) x W, computed transposed (W^T X^T) so that each lane ends up with runs of
+  // neighbouring columns of one row: out[nt][v] = T[row i16][column out_col(nt, g16) + v]
+  static __device__ __forceinline__ void apply(const TileRows& X, const Operand& W,
+                                               f32x4_t (&out)[4]) {
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W.frag[nt][ks], X.a[ks], out[nt], 0, 0, 0);
+    }
+  }
+  static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
+                                               const Lane& L, f32x4_t (&out)[4]) {
+    TileRows X;
+    X.load(T, L);
+    apply(X, W, out);
+  }
+
+  // One 32x32 block of a state, accumulated by one wave over LDS-resident tiles
+  // (block = 0..3: rows 32*(block/2).., columns 32*(block%2)..), and its way into operand images.
+  struct BlockAcc {
+    static constexpr int kBlocks = 4;
+    f32x16_t v;
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = 0.0f;
+    }
+    struct Frag {
+      bf16x8_t a, b;
+    };
+    static __device__ __forceinline__ Frag fetch(const unsigned char* Xt, const unsigned char* Yt,
+                                                 const Lane& L, int block) {
+      Frag f;
+      f.a = rows_operand(Xt, L, 32 * (block >> 1));
+      f.b = rows_operand(Yt, L, 32 * (block & 1));
+      return f;
+    }
+    __device__ __forceinline__ void mma(const Frag& f) {
+      v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a, f.b, v, 0, 0, 0);
+    }
+    // natural[m][n] = transposed[n][m] = scale * state[m][n] for this block (either may be null)
+    __device__ __forceinline__ void write_images(const Lane& L, int block, float scale,
+                                                 unsigned char* natural,
+                                                 unsigned char* transposed) const {
+      const int n = 32 * (block & 1) + (L.lane & 31);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int m = 32 * (block >> 1) + 8 * j + 4 * (L.lane >> 5);
+        const uint32_t lo = pack_bf16(v[4 * j] * scale, v[4 * j + 1] * scale);
+        const uint32_t hi = pack_bf16(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
+        if (natural != nullptr) {
+          uint16_t* p = reinterpret_cast<uint16_t*>(natural) + image_row(m) * kImageStride + n;
+          p[0] = static_cast<uint16_t>(lo);
+          p[kImageStride] = static_cast<uint16_t>(lo >> 16);
+          p[2 * kImageStride] = static_cast<uint16_t>(hi);
+          p[3 * kImageStride] = static_cast<uint16_t>(hi >> 16);
+        }
+        if (transposed != nullptr) {
+          uint32_t* p = reinterpret_cast<uint32_t*>(transposed + (image_row(n) * kImageStride + m) * 2);
+          p[0] = lo;
+          p[1] = hi;
+        }
+      }
+    }
+  };
+
+  // two neighbouring image elements (k, k+1) of image row n
+  static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
+                                                          float v0, float v1) {
+    *reinterpret_cast<uint32_t*>(image + (image_row(n) * kImageStride + k) * 2) = pack_bf16(v0, v1);
+  }
+};
+
+struct F32x32 {
+  typedef float io_t;
+  static constexpr int D = 32, EPL = 4, NT = 2;
+  static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 3, kDepthKV = 2, kDepthQAccum = 2;
+  static constexpr int kImageStride = 36;
+  static constexpr int kImageBytes = D * kImageStride * 4;
+  // Apply products leave lane (i16, g16) with the columns 16j + 4*g16 .. +3 (j = 0, 1) of tile
+  // row i16 (value 4*nt + v is column out_col(nt, g16) + v); image rows stay in place.
+  static __device__ __forceinline__ int out_col(int nt, int g16) { return 16 * nt + 4 * g16; }
+  static __device__ __forceinline__ int image_row(int n) { return n; }
+
+  static __device__ __forceinline__ void unpack(const u32x4_t r, float (&f)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(r[i]);
+  }
+  static __device__ __forceinline__ u32x4_t pack(const float (&f)[4]) {
+    u32x4_t r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
+    return r;
+  }
+
+  struct Acc {
+    f32x16_t v;
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = 0.0f;
+    }
+    // += (X tile)^T (Y tile): 32x32x2 steps, lane = column, half-wave = row of the pair
+    __device__ __forceinline__ void mfma(const unsigned char* Xt, const unsigned char* Yt,
+                                         const Lane& L) {
+      const int off = (L.lane >> 5) * kTileStride + (L.lane & 31) * 4;
+      float a[8], b[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        a[s] = *reinterpret_cast<const float*>(Xt + off + 2 * s * kTileStride);
+        b[s] = *reinterpret_cast<const float*>(Yt + off + 2 * s * kTileStride);
+      }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) v = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s], v, 0, 0, 0);
+    }
+    __device__ __forceinline__ f32x4_t group(int g) const { return quad(v, g); }
+    static __device__ __forceinline__ int group_row(int g, const Lane& L) {
+      return 8 * g + 4 * (L.lane >> 5);
+    }
+    static __device__ __forceinline__ int group_col(int, const Lane& L) { return L.lane & 31; }
+    static constexpr int kGroups = 4;
+  };
+
+  // frag[nt][s] = W[k(s)][16*nt + i16], contraction step s taking column
+  // k(s) = 16*(s/4) + 4*g16 + s%4: the columns a TileRows lane holds.
+  struct Operand {
+    float frag[2][8];
+    __device__ __forceinline__ void load(const unsigned char* image, const Lane& L) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const f32x4_t* p = reinterpret_cast<const f32x4_t*>(
+            image + ((16 * nt + L.i16) * kImageStride + 4 * L.g16) * 4);
+        const f32x4_t lo = p[0], hi = p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          frag[nt][i] = lo[i];
+          frag[nt][4 + i] = hi[i];
+        }
+      }
+    }
+  };
+
+  // Lane (i16, g16) holds bytes 64j + 16*g16 .. +15 (j = 0, 1) of tile row i16: the columns
+  // an apply product leaves it with.
+  struct TileRows {
+    float a[8];
+    __device__ __forceinline__ void load(const unsigned char* T, const Lane& L) {
+      const f32x4_t* p = reinterpret_cast<const f32x4_t*>(T + L.i16 * kTileStride + 16 * L.g16);
+      const f32x4_t lo = p[0], hi = p[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = lo[i];
+        a[4 + i] = hi[i];
+      }
+    }
+    __device__ __forceinline__ void unpack(float (&f)[8]) const {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] = a[i];
+    }
+    __device__ __forceinline__ void forget_unpacked() {}
+  };
+  static __device__ __forceinline__ void apply(const TileRows& X, const Operand& W,
+                                               f32x4_t (&out)[2]) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(W.frag[nt][s], X.a[s], out[nt], 0, 0, 0);
+    }
+  }
+  static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
+                                               const Lane& L, f32x4_t (&out)[2]) {
+    TileRows X;
+    X.load(T, L);
+    apply(X, W, out);
+  }
+
+  // One 16x16 block of the 32x32 state, accumulated by one wave over LDS-resident tiles
+  // (block = 0..3: rows 16*(block/2).., columns 16*(block%2)..), and its way into operand images.
+  struct BlockAcc {
+    static constexpr int kBlocks = 4;
+    f32x4_t v;
+    __device__ __forceinline__ void zero() { v = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+    struct Frag {
+      float a[4], b[4];
+    };
+    static __device__ __forceinline__ Frag fetch(const unsigned char* Xt, const unsigned char* Yt,
+                                                 const Lane& L, int block) {
+      const int offx = L.g16 * kTileStride + (16 * (block >> 1) + L.i16) * 4;
+      const int offy = L.g16 * kTileStride + (16 * (block & 1) + L.i16) * 4;
+      Frag f;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        f.a[s] = *reinterpret_cast<const float*>(Xt + offx + 4 * s * kTileStride);
+        f.b[s] = *reinterpret_cast<const float*>(Yt + offy + 4 * s * kTileStride);
+      }
+      return f;
+    }
+    __device__ __forceinline__ void mma(const Frag& f) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        v = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[s], f.b[s], v, 0, 0, 0);
+    }
+    __device__ __forceinline__ void write_images(const Lane& L, int block, float scale,
+                                                 unsigned char* natural,
+                                                 unsigned char* transposed) const {
+      const int n = 16 * (block & 1) + L.i16;
+      const int m = 16 * (block >> 1) + 4 * L.g16;
+      const f32x4_t w = v * scale;
+      if (natural != nullptr) {
+        float* p = reinterpret_cast<float*>(natural) + m * kImageStride + n;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i * kImageStride] = w[i];
+      }
+      if (transposed != nullptr)
+        *reinterpret_cast<f32x4_t*>(transposed + (n * kImageStride + m) * 4) = w;
+    }
+  };
+
+  static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
+                                                          float v0, float v1) {
+    float* p = reinterpret_cast<float*>(image + (n * kImageStride + k) * 4);
+    p[0] = v0;
+    p[1] = v1;
+  }
+};
+
+// floats per row of an fp32 scratch tile (D columns + padding)
+template <class F>
+constexpr int scratch_stride() { return F::D + 4; }
+
+// ---- tiles --------------------------------------------------------------------------------
+
+// The tiles one workgroup walks: local tile lt = 0 .. n_tiles-1 is tile (tile0 + lt * stride)
+// of the slice, i.e. rows 16*(tile0 + lt*stride) .. +15.  A fused workgroup has stride 1; in
+// the split path the tiles of a slice are dealt round-robin to its `splits` workgroups, so
+// that padding (which sits at one end of the sequence) is shared evenly.  Rows >= limit do
+// not exist; `flags`, if given, is the LDS copy of the key mask: flags[16*lt + r].
+struct Rows {
+  int tile0, stride, n_tiles, limit;
+  const uint8_t* flags;
+  __device__ __forceinline__ int row0(int lt) const { return (tile0 + lt * stride) * TR; }
+};
+
+// Raw 16-row tile in the load layout: x[h], y[h] hold row r8 + 8h; `live` bit h says the
+// row takes part (in range and, where a mask applies, a valid key).
+struct Raw {
+  u32x4_t x[2], y[2];
+  int live;
+};
+
+// The two tensors a pass reads, as buffer resources over one slice each.  Buffer loads are
+// used instead of flat loads because a lane whose offset lies outside the buffer gets zeros
+// and causes no memory traffic: rows that do not take part are skipped without a branch, so
+// every tile issues the same number of load instructions and the hardware's in-order load
+// counter can tell "this tile has arrived" from "the tiles prefetched after it have not".
+struct Src {
+  __amdgpu_buffer_rsrc_t x, y;
+  __device__ __forceinline__ Src(const unsigned char* X, const unsigned char* Y, int N) {
+    const int bytes = N * kRowBytes;
+    x = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(X), 0, bytes, 0x00020000);
+    y = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Y), 0, bytes, 0x00020000);
+  }
+};
+constexpr uint32_t kOutOfBuffer = 0x80000000u;
+
+// Loads local tile lt (all zeros, and no traffic, if lt is not one of the workgroup's tiles).
+// A row takes part when it is below rows.limit and, if rows.flags is given, its flag is set.
+template <bool USE_Y>
+__device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const Src& src, const Rows& rows,
+                                         int lt) {
+  r.live = 0;
+  const bool tile_ok = lt < rows.n_tiles;
+  const int row0 = rows.row0(lt);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int row = row0 + L.r8 + 8 * h;
+    bool live = tile_ok && row < rows.limit;
+    if (rows.flags != nullptr) live = live && rows.flags[tile_ok ? lt * TR + L.r8 + 8 * h : 0] != 0;
+    const uint32_t off = live ? static_cast<uint32_t>(row) * kRowBytes + L.ch * 16 : kOutOfBuffer;
+    r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
+    if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
+    else r.y[h] = u32x4_t{0, 0, 0, 0};
+    r.live |= static_cast<int>(live) << h;
+  }
+}
+
+// What becomes of the x rows on their way to the LDS tile.
+enum XMode { kXNone = 0, kXRaw = 1, kXNormalized = 2 };
+
+// inv[h] = 1/r of row h (0 for rows that do not take part; their registers are zero).
+// Xt receives nothing, the raw rows, or xhat; Yt the raw y rows.
+template <class F, int XMODE, bool USE_Y>
+__device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, unsigned char* Xt,
+                                      unsigned char* Yt, float (&inv)[2]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float f[F::EPL];
+    F::unpack(r.x[h], f);
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < F::EPL; ++i) ss += f[i] * f[i];
+    inv[h] = inv_norm_or_zero(row_sum8(ss), eps, (r.live >> h) & 1);
+    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+    if (XMODE == kXNormalized) {
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) f[i] *= inv[h];
+      *reinterpret_cast<u32x4_t*>(Xt + off) = F::pack(f);
+    } else if (XMODE == kXRaw) {
+      *reinterpret_cast<u32x4_t*>(Xt + off) = r.x[h];
+    }
+    if (USE_Y) *reinterpret_cast<u32x4_t*>(Yt + off) = r.y[h];
+  }
+}
+
+// Apply result -> scratch tile: row i16, columns out_col(nt, g16) .. +3 (one 128-bit write)
+template <class F>
+__device__ __forceinline__ void to_scratch(const f32x4_t (&out)[F::NT], float* Sc, const Lane& L) {
+#pragma unroll
+  for (int nt = 0; nt < F::NT; ++nt)
+    *reinterpret_cast<f32x4_t*>(Sc + L.i16 * scratch_stride<F>() + F::out_col(nt, L.g16)) = out[nt];
+}
+
+// scratch tile -> load layout: the EPL columns of row r8 + 8h this lane owns
+template <class F>
+__device__ __forceinline__ void from_scratch(const float* Sc, const Lane& L, int h,
+                                             float (&f)[F::EPL]) {
+  const f32x4_t* p = reinterpret_cast<const f32x4_t*>(
+      Sc + (L.r8 + 8 * h) * scratch_stride<F>() + F::EPL * L.ch);
+#pragma unroll
+  for (int q = 0; q < F::EPL / 4; ++q) {
+    const f32x4_t a = p[q];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[4 * q + i] = a[i];
+  }
+}
+
+template <class F>
+__device__ __forceinline__ void store_row(unsigned char* __restrict__ dst, int row, const Lane& L,
+                                          const float (&f)[F::EPL]) {
+  *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 16 * L.ch) = F::pack(f);
+}
+
+// ---- epilogues in the product layout ------------------------------------------------------
+// An apply product leaves lane (i16, g16) with 2*EPL values of tile row i16: the two 16-byte
+// pieces of the row at bytes 64j + 16*g16.  TileRows::unpack gives any LDS tile in the same
+// arrangement, so row-wise epilogues need no detour through an fp32 scratch tile.
+
+template <class F>
+__device__ __forceinline__ void product_rows(const f32x4_t (&out)[F::NT], float (&p)[2 * F::EPL]) {
+  static_assert(4 * F::NT == 2 * F::EPL, "an apply product covers one row");
+#pragma unroll
+  for (int nt = 0; nt < F::NT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) p[4 * nt + v] = out[nt][v];
+}
+
+// Sum over the four lanes (i16, 0..3) that share a row.
+__device__ __forceinline__ float row_sum_groups(float x, const Lane& L) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((L.lane ^ 16) << 2, __builtin_bit_cast(int, x)));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((L.lane ^ 32) << 2, __builtin_bit_cast(int, x)));
+  return x;
+}
+
+// p <- (p - u (u.p)) / r for the lane's row, u being the unit row held in `e`: the tangent
+// projection shared by dQ (u = qhat, p = g) and dK (u = khat, p = h).
+template <class F>
+__device__ __forceinline__ void project_rows(float (&p)[2 * F::EPL], typename F::TileRows& e,
+                                             float inv_r, const Lane& L) {
+  float proj = 0.0f;
+  {
+    float u[2 * F::EPL];
+    e.unpack(u);
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * p[c];
+  }
+  proj = row_sum_groups(proj, L);
+  e.forget_unpacked();
+  float u[2 * F::EPL];
+  e.unpack(u);
+#pragma unroll
+  for (int c = 0; c < 2 * F::EPL; ++c) p[c] = (p[c] - u[c] * proj) * inv_r;
+}
+
+template <class F>
+__device__ __forceinline__ void store_product_row(unsigned char* __restrict__ dst, int row,
+                                                  const Lane& L, const float (&p)[2 * F::EPL]) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    float c[F::EPL];
+#pragma unroll
+    for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];
+    *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 64 * j + 16 * L.g16) =
+        F::pack(c);
+  }
+}
+
+}  // namespace mfma
+}  // namespace cotten
