@@ -1,19 +1,16 @@
 // Resident kernels for short sequences (N <= 208) with 128-byte rows.
 //
-// One workgroup of 16 waves owns one slice and keeps it in LDS: wave w loads, stages and
-// later finishes the 16-row tile w, so every global load of the slice is issued at once and
-// nothing is read twice.  Between staging and the apply phase the d x d states are built by
-// one wave per output block, each walking all resident tiles (no cross-wave reduction):
+// One persistent workgroup of 16 waves owns one slice at a time and keeps it in LDS: wave w
+// loads and stages the 16-row tile w, so every global load of the slice is issued at once and
+// nothing is read twice; the loads of the workgroup's next slice are issued as soon as the
+// registers are free and travel while the current slice is worked on.  The d x d states are
+// built by one wave per output block, each walking all resident tiles (no cross-wave
+// reduction), and handed on as MFMA operand images in LDS.  Apply products are shared out
+// over the waves by tile; their epilogue runs in the layout the product comes out in, next to
+// the tile rows fetched from LDS in that same layout, and ends in 128-bit stores.
 //
-//   load     mask bytes and (Q[,dO]) tile, then (K,V) tile with masked rows skipped
-//   stage    khat, v, qhat (bwd) or q (fwd), dO  ->  LDS block of the tile;  1/r kept in registers
-//   barrier
-//   states   4 waves: S blocks;  backward: 4 more waves: dS blocks;  results -> operand images
-//   barrier
-//   apply    forward: wave w finishes tile w.  Backward: four waves per product (dQ, dV, dK)
-//            share out the tiles, so an operand image is fetched once per three or four tiles.  The
-//            epilogue runs in the layout the product comes out in, next to the tile rows
-//            fetched from LDS in that same layout, and ends in 128-bit stores.
+//   forward    stage K, V, Q | barrier | 4 waves: S | barrier | wave w: O rows of tile w
+//   backward   see resident_bwd_kernel (dS is built while dQ is applied)
 #include "cotten_launch.h"
 #include "cotten_mfma_core.h"
 
@@ -102,19 +99,25 @@ __device__ __forceinline__ int key_rows(const Args& a, const Lane& L, int slice,
 }
 
 // Issues the loads of the wave's tile of `slice` (none, at no cost, if the slice or the tile
-// does not exist).  Rows of K and V that are not valid keys are not read.
-template <bool BWD>
+// does not exist): PARTS bit 0 = K and V, of which rows that are not valid keys are not read;
+// bit 1 = Q (and dO).
+template <bool BWD, int PARTS = 3>
 __device__ __forceinline__ void fetch(Raw& rq, Raw& rk, const Args& a, const Lane& L, int slice,
                                       int tile, int keys) {
   const bool ok = slice < a.slices;
   const size_t base = ok ? static_cast<size_t>(slice) * a.N * kRowBytes : 0;
-  const Src q_src(a.Q + base, (BWD ? a.dO : a.Q) + base, a.N), kv_src(a.K + base, a.V + base, a.N);
   int rows = 0;
 #pragma unroll
   for (int h = 0; h < 2; ++h)
     rows |= static_cast<int>(ok && tile * TR + L.r8 + 8 * h < a.N) << h;
-  load_tile<BWD>(rq, L, q_src, tile, rows);
-  load_tile<true>(rk, L, kv_src, tile, rows & keys);
+  if (PARTS & 1) {
+    const Src kv_src(a.K + base, a.V + base, a.N);
+    load_tile<true>(rk, L, kv_src, tile, rows & keys);
+  }
+  if (PARTS & 2) {
+    const Src q_src(a.Q + base, (BWD ? a.dO : a.Q) + base, a.N);
+    load_tile<BWD>(rq, L, q_src, tile, rows);
+  }
 }
 
 // 1/r of the 16 tile rows, from the load layout to where any wave can pick them up by row.
@@ -125,36 +128,31 @@ __device__ __forceinline__ void publish_inv(float* dst, const Lane& L, const flo
   }
 }
 
-// Bit t set: tile t holds a valid key.
-__device__ __forceinline__ uint64_t live_tiles(const Lane& L, const int* live, int n_tiles) {
-  const int lv = L.lane < n_tiles ? live[L.lane] : 0;
-  return __ballot(lv != 0);
-}
-
-// One wave per state block: walks the given resident tiles (bit set), fetching the next
-// tile's operands while the matrix core works on the current one, then writes its block into
-// the images.
+// One wave per state block: walks all kMaxTiles resident tiles in straight-line code (so
+// that the LDS reads of later tiles overlap the matrix-core work on earlier ones) and then
+// writes its block into the images.  Tiles that contribute nothing must hold zeros.
 template <class F>
-__device__ __forceinline__ void build_state(const Lane& L, int block, uint64_t tiles, int x_off,
-                                            int y_off, float scale, unsigned char* natural,
+__device__ __forceinline__ void build_state(const Lane& L, int block, int x_off, int y_off,
+                                            float scale, unsigned char* natural,
                                             unsigned char* transposed) {
-  typedef typename F::BlockAcc Acc;
-  Acc acc;
+  typename F::BlockAcc acc;
   acc.zero();
-  if (tiles != 0) {
-    const unsigned char* blk = smem + __builtin_ctzll(tiles) * kBlockBytes;
-    tiles &= tiles - 1;
-    typename Acc::Frag cur = Acc::fetch(blk + x_off, blk + y_off, L, block);
-    while (tiles != 0) {
-      blk = smem + __builtin_ctzll(tiles) * kBlockBytes;
-      tiles &= tiles - 1;
-      const typename Acc::Frag nxt = Acc::fetch(blk + x_off, blk + y_off, L, block);
-      acc.mma(cur);
-      cur = nxt;
-    }
-    acc.mma(cur);
+#pragma unroll
+  for (int t = 0; t < kMaxTiles; ++t) {
+    const unsigned char* blk = smem + t * kBlockBytes;
+    acc.mma(F::BlockAcc::fetch(blk + x_off, blk + y_off, L, block));
   }
   acc.write_images(L, block, scale, natural, transposed);
+}
+
+// Zero rows for the two tiles at Xt and Yt.
+__device__ __forceinline__ void clear_tiles(const Lane& L, unsigned char* Xt, unsigned char* Yt) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+    *reinterpret_cast<u32x4_t*>(Xt + off) = u32x4_t{0, 0, 0, 0};
+    *reinterpret_cast<u32x4_t*>(Yt + off) = u32x4_t{0, 0, 0, 0};
+  }
 }
 
 // Both kernels are persistent: a workgroup takes slices blockIdx.x, blockIdx.x + gridDim.x, ...
@@ -168,33 +166,50 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
   const int n_tiles = (N + TR - 1) / TR;
   unsigned char* blk = smem + tile * kBlockBytes;
   unsigned char* img = smem + Lds<F>::kImages;
-  int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
   float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv) + tile * 2 * TR;
   const bool mine = tile < n_tiles;
+  if (!mine && tile < kMaxTiles) {  // absent tiles stay zero for the whole kernel
+    clear_tiles(L0, blk + kKt, blk + kVt);
+    clear_tiles(L0, blk + kQt, blk + kGt);
+  }
 
   int slice = blockIdx.x;
   Raw rq, rk;
-  fetch<false>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  // The first slice: Q does not have to wait for the mask bytes that select the K, V rows.
+  fetch<false, 2>(rq, rk, a, L0, slice, tile, 0);
+  fetch<false, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
+  // Per slice (B = workgroup barrier):
+  //   1  tile waves stage K, V                                                       B
+  //   2  waves 12-15 build S (at raised priority: everyone waits for it); tile waves
+  //      stage Q and issue the loads of the next slice                               B
+  //   3  wave w finishes the O rows of tile w (phase 1 of the next slice may start at once:
+  //      it writes only the K, V tiles, which nobody reads any more)
   for (; slice < a.slices; slice += stride) {
     if (mine) {
       const Lane L = L0.again();
       float inv[2];
-      const bool any_key = __ballot(rk.live != 0) != 0;
-      if (any_key) stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
-      if (L.lane == 0) live[tile] = any_key;
-      stage<F, kXRaw, false>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
-      publish_inv(invs, L, inv);
+      if (__ballot(rk.live != 0) != 0)
+        stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
+      else
+        clear_tiles(L, blk + kKt, blk + kVt);
     }
     __syncthreads();
     {
       const Lane L = L0.again();
-      fetch<false>(rq, rk, a, L, slice + stride, tile, keys);
-      keys = key_rows(a, L, slice + 2 * stride, tile);
-    }
-    if (tile < F::BlockAcc::kBlocks) {  // O = qhat S: contraction over rows of S -> transposed image
-      const Lane L = L0.again();
-      build_state<F>(L, tile, live_tiles(L, live, n_tiles), kKt, kVt, a.scale, nullptr, img);
+      constexpr int kB = F::BlockAcc::kBlocks;
+      if (tile >= kWaves - kB) {  // O = qhat S: contraction over rows of S -> transposed image
+        __builtin_amdgcn_s_setprio(3);
+        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, a.scale, nullptr, img);
+        __builtin_amdgcn_s_setprio(0);
+      }
+      if (mine) {
+        float inv[2];
+        stage<F, kXRaw, false>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
+        publish_inv(invs, L, inv);
+        fetch<false>(rq, rk, a, L, slice + stride, tile, keys);
+        keys = key_rows(a, L, slice + 2 * stride, tile);
+      }
     }
     __syncthreads();
     if (mine) {
@@ -214,14 +229,48 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       if (row < N)
         store_product_row<F>(a.O + static_cast<size_t>(slice) * N * kRowBytes, row, L, o);
     }
-    __syncthreads();  // the tiles and images are rewritten for the next slice
   }
 }
 
-// Backward apply phase: wave w < 12 takes product w % 3 and every fourth tile from w / 3 on, so
-// that each SIMD (waves w, w+4, w+8) gets one wave of each product.
-constexpr int kProducts = 3, kWavesPerProduct = 4;
+// One tile of an apply product, finished and stored:
+//   kind 0  dQ = (g - qhat (qhat.g)) / r_q,  g = dO W      (W = scale * S, natural image)
+//   kind 1  dV = khat W                                     (W = scale * dS, transposed image;
+//                                                            khat is zero on masked rows)
+//   kind 2  dK = (h - khat (khat.h)) / r_k,  h = v W       (W = scale * dS, natural image;
+//                                                            1/r_k is zero on masked rows)
+// Tiles without a valid key get zero rows of dK and dV without touching LDS.
+template <class F>
+__device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N,
+                                           const typename F::Operand& W, const int* live,
+                                           const float* invs, unsigned char* dst) {
+  const unsigned char* tb = smem + t * kBlockBytes;
+  const int row = t * TR + L.i16;
+  float p[2 * F::EPL];
+  if (kind != 0 && live[t] == 0) {
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) p[c] = 0.0f;
+  } else {
+    typename F::TileRows x;
+    x.load(tb + (kind == 0 ? kGt : kind == 1 ? kKt : kVt), L);
+    f32x4_t out[F::NT];
+    F::apply(x, W, out);
+    product_rows<F>(out, p);
+    if (kind != 1) {
+      typename F::TileRows e;
+      e.load(tb + (kind == 0 ? kQt : kKt), L);
+      project_rows<F>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
+    }
+  }
+  if (row < N) store_product_row<F>(dst, row, L, p);
+}
 
+// Backward, per slice (B = workgroup barrier):
+//   1  tile waves stage K, V                                                        B
+//   2  waves 12-15 build S (one block each, at raised priority: everyone waits for it);
+//      tile waves stage Q, dO and issue the loads of the next slice                 B
+//   3  waves 12-15 build dS;  waves 0-11 apply dQ (tiles w, w+12), which needs only S B
+//   4  all waves apply dV and dK: waves 2i, 2i+1 take tiles i and i+8, one product
+//      each, alternating so that every SIMD gets both kinds                         B
 template <class F>
 __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   const Lane L0;
@@ -234,35 +283,34 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
   float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv);
   const bool mine = tile < n_tiles;
-
-  // product 0: dQ = (g - qhat (qhat.g)) / r_q,  g = scale * dO S^T
-  // product 1: dV = khat (scale * dS)             (khat is zero on masked rows)
-  // product 2: dK = (h - khat (khat.h)) / r_k,  h = v (scale * dS)^T   (1/r_k = 0 on masked rows)
-  const int product = tile < kProducts * kWavesPerProduct ? tile % kProducts : kProducts;
-  const int x_off = product == 0 ? kGt : product == 1 ? kKt : kVt;
-  const int e_off = product == 0 ? kQt : kKt;
-  unsigned char* const dst0 = product == 0 ? a.dQ : product == 1 ? a.dV : a.dK;
-  const unsigned char* const image = product == 0 ? img_s : product == 1 ? img_dst : img_ds;
-  const float* inv_base = invs + (product == 0 ? 0 : TR);
+  if (!mine && tile < kMaxTiles) {  // absent tiles stay zero for the whole kernel
+    clear_tiles(L0, blk + kKt, blk + kVt);
+    clear_tiles(L0, blk + kQt, blk + kGt);
+  }
+  constexpr int kB = F::BlockAcc::kBlocks;
+  static_assert(kB == 4 && kWaves == 16 && kMaxTiles <= 16, "wave roles below");
+  const int kv_kind = 1 + (((tile >> 2) + tile) & 1);  // phase 4: dV or dK
 
   int slice = blockIdx.x;
   Raw rq, rk;
   COTTEN_RTRACE(0);
-  fetch<true>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  // The first slice: Q and dO do not have to wait for the mask bytes that select the K, V rows.
+  fetch<true, 2>(rq, rk, a, L0, slice, tile, 0);
+  fetch<true, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
+    const size_t base = static_cast<size_t>(slice) * N * kRowBytes;
     COTTEN_RTRACE_IT(1);
     if (mine) {
+      // A tile without a valid key adds nothing to S, and its dK, dV rows are plain zeros.
       const Lane L = L0.again();
-      float inv[2];
-      stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
-      publish_inv(invs + tile * 2 * TR, L, inv);
-      // A tile without a valid key is never read again: the states skip it and its dK, dV
-      // rows are plain zeros.
       const bool any_key = __ballot(rk.live != 0) != 0;
       if (any_key) {
+        float inv[2];
         stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
         publish_inv(invs + tile * 2 * TR + TR, L, inv);
+      } else {
+        clear_tiles(L, blk + kKt, blk + kVt);
       }
       if (L.lane == 0) live[tile] = any_key;
     }
@@ -271,53 +319,48 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
     COTTEN_RTRACE_IT(3);
     {
       const Lane L = L0.again();
-      fetch<true>(rq, rk, a, L, slice + stride, tile, keys);
-      keys = key_rows(a, L, slice + 2 * stride, tile);
-    }
-    constexpr int kB = F::BlockAcc::kBlocks;
-    if (tile < 2 * kB) {
-      const Lane L = L0.again();
-      if (tile < kB)  // g = dO S^T: contraction over columns of S -> natural image
-        build_state<F>(L, tile, live_tiles(L, live, n_tiles), kKt, kVt, a.scale, img_s, nullptr);
-      else            // dV = khat dS -> transposed image;  h = v dS^T -> natural image
-        build_state<F>(L, tile - kB, (1ull << n_tiles) - 1, kQt, kGt, a.scale, img_ds, img_dst);
+      if (tile >= kWaves - kB) {  // g = dO S^T: contraction over columns of S -> natural image
+        __builtin_amdgcn_s_setprio(3);  // the other waves wait for this at the next barrier
+        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, a.scale, img_s, nullptr);
+        __builtin_amdgcn_s_setprio(0);
+      }
+      if (mine) {
+        float inv[2];
+        stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
+        publish_inv(invs + tile * 2 * TR, L, inv);
+        fetch<true>(rq, rk, a, L, slice + stride, tile, keys);
+        keys = key_rows(a, L, slice + 2 * stride, tile);
+      }
     }
     COTTEN_RTRACE_IT(4);
     __syncthreads();
     COTTEN_RTRACE_IT(5);
-    if (product < kProducts) {
+    if (tile >= kWaves - kB) {
+      // dV = khat dS -> transposed image;  h = v dS^T -> natural image
       const Lane L = L0.again();
-      unsigned char* dst = dst0 + static_cast<size_t>(slice) * N * kRowBytes;
+      __builtin_amdgcn_s_setprio(3);
+      build_state<F>(L, tile - (kWaves - kB), kQt, kGt, a.scale, img_ds, img_dst);
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      const Lane L = L0.again();
       typename F::Operand W;
-      W.load(image, L);
+      W.load(img_s, L);
 #pragma unroll 1
-      for (int t = tile / kProducts; t < n_tiles; t += kWavesPerProduct) {
-        const unsigned char* tb = smem + t * kBlockBytes;
-        const int row = t * TR + L.i16;
-        if (product != 0 && live[t] == 0) {  // no valid key in the tile: dK = dV = 0
-          float zeros[2 * F::EPL];
-#pragma unroll
-          for (int c = 0; c < 2 * F::EPL; ++c) zeros[c] = 0.0f;
-          if (row < N) store_product_row<F>(dst, row, L, zeros);
-          continue;
-        }
-        typename F::TileRows x;
-        x.load(tb + x_off, L);
-        f32x4_t out[F::NT];
-        F::apply(x, W, out);
-        float p[2 * F::EPL];
-        product_rows<F>(out, p);
-        if (product != 1) {
-          typename F::TileRows e;
-          e.load(tb + e_off, L);
-          project_rows<F>(p, e, inv_base[t * 2 * TR + L.i16], L);
-        }
-        if (row < N) store_product_row<F>(dst, row, L, p);
-      }
+      for (int t = tile; t < n_tiles; t += kWaves - kB)
+        apply_tile<F>(L, 0, t, N, W, live, invs, a.dQ + base);
     }
     COTTEN_RTRACE_IT(6);
-    __syncthreads();  // the tiles and images are rewritten for the next slice
+    __syncthreads();
     COTTEN_RTRACE_IT(7);
+    {
+      const Lane L = L0.again();
+      typename F::Operand W;
+      W.load(kv_kind == 1 ? img_dst : img_ds, L);
+      unsigned char* dst = (kv_kind == 1 ? a.dV : a.dK) + base;
+#pragma unroll 1
+      for (int t = tile >> 1; t < n_tiles; t += kWaves / 2) apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst);
+    }
+    __syncthreads();  // the tiles and images are rewritten for the next slice
   }
 }
 
