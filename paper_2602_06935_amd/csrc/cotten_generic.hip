@@ -367,7 +367,7 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
     // cut the sequence so that about 256 workgroups exist (one per compute unit: measured best,
     // the fixed cost per workgroup outweighs the extra overlap of a second one), in blocks of 64 rows.
     constexpr long kFusedMaxN = 2048, kBlock = 64;
-    if (N <= resident_max_rows()) {
+    if (resident_supports(dtype, D, N)) {
       plan.path = Plan::kResident;
       plan.splits = 1;
       plan.rows_per_split = N;

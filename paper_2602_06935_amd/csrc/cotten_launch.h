@@ -59,8 +59,10 @@ bool mfma_supports(int dtype, int D);
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 
-// Resident kernels: short sequences (N <= resident_max_rows()) of the same two formats.
-int resident_max_rows();
+// Resident kernels: short bf16 sequences (a slice fits the LDS of one compute unit).  With
+// fp32 rows the matrix cores, 16 times slower there, bound each of their phases and the
+// tile-streaming kernels are faster, so those keep all fp32 shapes.
+bool resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_fwd(const Problem& p);
 hipError_t launch_resident_bwd(const Problem& p);
 

@@ -11,9 +11,10 @@
 //   apply products  T = X W        (contraction over columns; X raw, the 1/r of each row is
 //                   applied to the result; W held in registers)
 //                   bf16: 16x16x32 MFMA      fp32: 16x16x4 MFMA
-// Products come back through a wave-private fp32 scratch tile into the load layout,
-// where the epilogue (projection off the normalised row, 1/r, masking) runs in fp32
-// next to the unrounded inputs and results leave with 128-bit stores.
+// Products are computed transposed, which leaves every lane with runs of neighbouring
+// columns of one tile row; the epilogue (projection off the unit row, 1/r, masking) runs in
+// fp32 in that layout, next to the tile rows fetched from LDS in the same arrangement, and
+// results leave with 128-bit stores.
 //
 // Fused kernels (one workgroup = 4 waves per slice) run all phases in one launch;
 // split kernels cut long sequences over several workgroups per slice and pass
@@ -51,9 +52,7 @@ constexpr int kThreads = 64 * kWaves;
 template <class F>
 struct Layout {
   static constexpr int D = F::D;
-  static constexpr int kScratchStride = scratch_stride<F>();           // floats
-  static constexpr int kScratchBytes = TR * kScratchStride * 4;
-  static constexpr int kWaveBytes = 2 * kTileBytes + 2 * kScratchBytes;
+  static constexpr int kWaveBytes = 2 * kTileBytes + TR * 4;           // two tiles, 1/r per row
   static constexpr int kRStride = D + 4;                              // floats, column-major
   static constexpr int kRFloats = D * kRStride;
   static constexpr int kWorkBytes =
@@ -67,14 +66,12 @@ template <class F>
 struct WaveLds {
   unsigned char* Xt;
   unsigned char* Yt;
-  float* Sc0;
-  float* Sc1;
+  float* inv;
   __device__ __forceinline__ WaveLds(unsigned char* smem, int wave) {
     unsigned char* base = smem + wave * Layout<F>::kWaveBytes;
     Xt = base;
     Yt = base + kTileBytes;
-    Sc0 = reinterpret_cast<float*>(base + 2 * kTileBytes);
-    Sc1 = reinterpret_cast<float*>(base + 2 * kTileBytes + Layout<F>::kScratchBytes);
+    inv = reinterpret_cast<float*>(base + 2 * kTileBytes);
   }
 };
 
@@ -137,6 +134,18 @@ __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
   });
 }
 
+// The 1/r of the tile's 16 rows, handed from the load layout to the product layout.
+template <class F>
+__device__ __forceinline__ float inv_by_row(const WaveLds<F>& W, const Lane& L,
+                                            const float (&inv)[2]) {
+  if (L.ch == 0) {
+    W.inv[L.r8] = inv[0];
+    W.inv[L.r8 + 8] = inv[1];
+  }
+  wave_lds_fence();
+  return W.inv[L.i16];
+}
+
 // O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
 template <class F, int DEPTH>
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
@@ -146,19 +155,17 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
   for_each_tile<false, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
     stage<F, kXRaw, false>(r, L, eps, W.Xt, W.Yt, inv);
-    wave_lds_fence();
+    const float inv_r = inv_by_row(W, L, inv);
+    typename F::TileRows x;
+    x.load(W.Xt, L);
     f32x4_t out[F::NT];
-    F::apply(W.Xt, Sop, L, out);
-    to_scratch<F>(out, W.Sc0, L);
-    wave_lds_fence();
+    F::apply(x, Sop, out);
+    float o[2 * F::EPL];
+    product_rows<F>(out, o);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      float o[F::EPL];
-      from_scratch<F>(W.Sc0, L, h, o);
-#pragma unroll
-      for (int i = 0; i < F::EPL; ++i) o[i] *= inv[h];
-      if ((r.live >> h) & 1) store_row<F>(O, row0 + L.r8 + 8 * h, L, o);
-    }
+    for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
+    const int row = row0 + L.i16;
+    if (row < rows.limit) store_product_row<F>(O, row, L, o);
     wave_lds_fence();
   });
 }
@@ -177,35 +184,25 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
   if (kHold) held.load(Simage, L);
   for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
-    stage<F, ACCUM ? kXNormalized : kXNone, true>(r, L, eps, W.Xt, W.Yt, inv);
-    wave_lds_fence();
+    stage<F, kXNormalized, true>(r, L, eps, W.Xt, W.Yt, inv);
+    const float inv_r = inv_by_row(W, L, inv);
     if (ACCUM) dsacc.mfma(W.Xt, W.Yt, L);
+    typename F::TileRows x, e;
+    x.load(W.Yt, L);
+    e.load(W.Xt, L);
     f32x4_t out[F::NT];
     if (kHold) {
-      F::apply(W.Yt, held, L, out);  // g = scale * dO S^T
+      F::apply(x, held, out);  // g = scale * dO S^T
     } else {
       typename F::Operand fresh;
       fresh.load(Simage, L);
-      F::apply(W.Yt, fresh, L, out);
+      F::apply(x, fresh, out);
     }
-    to_scratch<F>(out, W.Sc0, L);
-    wave_lds_fence();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      float g[F::EPL], q[F::EPL];
-      from_scratch<F>(W.Sc0, L, h, g);
-      F::unpack(r.x[h], q);
-      float proj = 0.0f;
-#pragma unroll
-      for (int i = 0; i < F::EPL; ++i) {
-        q[i] *= inv[h];
-        proj += q[i] * g[i];
-      }
-      proj = row_sum8(proj);
-#pragma unroll
-      for (int i = 0; i < F::EPL; ++i) g[i] = (g[i] - q[i] * proj) * inv[h];
-      if ((r.live >> h) & 1) store_row<F>(dQ, row0 + L.r8 + 8 * h, L, g);
-    }
+    float g[2 * F::EPL];
+    product_rows<F>(out, g);
+    project_rows<F, false>(g, e, inv_r, L);
+    const int row = row0 + L.i16;
+    if (row < rows.limit) store_product_row<F>(dQ, row, L, g);
     wave_lds_fence();
   });
 }
@@ -220,52 +217,36 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
                                             const typename F::Operand& dSop_v,
                                             const typename F::Operand& dSop_h) {
   for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
+    const int row = row0 + L.i16;
     if (__ballot(r.live != 0) == 0) {  // nothing live: only the zero rows are due
-      float zeros[F::EPL];
+      float zeros[2 * F::EPL];
 #pragma unroll
-      for (int i = 0; i < F::EPL; ++i) zeros[i] = 0.0f;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int row = row0 + L.r8 + 8 * h;
-        if (row < rows.limit) {
-          store_row<F>(dK, row, L, zeros);
-          store_row<F>(dV, row, L, zeros);
-        }
+      for (int i = 0; i < 2 * F::EPL; ++i) zeros[i] = 0.0f;
+      if (row < rows.limit) {
+        store_product_row<F>(dK, row, L, zeros);
+        store_product_row<F>(dV, row, L, zeros);
       }
       return;
     }
     float inv[2];
     stage<F, kXRaw, true>(r, L, eps, W.Xt, W.Yt, inv);
-    wave_lds_fence();
+    // 1/r = 0 on masked rows, whose k and v registers are zero: dK and dV come out as exact zeros
+    const float inv_r = inv_by_row(W, L, inv);
+    typename F::TileRows xk, xv;
+    xk.load(W.Xt, L);
+    xv.load(W.Yt, L);
     f32x4_t out[F::NT];
-    F::apply(W.Xt, dSop_v, L, out);
-    to_scratch<F>(out, W.Sc0, L);
-    F::apply(W.Yt, dSop_h, L, out);
-    to_scratch<F>(out, W.Sc1, L);
-    wave_lds_fence();
+    float gv[2 * F::EPL], hh[2 * F::EPL];
+    F::apply(xk, dSop_v, out);
+    product_rows<F>(out, gv);
+    F::apply(xv, dSop_h, out);
+    product_rows<F>(out, hh);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int row = row0 + L.r8 + 8 * h;
-      float gv[F::EPL], hh[F::EPL], k[F::EPL];
-      from_scratch<F>(W.Sc0, L, h, gv);
-      from_scratch<F>(W.Sc1, L, h, hh);
-      F::unpack(r.x[h], k);
-      float proj = 0.0f;
-#pragma unroll
-      for (int i = 0; i < F::EPL; ++i) {
-        k[i] *= inv[h];  // inv = 0 on masked rows: khat, dK and dV come out as exact zeros
-        proj += k[i] * hh[i];
-      }
-      proj = row_sum8(proj);
-#pragma unroll
-      for (int i = 0; i < F::EPL; ++i) {
-        hh[i] = (hh[i] - k[i] * proj) * inv[h];
-        gv[i] *= inv[h];
-      }
-      if (row < rows.limit) {
-        store_row<F>(dK, row, L, hh);
-        store_row<F>(dV, row, L, gv);
-      }
+    for (int i = 0; i < 2 * F::EPL; ++i) gv[i] *= inv_r;
+    project_rows_raw<F>(hh, xk, inv_r, L);
+    if (row < rows.limit) {
+      store_product_row<F>(dK, row, L, hh);
+      store_product_row<F>(dV, row, L, gv);
     }
     wave_lds_fence();
   });

@@ -1,6 +1,6 @@
 // Device code shared by the MFMA kernels for 128-byte rows (bf16 d_h = 64, fp32 d_h = 32):
 // lane geometry, the two element formats with their MFMA products, tile loads through
-// buffer resources, staging into LDS tiles, and the scratch-tile epilogue helpers.
+// buffer resources, staging into LDS tiles, and the epilogue helpers.
 #pragma once
 #include "cotten_device.h"
 
@@ -251,30 +251,27 @@ struct Bf16x64 {
     __device__ __forceinline__ void mma(const Frag& f) {
       v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a, f.b, v, 0, 0, 0);
     }
-    // natural[m][n] = transposed[n][m] = scale * state[m][n] for this block (either may be null)
-    __device__ __forceinline__ void write_images(const Lane& L, int block, float scale,
-                                                 unsigned char* natural,
-                                                 unsigned char* transposed) const {
-      const int n = 32 * (block & 1) + (L.lane & 31);
+    // += (Y block)^T (X block): the transpose of what mma() adds
+    __device__ __forceinline__ void mma_swapped(const Frag& f) {
+      v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b, f.a, v, 0, 0, 0);
+    }
+    // The lane holds, of the accumulated block, column lane%32 and rows 8j + 4*(lane/32) .. +3:
+    // four neighbours of image row (c0 + column), which go out as one 64-bit write.
+    //   after mma():          r0 = 32*(block/2), c0 = 32*(block%2)  ->  image[n][m] (transposed)
+    //   after mma_swapped():  r0 = 32*(block%2), c0 = 32*(block/2)  ->  image[m][n] (natural)
+    __device__ __forceinline__ void write_image(const Lane& L, int r0, int c0, float scale,
+                                                unsigned char* image) const {
+      const int c = c0 + (L.lane & 31);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int m = 32 * (block >> 1) + 8 * j + 4 * (L.lane >> 5);
-        const uint32_t lo = pack_bf16(v[4 * j] * scale, v[4 * j + 1] * scale);
-        const uint32_t hi = pack_bf16(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
-        if (natural != nullptr) {
-          uint16_t* p = reinterpret_cast<uint16_t*>(natural) + image_row(m) * kImageStride + n;
-          p[0] = static_cast<uint16_t>(lo);
-          p[kImageStride] = static_cast<uint16_t>(lo >> 16);
-          p[2 * kImageStride] = static_cast<uint16_t>(hi);
-          p[3 * kImageStride] = static_cast<uint16_t>(hi >> 16);
-        }
-        if (transposed != nullptr) {
-          uint32_t* p = reinterpret_cast<uint32_t*>(transposed + (image_row(n) * kImageStride + m) * 2);
-          p[0] = lo;
-          p[1] = hi;
-        }
+        const int r = r0 + 8 * j + 4 * (L.lane >> 5);
+        uint32_t* p = reinterpret_cast<uint32_t*>(image + (image_row(c) * kImageStride + r) * 2);
+        p[0] = pack_bf16(v[4 * j] * scale, v[4 * j + 1] * scale);
+        p[1] = pack_bf16(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
       }
     }
+    static __device__ __forceinline__ int block_row0(int block) { return 32 * (block >> 1); }
+    static __device__ __forceinline__ int block_col0(int block) { return 32 * (block & 1); }
   };
 
   // two neighbouring image elements (k, k+1) of image row n
@@ -388,48 +385,6 @@ struct F32x32 {
     apply(X, W, out);
   }
 
-  // One 16x16 block of the 32x32 state, accumulated by one wave over LDS-resident tiles
-  // (block = 0..3: rows 16*(block/2).., columns 16*(block%2)..), and its way into operand images.
-  struct BlockAcc {
-    static constexpr int kBlocks = 4;
-    f32x4_t v;
-    __device__ __forceinline__ void zero() { v = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
-    struct Frag {
-      float a[4], b[4];
-    };
-    static __device__ __forceinline__ Frag fetch(const unsigned char* Xt, const unsigned char* Yt,
-                                                 const Lane& L, int block) {
-      const int offx = L.g16 * kTileStride + (16 * (block >> 1) + L.i16) * 4;
-      const int offy = L.g16 * kTileStride + (16 * (block & 1) + L.i16) * 4;
-      Frag f;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        f.a[s] = *reinterpret_cast<const float*>(Xt + offx + 4 * s * kTileStride);
-        f.b[s] = *reinterpret_cast<const float*>(Yt + offy + 4 * s * kTileStride);
-      }
-      return f;
-    }
-    __device__ __forceinline__ void mma(const Frag& f) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        v = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[s], f.b[s], v, 0, 0, 0);
-    }
-    __device__ __forceinline__ void write_images(const Lane& L, int block, float scale,
-                                                 unsigned char* natural,
-                                                 unsigned char* transposed) const {
-      const int n = 16 * (block & 1) + L.i16;
-      const int m = 16 * (block >> 1) + 4 * L.g16;
-      const f32x4_t w = v * scale;
-      if (natural != nullptr) {
-        float* p = reinterpret_cast<float*>(natural) + m * kImageStride + n;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) p[i * kImageStride] = w[i];
-      }
-      if (transposed != nullptr)
-        *reinterpret_cast<f32x4_t*>(transposed + (n * kImageStride + m) * 4) = w;
-    }
-  };
-
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
                                                           float v0, float v1) {
     float* p = reinterpret_cast<float*>(image + (n * kImageStride + k) * 4);
@@ -437,10 +392,6 @@ struct F32x32 {
     p[1] = v1;
   }
 };
-
-// floats per row of an fp32 scratch tile (D columns + padding)
-template <class F>
-constexpr int scratch_stride() { return F::D + 4; }
 
 // ---- tiles --------------------------------------------------------------------------------
 
@@ -526,34 +477,6 @@ __device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, un
   }
 }
 
-// Apply result -> scratch tile: row i16, columns out_col(nt, g16) .. +3 (one 128-bit write)
-template <class F>
-__device__ __forceinline__ void to_scratch(const f32x4_t (&out)[F::NT], float* Sc, const Lane& L) {
-#pragma unroll
-  for (int nt = 0; nt < F::NT; ++nt)
-    *reinterpret_cast<f32x4_t*>(Sc + L.i16 * scratch_stride<F>() + F::out_col(nt, L.g16)) = out[nt];
-}
-
-// scratch tile -> load layout: the EPL columns of row r8 + 8h this lane owns
-template <class F>
-__device__ __forceinline__ void from_scratch(const float* Sc, const Lane& L, int h,
-                                             float (&f)[F::EPL]) {
-  const f32x4_t* p = reinterpret_cast<const f32x4_t*>(
-      Sc + (L.r8 + 8 * h) * scratch_stride<F>() + F::EPL * L.ch);
-#pragma unroll
-  for (int q = 0; q < F::EPL / 4; ++q) {
-    const f32x4_t a = p[q];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) f[4 * q + i] = a[i];
-  }
-}
-
-template <class F>
-__device__ __forceinline__ void store_row(unsigned char* __restrict__ dst, int row, const Lane& L,
-                                          const float (&f)[F::EPL]) {
-  *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 16 * L.ch) = F::pack(f);
-}
-
 // ---- epilogues in the product layout ------------------------------------------------------
 // An apply product leaves lane (i16, g16) with 2*EPL values of tile row i16: the two 16-byte
 // pieces of the row at bytes 64j + 16*g16.  TileRows::unpack gives any LDS tile in the same
@@ -576,23 +499,38 @@ __device__ __forceinline__ float row_sum_groups(float x, const Lane& L) {
 }
 
 // p <- (p - u (u.p)) / r for the lane's row, u being the unit row held in `e`: the tangent
-// projection shared by dQ (u = qhat, p = g) and dK (u = khat, p = h).
-template <class F>
+// projection shared by dQ (u = qhat, p = g) and dK (u = khat, p = h).  With LAZY the unit row
+// is unpacked twice instead of being kept in registers across the row sum.
+template <class F, bool LAZY>
 __device__ __forceinline__ void project_rows(float (&p)[2 * F::EPL], typename F::TileRows& e,
                                              float inv_r, const Lane& L) {
-  float proj = 0.0f;
-  {
-    float u[2 * F::EPL];
-    e.unpack(u);
-#pragma unroll
-    for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * p[c];
-  }
-  proj = row_sum_groups(proj, L);
-  e.forget_unpacked();
   float u[2 * F::EPL];
   e.unpack(u);
+  float proj = 0.0f;
+#pragma unroll
+  for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * p[c];
+  proj = row_sum_groups(proj, L);
+  if (LAZY) {
+    e.forget_unpacked();
+    e.unpack(u);
+  }
 #pragma unroll
   for (int c = 0; c < 2 * F::EPL; ++c) p[c] = (p[c] - u[c] * proj) * inv_r;
+}
+
+// The same with the raw row x = r * u in `e`:  (p - u (u.p)) / r = p/r - x (x.p) / r^3.
+template <class F>
+__device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
+                                                 const typename F::TileRows& e, float inv_r,
+                                                 const Lane& L) {
+  float x[2 * F::EPL];
+  e.unpack(x);
+  float proj = 0.0f;
+#pragma unroll
+  for (int c = 0; c < 2 * F::EPL; ++c) proj += x[c] * p[c];
+  proj = row_sum_groups(proj, L) * (inv_r * inv_r * inv_r);
+#pragma unroll
+  for (int c = 0; c < 2 * F::EPL; ++c) p[c] = p[c] * inv_r - x[c] * proj;
 }
 
 template <class F>

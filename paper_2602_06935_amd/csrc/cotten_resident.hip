@@ -1,4 +1,4 @@
-// Resident kernels for short sequences (N <= 208) with 128-byte rows.
+// Resident kernels for short bf16 sequences (N <= 208, d_h = 64).
 //
 // One persistent workgroup of 16 waves owns one slice at a time and keeps it in LDS: wave w
 // loads and stages the 16-row tile w, so every global load of the slice is issued at once and
@@ -135,14 +135,23 @@ template <class F>
 __device__ __forceinline__ void build_state(const Lane& L, int block, int x_off, int y_off,
                                             float scale, unsigned char* natural,
                                             unsigned char* transposed) {
-  typename F::BlockAcc acc;
-  acc.zero();
+  typedef typename F::BlockAcc Acc;
+  // Images are written with wide stores from an accumulator that holds the block the other
+  // way round: the natural image needs the transposed block, i.e. the operands swapped
+  // (a second accumulation, far cheaper than narrow image writes).
+  Acc acc_t, acc_n;
+  acc_t.zero();
+  acc_n.zero();
 #pragma unroll
   for (int t = 0; t < kMaxTiles; ++t) {
     const unsigned char* blk = smem + t * kBlockBytes;
-    acc.mma(F::BlockAcc::fetch(blk + x_off, blk + y_off, L, block));
+    const typename Acc::Frag f = Acc::fetch(blk + x_off, blk + y_off, L, block);
+    if (transposed != nullptr) acc_t.mma(f);
+    if (natural != nullptr) acc_n.mma_swapped(f);
   }
-  acc.write_images(L, block, scale, natural, transposed);
+  const int r0 = Acc::block_row0(block), c0 = Acc::block_col0(block);
+  if (transposed != nullptr) acc_t.write_image(L, r0, c0, scale, transposed);
+  if (natural != nullptr) acc_n.write_image(L, c0, r0, scale, natural);
 }
 
 // Zero rows for the two tiles at Xt and Yt.
@@ -258,7 +267,7 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
     if (kind != 1) {
       typename F::TileRows e;
       e.load(tb + (kind == 0 ? kQt : kKt), L);
-      project_rows<F>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
+      project_rows<F, true>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
     }
   }
   if (row < N) store_product_row<F>(dst, row, L, p);
@@ -397,14 +406,12 @@ hipError_t run(const Problem& p, bool bwd) {
 
 }  // namespace
 
-int resident_max_rows() { return kMaxTiles * mfma::TR; }
-
-hipError_t launch_resident_fwd(const Problem& p) {
-  return p.dtype == 1 ? run<Bf16x64>(p, false) : run<F32x32>(p, false);
+bool resident_supports(int dtype, int D, int N) {
+  return dtype == 1 && D == mfma::Bf16x64::D && N <= kMaxTiles * mfma::TR;
 }
 
-hipError_t launch_resident_bwd(const Problem& p) {
-  return p.dtype == 1 ? run<Bf16x64>(p, true) : run<F32x32>(p, true);
-}
+hipError_t launch_resident_fwd(const Problem& p) { return run<Bf16x64>(p, false); }
+
+hipError_t launch_resident_bwd(const Problem& p) { return run<Bf16x64>(p, true); }
 
 }  // namespace cotten
