@@ -141,11 +141,12 @@ def measured_traffic(workload, kernel_tags):
     workload: FETCH_SIZE + WRITE_SIZE (scaled by the copy kernel's reading) summed over the
     kernels of the call, i.e. those whose name contains one of `kernel_tags`.  None when no
     summary is there."""
-    path = os.path.join(ROOT, "profiles", f"mfma_path_{workload}.txt")
-    if not os.path.exists(path):
+    import glob
+    paths = sorted(glob.glob(os.path.join(ROOT, "profiles", f"*_path_{workload}.txt")))
+    if not paths:
         return None
     total, seen = 0.0, 0
-    for line in open(path):
+    for line in open(paths[-1]):
         parts = line.strip().split(",")
         if len(parts) == 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") \
                 and any(t in parts[1] for t in kernel_tags) and parts[2].endswith("MB per launch"):
@@ -154,8 +155,9 @@ def measured_traffic(workload, kernel_tags):
     return int(total) if seen else None
 
 
-# kernels one backward call launches (fused: one; long sequences: three)
-BWD_KERNELS = ("fused_bwd_kernel", "split_state_kernel", "split_q_kernel", "split_kv_kernel")
+# kernels one backward call launches (resident or fused: one; long sequences: three)
+BWD_KERNELS = ("resident_bwd_kernel", "fused_bwd_kernel", "split_state_kernel", "split_q_kernel",
+               "split_kv_kernel")
 
 
 def cpu_baseline(batch, budget_s=12.0):

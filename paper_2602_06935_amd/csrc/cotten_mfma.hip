@@ -45,6 +45,7 @@ using namespace mfma;
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
+constexpr bool kSplitStream = false;  // store policy of the split kernels (measured)
 
 // ---- LDS map ----------------------------------------------------------------------------
 // [working set of the 4 waves | (aliased) two reduction buffers][image 0][image 1][flags]
@@ -147,7 +148,7 @@ __device__ __forceinline__ float inv_by_row(const WaveLds<F>& W, const Lane& L,
 }
 
 // O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
-template <class F, int DEPTH>
+template <class F, int DEPTH, bool STREAM>
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
                                                const Src& src, unsigned char* __restrict__ O,
                                                const Rows rows, float eps, Raw& first,
@@ -165,13 +166,13 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
 #pragma unroll
     for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
     const int row = row0 + L.i16;
-    if (row < rows.limit) store_product_row<F>(O, row, L, o);
+    if (row < rows.limit) store_product_row<F, STREAM>(O, row, L, o);
     wave_lds_fence();
   });
 }
 
 // dQ rows from (Q, dO) and W = scale * S (image op[a][c]); with ACCUM also dsacc += qhat^T dO.
-template <class F, bool ACCUM, int DEPTH>
+template <class F, bool ACCUM, int DEPTH, bool STREAM>
 __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
                                            const Src& src, unsigned char* __restrict__ dQ,
                                            const Rows rows,
@@ -202,14 +203,14 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
     product_rows<F>(out, g);
     project_rows<F, false>(g, e, inv_r, L);
     const int row = row0 + L.i16;
-    if (row < rows.limit) store_product_row<F>(dQ, row, L, g);
+    if (row < rows.limit) store_product_row<F, STREAM>(dQ, row, L, g);
     wave_lds_fence();
   });
 }
 
 // dK, dV rows from (K, V) and scale * dS: dV = (k dS)/r (image op[c][a]),
 // h = v dS^T (image op[a][c]).  Rows below the limit that are masked get zeros.
-template <class F, int DEPTH>
+template <class F, int DEPTH, bool STREAM>
 __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
                                             const Src& src, unsigned char* __restrict__ dK,
                                             unsigned char* __restrict__ dV, const Rows rows,
@@ -223,8 +224,8 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
 #pragma unroll
       for (int i = 0; i < 2 * F::EPL; ++i) zeros[i] = 0.0f;
       if (row < rows.limit) {
-        store_product_row<F>(dK, row, L, zeros);
-        store_product_row<F>(dV, row, L, zeros);
+        store_product_row<F, STREAM>(dK, row, L, zeros);
+        store_product_row<F, STREAM>(dV, row, L, zeros);
       }
       return;
     }
@@ -245,8 +246,8 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
     for (int i = 0; i < 2 * F::EPL; ++i) gv[i] *= inv_r;
     project_rows_raw<F>(hh, xk, inv_r, L);
     if (row < rows.limit) {
-      store_product_row<F>(dK, row, L, hh);
-      store_product_row<F>(dV, row, L, gv);
+      store_product_row<F, STREAM>(dK, row, L, hh);
+      store_product_row<F, STREAM>(dV, row, L, gv);
     }
     wave_lds_fence();
   });
@@ -422,7 +423,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F, F::kDepthFwd>(L, W, q_src, a.O + base, all, a.eps, qfirst, Sop);
+  fwd_apply_pass<F, F::kDepthFwd, true>(L, W, q_src, a.O + base, all, a.eps, qfirst, Sop);
 }
 
 template <class F>
@@ -459,7 +460,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   __syncthreads();
   acc.zero();
   COTTEN_TRACE_POINT(4);
-  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, q_src, a.dQ + base, all, a.eps,
+  bwd_q_pass<F, true, F::kDepthQAccum, true>(L, W, q_src, a.dQ + base, all, a.eps,
                                        qfirst, op0, acc);
   COTTEN_TRACE_POINT(5);
   // the key/value tiles are walked again: get the first one moving before the reduction
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
   dS_h.load(op0, L);  // h = v dS^T: contraction over columns of dS
   COTTEN_TRACE_POINT(7);
-  bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps,
+  bwd_kv_pass<F, F::kDepthKV, true>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps,
                               kfirst, dS_v, dS_h);
   COTTEN_TRACE_POINT(8);
 }
@@ -541,7 +542,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
-  fwd_apply_pass<F, F::kDepthFwd>(L, W, q_src, a.O + base, all, a.eps, first, Sop);
+  fwd_apply_pass<F, F::kDepthFwd, kSplitStream>(L, W, q_src, a.O + base, all, a.eps, first, Sop);
 }
 
 // Backward, step 2: one pass over this workgroup's (Q,dO) tiles writes dQ (S is complete)
@@ -565,7 +566,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_q_kernel(const Args a) {
   __syncthreads();
   typename F::Acc acc;
   acc.zero();
-  bwd_q_pass<F, true, F::kDepthQAccum>(L, W, q_src, a.dQ + base, all, a.eps, first, op0, acc);
+  bwd_q_pass<F, true, F::kDepthQAccum, kSplitStream>(L, W, q_src, a.dQ + base, all, a.eps, first, op0, acc);
   wg_reduce<F>(L, smem, acc);
   publish_partial<F>(a.ds_partials, bh, split, a.splits);
 }
@@ -594,7 +595,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_kv_kernel(const Args a) {
   typename F::Operand dS_v, dS_h;
   dS_v.load(op1, L);
   dS_h.load(op0, L);
-  bwd_kv_pass<F, F::kDepthKV>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps, first, dS_v,
+  bwd_kv_pass<F, F::kDepthKV, kSplitStream>(L, W, kv_src, a.dK + base, a.dV + base, keys, a.eps, first, dS_v,
                               dS_h);
 }
 

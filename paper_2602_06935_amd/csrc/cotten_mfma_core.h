@@ -533,7 +533,11 @@ __device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
   for (int c = 0; c < 2 * F::EPL; ++c) p[c] = p[c] * inv_r - x[c] * proj;
 }
 
-template <class F>
+// STREAM: non-temporal stores.  Results are not read again by these kernels, and written this
+// way they do not displace the inputs still on their way through L2 (measured: a clear gain
+// where a workgroup owns a whole slice, none where long sequences are cut up).  Loads are
+// better left with the default policy in every kernel here.
+template <class F, bool STREAM>
 __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ dst, int row,
                                                   const Lane& L, const float (&p)[2 * F::EPL]) {
 #pragma unroll
@@ -541,8 +545,10 @@ __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ ds
     float c[F::EPL];
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];
-    *reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 64 * j + 16 * L.g16) =
-        F::pack(c);
+    u32x4_t* at =
+        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 64 * j + 16 * L.g16);
+    if (STREAM) __builtin_nontemporal_store(F::pack(c), at);
+    else *at = F::pack(c);
   }
 }
 

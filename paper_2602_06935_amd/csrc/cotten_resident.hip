@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
       const int row = tile * TR + L.i16;
       if (row < N)
-        store_product_row<F>(a.O + static_cast<size_t>(slice) * N * kRowBytes, row, L, o);
+        store_product_row<F, true>(a.O + static_cast<size_t>(slice) * N * kRowBytes, row, L, o);
     }
   }
 }
@@ -270,7 +270,7 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
       project_rows<F, true>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
     }
   }
-  if (row < N) store_product_row<F>(dst, row, L, p);
+  if (row < N) store_product_row<F, true>(dst, row, L, p);
 }
 
 // Backward, per slice (B = workgroup barrier):
