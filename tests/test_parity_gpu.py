@@ -151,6 +151,49 @@ def test_mask_semantics(oracle, dtype, d):
     assert np.array_equal(gpu_fwd(Q, K, V, None, dtype), gpu_fwd(Q, K, V, ones, dtype))
 
 
+@pytest.mark.parametrize("N", [16, 48, 113, 207, 208, 209])
+def test_short_bf16_lengths_around_the_resident_limit(oracle, N):
+    """bf16 d_h = 64 up to 208 rows is served by the kernels that keep a slice in LDS, 209 rows by
+    the streaming kernels: both sides of the limit, full tiles and ragged tails."""
+    B, H, d = 3, 2, 64
+    Q, K, V, dO = _case(7000 + N, B, H, N, d, "bf16")
+    lengths = [N, max(1, N // 3), 1]
+    mask = np.zeros((B, N), np.uint8)
+    for b, L in enumerate(lengths):
+        mask[b, N - L:] = 1
+    _check_case(oracle, Q, K, V, dO, mask, "bf16", label=f"short bf16 N={N}")
+
+
+def test_resident_workgroups_take_several_slices(oracle):
+    """More slices than compute units: a persistent workgroup walks three slices and more,
+    with its next slice prefetched while the current one is worked on.  The masks mix tiles
+    without any valid key at the start, in the middle and at the end of a sequence."""
+    B, H, N, d = 175, 4, 200, 64          # 700 slices
+    Q, K, V, dO = _case(31, B, H, N, d, "bf16")
+    rng = np.random.default_rng(5)
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        kind = b % 4
+        if kind == 0:                      # left padding
+            mask[b, N - int(rng.integers(1, N + 1)):] = 1
+        elif kind == 1:                    # right padding
+            mask[b, :int(rng.integers(1, N + 1))] = 1
+        elif kind == 2:                    # two islands with whole dead tiles between them
+            mask[b, 16:40] = 1
+            mask[b, 150:171] = 1
+        else:                              # scattered
+            mask[b] = rng.random(N) < 0.3
+    mask[7] = 0                            # no valid key at all
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, "bf16", label="700 slices, mixed masks")
+    assert np.all(got_o[7] == 0.0) and np.all(got_g[1][7] == 0.0) and np.all(got_g[2][7] == 0.0)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], got_g[1].shape)
+    assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
+    # run-to-run: bit for bit
+    again = gpu_bwd(Q, K, V, dO, mask, "bf16")
+    for a, c in zip(again, got_g):
+        assert np.array_equal(a, c)
+
+
 @pytest.mark.parametrize("eps", [1e-12, 1e-6, 1e-3])
 def test_eps_and_scale(oracle, eps):
     Q, K, V, dO = _case(21, 2, 2, 90, 32)
