@@ -20,6 +20,14 @@
  * masks nothing on the query side; the backward is the chain rule applied to
  * the expressions above (the paper prints none).
  *
+ * The learnable normaliser of the scaled variant (same section, the scaled
+ * CosineAttention): s = 1 / n^m with a learnable exponent m.  Here one m per head
+ * and one n per sequence (its valid length, or the padded length), so slice
+ * (b,h) has s_bh = n_b^(-m_h).  cotten_oracle_normaliser evaluates it,
+ * cotten_oracle_scaled_fwd / _bwd take one s per slice, the backward also
+ * returns d/d(log s_bh) = sum_i dO_i . O_i (O is linear in s), and
+ * cotten_oracle_normaliser_bwd turns that into dm_h = -sum_b ln(n_b) dlog_s_bh.
+ *
  * Pins (tests/test_oracle_pins.py): linear == quadratic on small inputs;
  * closed forms; unit norms; masked-key invariance; permutation equivariance;
  * fp64 autograd of the library expression; central finite differences and an
@@ -190,5 +198,58 @@ void cotten_oracle_bwd(const double* Q, const double* K, const double* V,
       for (int a = 0; a < d; ++a) gk[(size_t)j * d + a] = (gh[a] - xh[a] * proj) / rk;
     }
     free(S); free(dS); free(xh); free(gh);
+  }
+}
+
+/* ---- the learnable normaliser 1 / n^m of the scaled variant ----------------- */
+
+/* s[b*H+h] = n_b^(-m_h) */
+void cotten_oracle_normaliser(const double* m, const double* n, double* s, int B, int H) {
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h) s[(size_t)b * H + h] = pow(n[b], -m[h]);
+}
+
+/* Forward with one scalar per slice: the reordered form, slice by slice. */
+void cotten_oracle_scaled_fwd(const double* Q, const double* K, const double* V,
+                              const uint8_t* mask, const double* s, double* O, int B, int H,
+                              int N, int d, double eps) {
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const uint8_t* mrow = mask == NULL ? NULL : mask + (size_t)b * N;
+    cotten_oracle_fwd_linear(Q + off, K + off, V + off, mrow, O + off, 1, 1, N, d, s[bh], eps);
+  }
+}
+
+/* Backward with one scalar per slice.  dQ, dK, dV as in cotten_oracle_bwd with
+ * scale = s_bh.  O = s * U with U free of s, hence
+ *   d loss / d log s_bh = s_bh * sum_i dO_i . U_i = sum_i dO_i . O_i. */
+void cotten_oracle_scaled_bwd(const double* Q, const double* K, const double* V,
+                              const uint8_t* mask, const double* s, const double* dO,
+                              double* dQ, double* dK, double* dV, double* dlog_s, int B,
+                              int H, int N, int d, double eps) {
+  double* O = (double*)malloc(sizeof(double) * (size_t)N * d);
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const uint8_t* mrow = mask == NULL ? NULL : mask + (size_t)b * N;
+    cotten_oracle_bwd(Q + off, K + off, V + off, mrow, dO + off, dQ + off, dK + off, dV + off,
+                      1, 1, N, d, s[bh], eps);
+    cotten_oracle_fwd_linear(Q + off, K + off, V + off, mrow, O, 1, 1, N, d, s[bh], eps);
+    double acc = 0.0;
+    for (size_t e = 0; e < (size_t)N * d; ++e) acc += dO[off + e] * O[e];
+    dlog_s[bh] = acc;
+  }
+  free(O);
+}
+
+/* s_bh = exp(-m_h ln n_b)  =>  d log s_bh / d m_h = -ln n_b  =>
+ * dm_h = -sum_b ln(n_b) * dlog_s[b*H+h] */
+void cotten_oracle_normaliser_bwd(const double* dlog_s, const double* n, double* dm, int B,
+                                  int H) {
+  for (int h = 0; h < H; ++h) {
+    double acc = 0.0;
+    for (int b = 0; b < B; ++b) acc += log(n[b]) * dlog_s[(size_t)b * H + h];
+    dm[h] = -acc;
   }
 }

@@ -43,6 +43,14 @@ def _load():
             fn.restype = None
         lib.cotten_oracle_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, i, i, i, i, f, f]
         lib.cotten_oracle_bwd.restype = None
+        lib.cotten_oracle_normaliser.argtypes = [dp, dp, dp, i, i]
+        lib.cotten_oracle_normaliser.restype = None
+        lib.cotten_oracle_normaliser_bwd.argtypes = [dp, dp, dp, i, i]
+        lib.cotten_oracle_normaliser_bwd.restype = None
+        lib.cotten_oracle_scaled_fwd.argtypes = [dp, dp, dp, bp, dp, dp, i, i, i, i, f]
+        lib.cotten_oracle_scaled_fwd.restype = None
+        lib.cotten_oracle_scaled_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, dp, dp, i, i, i, i, f]
+        lib.cotten_oracle_scaled_bwd.restype = None
         lib.cotten_oracle_threads.argtypes = []
         lib.cotten_oracle_threads.restype = ctypes.c_int
         _lib = lib
@@ -102,3 +110,47 @@ def bwd(Q, K, V, dO, mask=None, scale: Optional[float] = None,
     _load().cotten_oracle_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(dO), _ptr(dQ), _ptr(dK),
                               _ptr(dV), B, H, N, d, s, float(eps))
     return dQ, dK, dV
+
+
+def normaliser(m, n) -> np.ndarray:
+    """s[b,h] = n_b ** (-m_h): the learnable normaliser 1/n^m, one exponent per head and one
+    n per sequence."""
+    m, n = _f64(m), _f64(n)
+    assert m.ndim == 1 and n.ndim == 1
+    s = np.empty((n.shape[0], m.shape[0]), np.float64)
+    _load().cotten_oracle_normaliser(_ptr(m), _ptr(n), _ptr(s), n.shape[0], m.shape[0])
+    return s
+
+
+def normaliser_bwd(dlog_s, n) -> np.ndarray:
+    """dm[h] = -sum_b ln(n_b) dlog_s[b,h]."""
+    g, n = _f64(dlog_s), _f64(n)
+    assert g.ndim == 2 and g.shape[0] == n.shape[0]
+    dm = np.empty(g.shape[1], np.float64)
+    _load().cotten_oracle_normaliser_bwd(_ptr(g), _ptr(n), _ptr(dm), g.shape[0], g.shape[1])
+    return dm
+
+
+def scaled_fwd(Q, K, V, s, mask=None, eps: float = 1e-6) -> np.ndarray:
+    """O with one scalar s[b,h] per slice."""
+    Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
+    B, H, N, d = Q.shape
+    assert s.shape == (B, H)
+    O = np.empty_like(Q)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_scaled_fwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(s), _ptr(O), B, H, N, d,
+                                     float(eps))
+    return O
+
+
+def scaled_bwd(Q, K, V, dO, s, mask=None, eps: float = 1e-6):
+    """(dQ, dK, dV, dlog_s) with one scalar s[b,h] per slice; dlog_s[b,h] = d loss / d log s[b,h]."""
+    Q, K, V, dO, s = _f64(Q), _f64(K), _f64(V), _f64(dO), _f64(s)
+    B, H, N, d = Q.shape
+    assert s.shape == (B, H)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dlog = np.empty((B, H), np.float64)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_scaled_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(s), _ptr(dO), _ptr(dQ),
+                                     _ptr(dK), _ptr(dV), _ptr(dlog), B, H, N, d, float(eps))
+    return dQ, dK, dV, dlog

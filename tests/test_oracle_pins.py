@@ -300,3 +300,93 @@ def test_zero_rows_are_finite(oracle):
     assert np.all(np.isfinite(O)) and all(np.all(np.isfinite(g)) for g in (dQ, dK, dV))
     assert np.all(O[0, 0, 3] == 0.0)
     assert np.all(dV[1, 1, 2] == 0.0)     # khat = 0  =>  no gradient reaches that value row
+
+
+# ------------------------------------------- learnable normaliser 1 / n^m pins
+
+def test_normaliser_closed_forms(oracle):
+    n = np.array([1.0, 7.0, 200.0])
+    s = oracle.normaliser([0.0, 1.0, 0.5, 2.0], n)
+    assert s.shape == (3, 4)
+    assert np.allclose(s[:, 0], 1.0, rtol=0, atol=0)            # m = 0: no scaling
+    assert np.allclose(s[:, 1], 1.0 / n, rtol=1e-15)            # m = 1: 1/n
+    assert np.allclose(s[:, 2], 1.0 / np.sqrt(n), rtol=1e-15)   # m = 1/2
+    assert np.allclose(s[:, 3], 1.0 / n ** 2, rtol=1e-15)
+    assert np.all(s[0] == 1.0)                                   # n = 1: any exponent
+
+
+def test_scaled_forward_is_the_quadratic_definition_slice_by_slice(oracle):
+    Q, K, V, _, mask = _small_case(51, B=3, H=2)
+    s = np.array([[0.3, 1.7], [0.05, 2.0], [1.0, 0.4]])
+    O = oracle.scaled_fwd(Q, K, V, s, mask, eps=1e-6)
+    for b in range(3):
+        for h in range(2):
+            ref = oracle.fwd_quadratic(Q[b:b + 1, h:h + 1], K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1],
+                                       mask[b:b + 1], scale=s[b, h], eps=1e-6)
+            assert _rel(O[b:b + 1, h:h + 1], ref) < 1e-13
+    # the forward is linear in s
+    O2 = oracle.scaled_fwd(Q, K, V, 3.0 * s, mask, eps=1e-6)
+    assert _rel(O2, 3.0 * O) < 1e-14
+
+
+def test_scaled_backward_pins(oracle):
+    Q, K, V, dO, mask = _small_case(52, B=3, H=2)
+    s = np.array([[0.3, 1.7], [0.05, 2.0], [1.0, 0.4]])
+    dQ, dK, dV, dlog = oracle.scaled_bwd(Q, K, V, dO, s, mask, eps=1e-6)
+    # dQ, dK, dV: the scalar-scale backward, slice by slice
+    for b in range(3):
+        for h in range(2):
+            sl = (slice(b, b + 1), slice(h, h + 1))
+            ref = oracle.bwd(Q[sl], K[sl], V[sl], dO[sl], mask[b:b + 1], scale=s[b, h], eps=1e-6)
+            for g, r in zip((dQ, dK, dV), ref):
+                assert _rel(g[sl], r) < 1e-13
+    # dlog_s: O is linear in s, so d/d log s = <dO, O>, with O from the quadratic definition
+    for b in range(3):
+        for h in range(2):
+            sl = (slice(b, b + 1), slice(h, h + 1))
+            O = oracle.fwd_quadratic(Q[sl], K[sl], V[sl], mask[b:b + 1], scale=s[b, h], eps=1e-6)
+            assert abs(dlog[b, h] - np.sum(dO[sl] * O)) <= 1e-12 * max(1.0, abs(dlog[b, h]))
+    # central differences of loss(log s) = <dO, O(s)>
+    step = 1e-6
+    for b, h in ((0, 1), (2, 0)):
+        sp, sm = s.copy(), s.copy()
+        sp[b, h] *= np.exp(step)
+        sm[b, h] *= np.exp(-step)
+        lp = np.sum(dO * oracle.scaled_fwd(Q, K, V, sp, mask))
+        lm = np.sum(dO * oracle.scaled_fwd(Q, K, V, sm, mask))
+        assert abs((lp - lm) / (2 * step) - dlog[b, h]) < 1e-7 * max(1.0, abs(dlog[b, h]))
+
+
+def test_normaliser_gradient_against_autograd_and_differences(oracle):
+    """dm_h through normaliser -> scaled attention -> loss = <dO, O>: fp64 autograd of the
+    library expression n**(-m) times the cosine attention, and central differences."""
+    import torch
+    B, H = 3, 2
+    Q, K, V, dO, mask = _small_case(53, B=B, H=H, lengths=[16, 5, 9])
+    n = mask.sum(axis=1).astype(np.float64)           # n = valid length of each sequence
+    m = np.array([0.8, 1.3])
+    s = oracle.normaliser(m, n)
+    _, _, _, dlog = oracle.scaled_bwd(Q, K, V, dO, s, mask)
+    dm = oracle.normaliser_bwd(dlog, n)
+
+    t = lambda x: torch.tensor(np.asarray(x, dtype=np.float64))
+    mt = t(m).requires_grad_(True)
+    Qh = t(Q) / torch.sqrt((t(Q) ** 2).sum(-1, keepdim=True) + 1e-6)
+    Kh = t(K) / torch.sqrt((t(K) ** 2).sum(-1, keepdim=True) + 1e-6)
+    mk = t(mask)[:, None, :, None]
+    S = torch.matmul((Kh * mk).transpose(-1, -2), t(V) * mk)
+    st = t(n)[:, None] ** (-mt[None, :])
+    O = st[:, :, None, None] * torch.matmul(Qh, S)
+    (O * t(dO)).sum().backward()
+    assert _rel(dm, mt.grad.numpy()) < 1e-12
+
+    step = 1e-6
+    for h in range(H):
+        mp, mm = m.copy(), m.copy()
+        mp[h] += step
+        mm[h] -= step
+        lp = np.sum(dO * oracle.scaled_fwd(Q, K, V, oracle.normaliser(mp, n), mask))
+        lm = np.sum(dO * oracle.scaled_fwd(Q, K, V, oracle.normaliser(mm, n), mask))
+        assert abs((lp - lm) / (2 * step) - dm[h]) < 1e-6 * max(1.0, abs(dm[h]))
+    # n = 1 for every sequence: ln n = 0, the exponent has no effect
+    assert np.all(oracle.normaliser_bwd(dlog, np.ones(B)) == 0.0)
