@@ -25,6 +25,17 @@
  * with r(x) = sqrt(sum_c x_c^2 + eps); dK and dV rows of masked keys are written
  * as exact zeros.  If a batch row has no valid key, O = 0 for it.
  *
+ * Learnable normaliser (the scaled CosineAttention, scale = 1/n^m with a learnable
+ * exponent).  Instead of one scalar the caller may pass one scale per slice,
+ * params->slice_scale[b*H+h], and ask the backward for
+ *
+ *     dlog_scale[b*H+h] = d loss / d log(scale_bh) = sum_i dO_i . O_i  (= <S, dS>)
+ *
+ * which costs the kernels nothing extra in memory traffic.  cotten_normaliser_fwd
+ * fills slice_scale from one exponent per head and one n per sequence,
+ * scale_bh = n_b^(-m_h), and cotten_normaliser_bwd reduces dlog_scale to the
+ * gradient of the exponents, dm_h = -sum_b ln(n_b) * dlog_scale[b*H+h].
+ *
  * Memory.  Every pointer is a DEVICE pointer owned by the caller.  Q, K, V, O,
  * dO, dQ, dK, dV are [B, H, N, d_h] row-major and contiguous (each slice (b,h) is
  * one contiguous N x d_h block), element type given by `dtype`; mask is [B, N]
@@ -88,6 +99,10 @@ typedef struct cotten_params {
   float eps;              /* epsilon inside the square root; < 0 selects 1e-6; 0 allowed */
   void* workspace;        /* device buffer, 16-byte aligned, or NULL = library-owned    */
   size_t workspace_bytes; /* size of `workspace` (ignored when it is NULL)              */
+  const float* slice_scale; /* device, [B*H] floats, or NULL.  When given, slice (b,h) uses
+                               slice_scale[b*H+h] (finite, > 0) and `scale` is ignored      */
+  float* dlog_scale;      /* backward only: device, [B*H] floats, or NULL.  When given it
+                             receives sum_i dO_i . O_i of every slice (see above)          */
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):
@@ -110,6 +125,19 @@ int cotten_attn_fwd_ex(const void* Q, const void* K, const void* V, const uint8_
 int cotten_attn_bwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask,
                        const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
                        int d_h, void* stream, const cotten_params* params);
+
+/* Learnable normaliser 1/n^m of the scaled CosineAttention ("Model Description"), one
+ * exponent per head:  slice_scale[b*H+h] = n_b^(-m_h).  m: device, [H] floats.  n: device,
+ * [B] int32 with n_b >= 1 (for instance the valid length of each sequence), or NULL for
+ * n_b = N, the padded length.  slice_scale: device, [B*H] floats, written. */
+int cotten_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B, int H,
+                          int N, void* stream);
+
+/* Gradient of the exponents from the backward call's dlog_scale:
+ * dm[h] = -sum_b ln(n_b) * dlog_scale[b*H+h], summed in a fixed order.  dm: device, [H]
+ * floats, written.  n as above. */
+int cotten_normaliser_bwd(const float* dlog_scale, const int32_t* n, float* dm, int B, int H,
+                          int N, void* stream);
 
 /* Bytes of workspace the given call would use (pure host arithmetic; 0 for an
  * unsupported shape).  Grows like B*H*d_h^2 times the number of sequence splits,

@@ -22,12 +22,14 @@ COTTEN_BF16 = 1
 EXPORTS = (
     "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
     "cotten_attn_workspace_bytes", "cotten_status_string",
+    "cotten_normaliser_fwd", "cotten_normaliser_bwd",
 )
 
 
 class CottenParams(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int), ("scale", ctypes.c_float), ("eps", ctypes.c_float),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p)]
 
 
 class CottenError(RuntimeError):
@@ -59,6 +61,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
         f.restype = ctypes.c_int
     lib.cotten_attn_workspace_bytes.argtypes = [ip, ip, ip, ip, ip, ip]
     lib.cotten_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.cotten_normaliser_fwd.argtypes = [vp, vp, vp, ip, ip, ip, vp]
+    lib.cotten_normaliser_bwd.argtypes = [vp, vp, vp, ip, ip, ip, vp]
+    lib.cotten_normaliser_fwd.restype = lib.cotten_normaliser_bwd.restype = ctypes.c_int
     lib.cotten_status_string.argtypes = [ip]
     lib.cotten_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -104,8 +109,21 @@ def _mask_ptr(mask: Optional[torch.Tensor], B: int, N: int, dev) -> Optional[int
     return mask.data_ptr()
 
 
-def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor]) -> CottenParams:
+def _f32_vector(name: str, t: Optional[torch.Tensor], numel: int, dev) -> Optional[int]:
+    if t is None:
+        return None
+    if t.dtype != torch.float32 or t.numel() != numel or not t.is_contiguous() or t.device != dev:
+        raise ValueError(f"{name} must be a contiguous float32 GPU tensor of {numel} elements")
+    return t.data_ptr()
+
+
+def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
+            slice_scale: Optional[torch.Tensor] = None,
+            dlog_scale: Optional[torch.Tensor] = None) -> CottenParams:
     p = CottenParams()
+    slices = Q.shape[0] * Q.shape[1]
+    p.slice_scale = _f32_vector("slice_scale", slice_scale, slices, Q.device)
+    p.dlog_scale = _f32_vector("dlog_scale", dlog_scale, slices, Q.device)
     p.dtype = _dtype_code(Q)
     p.scale = 0.0 if scale is None else float(scale)
     p.eps = -1.0 if eps is None else float(eps)
@@ -131,8 +149,10 @@ def _stream_handle(stream) -> int:
 def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     mask: Optional[torch.Tensor], O: Optional[torch.Tensor] = None, *,
                     scale: Optional[float] = None, eps: Optional[float] = None,
-                    stream=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O."""
+                    stream=None, workspace: Optional[torch.Tensor] = None,
+                    slice_scale: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O.
+    `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q)
     if Q.dim() != 4:
@@ -141,7 +161,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     if O is None:
         O = torch.empty_like(Q)
     _prep("O", O, Q)
-    prm = _params(Q, scale, eps, workspace)
+    prm = _params(Q, scale, eps, workspace, slice_scale)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
@@ -154,9 +174,13 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     dQ: Optional[torch.Tensor] = None, dK: Optional[torch.Tensor] = None,
                     dV: Optional[torch.Tensor] = None, *, scale: Optional[float] = None,
                     eps: Optional[float] = None, stream=None,
-                    workspace: Optional[torch.Tensor] = None
+                    workspace: Optional[torch.Tensor] = None,
+                    slice_scale: Optional[torch.Tensor] = None,
+                    dlog_scale: Optional[torch.Tensor] = None
                     ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-    """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors."""
+    """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
+    `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
+    d loss / d log(scale) of every slice."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q); dO = _prep("dO", dO, Q)
     if Q.dim() != 4:
@@ -165,10 +189,51 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     dQ = torch.empty_like(Q) if dQ is None else _prep("dQ", dQ, Q)
     dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
     dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
-    prm = _params(Q, scale, eps, workspace)
+    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),
                                       dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                                       B, H, N, d, _stream_handle(stream), ctypes.byref(prm)))
     return dQ, dK, dV
+
+
+def _lengths_ptr(n: Optional[torch.Tensor], B: int, dev) -> Optional[int]:
+    if n is None:
+        return None
+    if n.dtype != torch.int32 or n.numel() != B or not n.is_contiguous() or n.device != dev:
+        raise ValueError("n must be a contiguous int32 GPU tensor of B elements")
+    return n.data_ptr()
+
+
+def cotten_normaliser_fwd(m: torch.Tensor, n: Optional[torch.Tensor], B: int, N: int,
+                          slice_scale: Optional[torch.Tensor] = None, *, stream=None) -> torch.Tensor:
+    """slice_scale[b,h] = n_b ** (-m_h) (n = None: the padded length N for every sequence)."""
+    lib = load_library()
+    if not m.is_cuda or m.dtype != torch.float32 or not m.is_contiguous() or m.dim() != 1:
+        raise ValueError("m must be a contiguous float32 GPU vector [H]")
+    H = m.numel()
+    if slice_scale is None:
+        slice_scale = torch.empty(B, H, device=m.device, dtype=torch.float32)
+    with torch.cuda.device(m.device):
+        _check(lib.cotten_normaliser_fwd(m.data_ptr(), _lengths_ptr(n, B, m.device),
+                                         _f32_vector("slice_scale", slice_scale, B * H, m.device),
+                                         B, H, N, _stream_handle(stream)))
+    return slice_scale
+
+
+def cotten_normaliser_bwd(dlog_scale: torch.Tensor, n: Optional[torch.Tensor], N: int,
+                          dm: Optional[torch.Tensor] = None, *, stream=None) -> torch.Tensor:
+    """dm[h] = -sum_b ln(n_b) * dlog_scale[b,h]."""
+    lib = load_library()
+    if not dlog_scale.is_cuda or dlog_scale.dim() != 2:
+        raise ValueError("dlog_scale must be a GPU tensor [B,H]")
+    B, H = dlog_scale.shape
+    dev = dlog_scale.device
+    if dm is None:
+        dm = torch.empty(H, device=dev, dtype=torch.float32)
+    with torch.cuda.device(dev):
+        _check(lib.cotten_normaliser_bwd(_f32_vector("dlog_scale", dlog_scale, B * H, dev),
+                                         _lengths_ptr(n, B, dev), _f32_vector("dm", dm, H, dev),
+                                         B, H, N, _stream_handle(stream)))
+    return dm

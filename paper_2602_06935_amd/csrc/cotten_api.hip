@@ -90,6 +90,8 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   } else if (need > 0) {
     if (int rc = own_workspace(need, &p.workspace)) return rc;
   }
+  p.slice_scale = prm->slice_scale;
+  p.dlog_scale = bwd ? prm->dlog_scale : nullptr;
   p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
   p.O = O; p.dQ = dQ; p.dK = dK; p.dV = dV;
   p.B = B; p.H = H; p.N = N; p.D = d_h;
@@ -105,7 +107,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 
-const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0};
+const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr};
 
 }  // namespace
 
@@ -132,6 +134,26 @@ int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* 
                     const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N, int d_h,
                     void* stream) {
   return cotten_attn_bwd_ex(Q, K, V, mask, dO, dQ, dK, dV, B, H, N, d_h, stream, &kDefaults);
+}
+
+int cotten_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B, int H,
+                          int N, void* stream) {
+  if (m == nullptr || slice_scale == nullptr) return COTTEN_ERR_NULL_POINTER;
+  if (B < 1 || H < 1 || N < 1) return COTTEN_ERR_BAD_SHAPE;
+  return cotten::launch_normaliser_fwd(m, n, slice_scale, B, H, N,
+                                       static_cast<hipStream_t>(stream)) == hipSuccess
+             ? COTTEN_OK
+             : COTTEN_ERR_LAUNCH;
+}
+
+int cotten_normaliser_bwd(const float* dlog_scale, const int32_t* n, float* dm, int B, int H,
+                          int N, void* stream) {
+  if (dlog_scale == nullptr || dm == nullptr) return COTTEN_ERR_NULL_POINTER;
+  if (B < 1 || H < 1 || N < 1) return COTTEN_ERR_BAD_SHAPE;
+  return cotten::launch_normaliser_bwd(dlog_scale, n, dm, B, H, N,
+                                       static_cast<hipStream_t>(stream)) == hipSuccess
+             ? COTTEN_OK
+             : COTTEN_ERR_LAUNCH;
 }
 
 size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd) {

@@ -125,7 +125,8 @@ __device__ __forceinline__ void load_state(const float* __restrict__ state, floa
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
     const T* __restrict__ Q, const float* __restrict__ states, T* __restrict__ O, int N,
-    int splits, int rows_per_split, float scale, float eps) {
+    int splits, int rows_per_split, float scale, const float* __restrict__ slice_scale,
+    float eps) {
   constexpr int CH = D / 8;
   __shared__ float S[D][D];
   __shared__ float qs[kTileRows][D + 4];
@@ -138,6 +139,7 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
   const int r_end = min(N, r_begin + rows_per_split);
   const int lrow = tid >> 3, chunk = tid & 7;
 
+  if (slice_scale != nullptr) scale = slice_scale[bh];
   load_state<D, false>(states + static_cast<size_t>(bh) * D * D, scale, S);
   __syncthreads();
 
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
     const T* __restrict__ dO, const uint8_t* __restrict__ mask,
     const float* __restrict__ states, const float* __restrict__ dstates, T* __restrict__ dQ,
     T* __restrict__ dK, T* __restrict__ dV, int H, int N, int splits, int rows_per_split,
-    float scale, float eps) {
+    float scale, const float* __restrict__ slice_scale, float eps) {
   constexpr int CH = D / 8;
   __shared__ float M0[D][D];              // S^T (dQ blocks)  or dS   (dK/dV blocks)
   __shared__ float M1[D][D];              // unused           or dS^T
@@ -191,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
   const int r_end = min(N, r_begin + rows_per_split);
   const int lrow = tid >> 3, chunk = tid & 7;
   const int c0 = chunk * CH;
+  if (slice_scale != nullptr) scale = slice_scale[bh];
 
   if (blockIdx.y == 0) {
     load_state<D, true>(states + static_cast<size_t>(bh) * D * D, scale, M0);  // M0[c][a] = s S[a][c]
@@ -290,6 +293,55 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
   }
 }
 
+// dlog[bh] = scale_bh * <S_bh, dS'_bh> with dS' = sum_i qhat_i^T dO_i (the states in the
+// workspace carry no scale), i.e. <S, dS> = sum_i dO_i . O_i.  One workgroup per slice; the
+// sum runs in a fixed order (strided per thread, then a tree over the threads).
+__global__ __launch_bounds__(kThreads) void state_inner_product_kernel(
+    const float* __restrict__ states, const float* __restrict__ dstates, int dd, float scale,
+    const float* __restrict__ slice_scale, float* __restrict__ dlog) {
+  __shared__ float part[kThreads];
+  const size_t off = static_cast<size_t>(blockIdx.x) * dd;
+  float s = 0.0f;
+  for (int e = threadIdx.x; e < dd; e += kThreads) s += states[off + e] * dstates[off + e];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if (static_cast<int>(threadIdx.x) < w) part[threadIdx.x] += part[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0)
+    dlog[blockIdx.x] = part[0] * (slice_scale != nullptr ? slice_scale[blockIdx.x] : scale);
+}
+
+// slice_scale[b*H+h] = n_b^(-m_h) = exp2(-m_h log2 n_b)
+__global__ __launch_bounds__(kThreads) void normaliser_fwd_kernel(
+    const float* __restrict__ m, const int32_t* __restrict__ n, float* __restrict__ slice_scale,
+    int B, int H, int N) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= B * H) return;
+  const float nb = static_cast<float>(n != nullptr ? n[e / H] : N);
+  slice_scale[e] = exp2f(-m[e % H] * log2f(nb));
+}
+
+// dm[h] = -sum_b ln(n_b) dlog[b*H+h]: one workgroup per head, fixed order (strided per
+// thread, then a tree over the threads).
+__global__ __launch_bounds__(kThreads) void normaliser_bwd_kernel(
+    const float* __restrict__ dlog, const int32_t* __restrict__ n, float* __restrict__ dm, int B,
+    int H, int N) {
+  __shared__ float part[kThreads];
+  const int h = blockIdx.x;
+  float s = 0.0f;
+  for (int b = threadIdx.x; b < B; b += kThreads)
+    s += logf(static_cast<float>(n != nullptr ? n[b] : N)) * dlog[static_cast<size_t>(b) * H + h];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if (static_cast<int>(threadIdx.x) < w) part[threadIdx.x] += part[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) dm[h] = -part[0];
+}
+
 // Where the reduced states of the generic path live: behind the partials when a reduction
 // is needed, otherwise the single partial of each slice already is the state.
 const float* reduce_generic(const Problem& p, const Plan& plan, int nstates) {
@@ -313,7 +365,7 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
   const float* states = reduce_generic(p, plan, 1);
   hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.N,
-                     plan.splits, plan.rows_per_split, p.scale, p.eps);
+                     plan.splits, plan.rows_per_split, p.scale, p.slice_scale, p.eps);
   return hipGetLastError();
 }
 
@@ -333,7 +385,11 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask, states,
                      dstates, static_cast<T*>(p.dQ), static_cast<T*>(p.dK),
                      static_cast<T*>(p.dV), p.H, p.N, plan.splits, plan.rows_per_split, p.scale,
-                     p.eps);
+                     p.slice_scale, p.eps);
+  if (p.dlog_scale != nullptr)
+    hipLaunchKernelGGL(state_inner_product_kernel, dim3(static_cast<unsigned>(BH)),
+                       dim3(kThreads), 0, p.stream, states, dstates, D * D, p.scale,
+                       p.slice_scale, p.dlog_scale);
   return hipGetLastError();
 }
 
@@ -419,6 +475,21 @@ hipError_t launch_generic_fwd(const Problem& p, const Plan& plan) {
 
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan) {
   return p.dtype == 0 ? dispatch_d<float>(p, plan, true) : dispatch_d<bf16>(p, plan, true);
+}
+
+hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B,
+                                 int H, int N, hipStream_t stream) {
+  const unsigned blocks = static_cast<unsigned>((static_cast<long>(B) * H + kThreads - 1) / kThreads);
+  hipLaunchKernelGGL(normaliser_fwd_kernel, dim3(blocks), dim3(kThreads), 0, stream, m, n,
+                     slice_scale, B, H, N);
+  return hipGetLastError();
+}
+
+hipError_t launch_normaliser_bwd(const float* dlog, const int32_t* n, float* dm, int B, int H,
+                                 int N, hipStream_t stream) {
+  hipLaunchKernelGGL(normaliser_bwd_kernel, dim3(static_cast<unsigned>(H)), dim3(kThreads), 0,
+                     stream, dlog, n, dm, B, H, N);
+  return hipGetLastError();
 }
 
 }  // namespace cotten

@@ -20,6 +20,8 @@ struct Problem {
   int B, H, N, D;
   int dtype;            // 0 = f32, 1 = bf16
   float scale, eps;
+  const float* slice_scale;  // [B*H] or nullptr: per-slice scale instead of `scale`
+  float* dlog_scale;         // backward only, [B*H] or nullptr: receives <S, dS> per slice
   float* workspace;     // partial and reduced states, see Plan
   hipStream_t stream;
 };
@@ -65,5 +67,12 @@ hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 bool resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_fwd(const Problem& p);
 hipError_t launch_resident_bwd(const Problem& p);
+
+// Learnable normaliser: slice_scale[b*H+h] = n_b^(-m_h), and dm[h] = -sum_b ln(n_b) dlog[b*H+h].
+// n may be nullptr (n_b = N).
+hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B,
+                                 int H, int N, hipStream_t stream);
+hipError_t launch_normaliser_bwd(const float* dlog, const int32_t* n, float* dm, int B, int H,
+                                 int N, hipStream_t stream);
 
 }  // namespace cotten

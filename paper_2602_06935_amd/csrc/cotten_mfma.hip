@@ -391,7 +391,27 @@ struct Args {
   float* ds_partials;
   int H, N, splits;
   float scale, eps;
+  const float* scales;  // per-slice scale, or nullptr
+  float* dlog;          // backward: sum_i dO_i . O_i per slice, or nullptr
 };
+
+__device__ __forceinline__ float slice_scale(const Args& a, int bh) {
+  return a.scales != nullptr ? a.scales[bh] : a.scale;
+}
+
+// Sum of x over the workgroup in a fixed order (tree through `scratch`, kThreads floats of
+// LDS not otherwise in use); every thread gets it.
+__device__ __forceinline__ float block_sum(float x, float* scratch) {
+  scratch[threadIdx.x] = x;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if (static_cast<int>(threadIdx.x) < w) scratch[threadIdx.x] += scratch[threadIdx.x + w];
+    __syncthreads();
+  }
+  const float total = scratch[0];
+  __syncthreads();
+  return total;
+}
 
 template <class F>
 __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
@@ -418,7 +438,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   state_pass<F, F::kDepthState>(L, W, kv_src, keys, a.eps, kfirst, acc);
   wg_reduce<F>(L, smem, acc);
   // O = qhat S: contraction over rows of S
-  make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), false}, a.scale, nullptr,
+  make_operands<F>(StateSource<F>{reinterpret_cast<const float*>(smem), false}, slice_scale(a, bh), nullptr,
                    op0);
   __syncthreads();
   typename F::Operand Sop;
@@ -456,7 +476,8 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   COTTEN_TRACE_POINT(2);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(3);
-  make_operands<F>(reduced, a.scale, op0, nullptr);  // g = dO S^T: contraction over columns of S
+  const float scale = slice_scale(a, bh);
+  make_operands<F>(reduced, scale, op0, nullptr);  // g = dO S^T: contraction over columns of S
   __syncthreads();
   acc.zero();
   COTTEN_TRACE_POINT(4);
@@ -467,7 +488,16 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   load_first<true>(kfirst, L, kv_src, keys);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(6);
-  make_operands<F>(reduced, a.scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
+  if (a.dlog != nullptr) {
+    // sum_i dO_i . O_i = <scale * S, sum_i qhat_i^T dO_i>: the S image against the sum just
+    // reduced, before that image is replaced (image 1 is free and serves as scratch)
+    float part = 0.0f;
+    for (int e = threadIdx.x; e < F::D * F::D; e += kThreads)
+      part += F::image_at(op0, e % F::D, e / F::D) * reduced.at(e % F::D, e / F::D);
+    part = block_sum(part, reinterpret_cast<float*>(op1));
+    if (threadIdx.x == 0) a.dlog[bh] = part;
+  }
+  make_operands<F>(reduced, scale, op0, op1);  // op0 = dS natural, op1 = dS transposed
   __syncthreads();
   typename F::Operand dS_v, dS_h;
   dS_v.load(op1, L);  // dV = khat dS: contraction over rows of dS
@@ -538,7 +568,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   float* gathered = reinterpret_cast<float*>(smem);
   gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * D * D, a.splits, gathered);
   __syncthreads();
-  make_operands<F>(StateSource<F>{gathered, true}, a.scale, nullptr, op0);
+  make_operands<F>(StateSource<F>{gathered, true}, slice_scale(a, bh), nullptr, op0);
   __syncthreads();
   typename F::Operand Sop;
   Sop.load(op0, L);
@@ -562,7 +592,7 @@ __global__ __launch_bounds__(kThreads, 2) void split_q_kernel(const Args a) {
   float* gathered = reinterpret_cast<float*>(smem);
   gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
   __syncthreads();
-  make_operands<F>(StateSource<F>{gathered, true}, a.scale, op0, nullptr);
+  make_operands<F>(StateSource<F>{gathered, true}, slice_scale(a, bh), op0, nullptr);
   __syncthreads();
   typename F::Acc acc;
   acc.zero();
@@ -588,7 +618,19 @@ __global__ __launch_bounds__(kThreads, 2) void split_kv_kernel(const Args a) {
   float* gathered = reinterpret_cast<float*>(smem);
   gather_partials<F>(a.ds_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
   __syncthreads();
-  make_operands<F>(StateSource<F>{gathered, true}, a.scale, op0, op1);
+  const float scale = slice_scale(a, bh);
+  if (a.dlog != nullptr && split == 0) {
+    // sum_i dO_i . O_i = scale * <S, sum_i qhat_i^T dO_i>: the first workgroup of the slice
+    // sums the partial S once more (image 1 is free and serves as scratch)
+    float* s_total = gathered + DD;
+    gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, s_total);
+    __syncthreads();
+    float part = 0.0f;
+    for (int e = threadIdx.x; e < DD; e += kThreads) part += s_total[e] * gathered[e];
+    part = block_sum(part, reinterpret_cast<float*>(op1));
+    if (threadIdx.x == 0) a.dlog[bh] = scale * part;
+  }
+  make_operands<F>(StateSource<F>{gathered, true}, scale, op0, op1);
   __syncthreads();
   Raw first;
   load_first<true>(first, L, kv_src, keys);
@@ -636,6 +678,8 @@ Args make_args(const Problem& p, const Plan& plan, int D) {
   a.splits = plan.splits;
   a.scale = p.scale;
   a.eps = p.eps;
+  a.scales = p.slice_scale;
+  a.dlog = p.dlog_scale;
   return a;
 }
 

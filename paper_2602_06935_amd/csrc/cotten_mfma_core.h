@@ -270,6 +270,23 @@ struct Bf16x64 {
         p[1] = pack_bf16(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
       }
     }
+    // Sum over this lane's elements of (accumulated block) x (the block of another matrix
+    // read back from an image written by write_image with the same r0, c0).
+    __device__ __forceinline__ float dot_image(const Lane& L, int r0, int c0,
+                                               const unsigned char* image) const {
+      const int c = c0 + (L.lane & 31);
+      float s = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = r0 + 8 * j + 4 * (L.lane >> 5);
+        const uint32_t* p =
+            reinterpret_cast<const uint32_t*>(image + (image_row(c) * kImageStride + r) * 2);
+        const uint32_t lo = p[0], hi = p[1];
+        s += v[4 * j] * __uint_as_float(lo << 16) + v[4 * j + 1] * __uint_as_float(lo & 0xffff0000u);
+        s += v[4 * j + 2] * __uint_as_float(hi << 16) + v[4 * j + 3] * __uint_as_float(hi & 0xffff0000u);
+      }
+      return s;
+    }
     static __device__ __forceinline__ int block_row0(int block) { return 32 * (block >> 1); }
     static __device__ __forceinline__ int block_col0(int block) { return 32 * (block & 1); }
   };
@@ -278,6 +295,12 @@ struct Bf16x64 {
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
                                                           float v0, float v1) {
     *reinterpret_cast<uint32_t*>(image + (image_row(n) * kImageStride + k) * 2) = pack_bf16(v0, v1);
+  }
+  // element k of image row n
+  static __device__ __forceinline__ float image_at(const unsigned char* image, int n, int k) {
+    const uint32_t h =
+        *reinterpret_cast<const uint16_t*>(image + (image_row(n) * kImageStride + k) * 2);
+    return __uint_as_float(h << 16);
   }
 };
 
@@ -391,6 +414,9 @@ struct F32x32 {
     p[0] = v0;
     p[1] = v1;
   }
+  static __device__ __forceinline__ float image_at(const unsigned char* image, int n, int k) {
+    return *reinterpret_cast<const float*>(image + (n * kImageStride + k) * 4);
+  }
 };
 
 // ---- tiles --------------------------------------------------------------------------------
@@ -489,6 +515,13 @@ __device__ __forceinline__ void product_rows(const f32x4_t (&out)[F::NT], float 
   for (int nt = 0; nt < F::NT; ++nt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) p[4 * nt + v] = out[nt][v];
+}
+
+// Sum over the 64 lanes of the wave, every lane gets it (fixed butterfly order).
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int w = 1; w < 64; w <<= 1) x += __shfl_xor(x, w);
+  return x;
 }
 
 // Sum over the four lanes (i16, 0..3) that share a row.

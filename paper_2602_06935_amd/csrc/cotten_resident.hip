@@ -48,7 +48,8 @@ struct Lds {
   static constexpr int kImages = kMaxTiles * kBlockBytes;          // three operand images
   static constexpr int kLive = kImages + 3 * F::kImageBytes;       // one int per tile
   static constexpr int kInv = kLive + 16 * 4;                      // 1/r per tile: 16 q rows, 16 k rows
-  static constexpr int kBytes = kInv + kMaxTiles * 2 * TR * 4;
+  static constexpr int kDots = kInv + kMaxTiles * 2 * TR * 4;     // <S, dS> per state block
+  static constexpr int kBytes = kDots + 4 * 4;
 };
 
 extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -65,6 +66,8 @@ struct Args {
   unsigned char* dV;
   int H, N, slices;
   float scale, eps;
+  const float* scales;  // per-slice scale, or nullptr
+  float* dlog;          // backward: <S, dS> per slice, or nullptr
 };
 
 // The wave's tile: rows 16*tile + r8 + 8h.  `want` bit h: the row takes part.
@@ -134,7 +137,9 @@ __device__ __forceinline__ void publish_inv(float* dst, const Lane& L, const flo
 template <class F>
 __device__ __forceinline__ void build_state(const Lane& L, int block, int x_off, int y_off,
                                             float scale, unsigned char* natural,
-                                            unsigned char* transposed) {
+                                            unsigned char* transposed,
+                                            const unsigned char* other_natural = nullptr,
+                                            float* dot_out = nullptr) {
   typedef typename F::BlockAcc Acc;
   // Images are written with wide stores from an accumulator that holds the block the other
   // way round: the natural image needs the transposed block, i.e. the operands swapped
@@ -152,6 +157,11 @@ __device__ __forceinline__ void build_state(const Lane& L, int block, int x_off,
   const int r0 = Acc::block_row0(block), c0 = Acc::block_col0(block);
   if (transposed != nullptr) acc_t.write_image(L, r0, c0, scale, transposed);
   if (natural != nullptr) acc_n.write_image(L, c0, r0, scale, natural);
+  // <this state, the state whose natural image is given>, this wave's block of it
+  if (dot_out != nullptr) {
+    const float dot = wave_sum(acc_n.dot_image(L, c0, r0, other_natural));
+    if (L.lane == 0) *dot_out = dot;
+  }
 }
 
 // Zero rows for the two tiles at Xt and Yt.
@@ -209,7 +219,8 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       constexpr int kB = F::BlockAcc::kBlocks;
       if (tile >= kWaves - kB) {  // O = qhat S: contraction over rows of S -> transposed image
         __builtin_amdgcn_s_setprio(3);
-        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, a.scale, nullptr, img);
+        const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
+        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, scale, nullptr, img);
         __builtin_amdgcn_s_setprio(0);
       }
       if (mine) {
@@ -307,8 +318,10 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   fetch<true, 2>(rq, rk, a, L0, slice, tile, 0);
   fetch<true, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
+  float* dots = reinterpret_cast<float*>(smem + Lds<F>::kDots);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
     const size_t base = static_cast<size_t>(slice) * N * kRowBytes;
+    const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
     COTTEN_RTRACE_IT(1);
     if (mine) {
       // A tile without a valid key adds nothing to S, and its dK, dV rows are plain zeros.
@@ -330,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       const Lane L = L0.again();
       if (tile >= kWaves - kB) {  // g = dO S^T: contraction over columns of S -> natural image
         __builtin_amdgcn_s_setprio(3);  // the other waves wait for this at the next barrier
-        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, a.scale, img_s, nullptr);
+        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, scale, img_s, nullptr);
         __builtin_amdgcn_s_setprio(0);
       }
       if (mine) {
@@ -348,7 +361,9 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       // dV = khat dS -> transposed image;  h = v dS^T -> natural image
       const Lane L = L0.again();
       __builtin_amdgcn_s_setprio(3);
-      build_state<F>(L, tile - (kWaves - kB), kQt, kGt, a.scale, img_ds, img_dst);
+      // with dlog wanted: this block of <scale * S (its image), sum_i qhat_i^T dO_i>
+      build_state<F>(L, tile - (kWaves - kB), kQt, kGt, scale, img_ds, img_dst, img_s,
+                     a.dlog != nullptr ? dots + (tile - (kWaves - kB)) : nullptr);
       __builtin_amdgcn_s_setprio(0);
     } else {
       const Lane L = L0.again();
@@ -361,6 +376,9 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
     COTTEN_RTRACE_IT(6);
     __syncthreads();
     COTTEN_RTRACE_IT(7);
+    // d loss / d log(scale) = sum_i dO_i . O_i = <scale * S, sum_i qhat_i^T dO_i>, blocks in order
+    if (a.dlog != nullptr && threadIdx.x == 0)
+      a.dlog[slice] = ((dots[0] + dots[1]) + dots[2]) + dots[3];
     {
       const Lane L = L0.again();
       typename F::Operand W;
@@ -390,6 +408,8 @@ hipError_t run(const Problem& p, bool bwd) {
   a.slices = p.B * p.H;
   a.scale = p.scale;
   a.eps = p.eps;
+  a.scales = p.slice_scale;
+  a.dlog = p.dlog_scale;
   const dim3 grid(static_cast<unsigned>(a.slices < kWorkgroups ? a.slices : kWorkgroups));
   const size_t lds = Lds<F>::kBytes;
   const void* kern = bwd ? reinterpret_cast<const void*>(resident_bwd_kernel<F>)
