@@ -249,6 +249,23 @@ def test_long_sequence_split_path(oracle, dtype, d):
         assert np.array_equal(a, c)
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 64)])
+def test_extreme_shapes(oracle, dtype, d):
+    """Very many short slices (persistent workgroups loop 100+ times / tens of thousands of
+    workgroups) and one very long ragged sequence (thousands of tiles per slice, 49999 rows)."""
+    B, H, N = 4096, 8, 16
+    Q, K, V, dO = _case(61, B, H, N, d, dtype)
+    mask = (np.random.default_rng(62).random((B, N)) < 0.5).astype(np.uint8)
+    mask[::7] = 0
+    _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"32768 slices of 16 rows, d={d}")
+    B, H, N = 1, 2, 49999
+    Q, K, V, dO = _case(63, B, H, N, d, dtype)
+    mask = np.zeros((B, N), np.uint8)
+    mask[0, 12345:] = 1
+    mask[0, 30000:30100] = 0
+    _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"one sequence of {N} rows, d={d}")
+
+
 def test_binding_reports_library_errors():
     x = torch.zeros(1, 1, 8, 48, device="cuda")
     with pytest.raises(binding.CottenError) as ei:
