@@ -38,7 +38,9 @@
  *
  * Memory.  Every pointer is a DEVICE pointer owned by the caller.  Q, K, V, O,
  * dO, dQ, dK, dV are [B, H, N, d_h] row-major and contiguous (each slice (b,h) is
- * one contiguous N x d_h block), element type given by `dtype`; mask is [B, N]
+ * one contiguous N x d_h block) or, with params->layout = COTTEN_BNHD, [B, N, H, d_h]
+ * (the layout of the per-head split of a d_model-wide projection: no transposes
+ * around the call); element type given by `dtype`; mask is [B, N]
  * bytes shared by the H heads, or NULL for "every key valid".  Tensor base
  * pointers must be 16-byte aligned.  Outputs must not overlap inputs or each
  * other.  Masked K/V rows are never dereferenced into arithmetic: they may hold
@@ -80,10 +82,18 @@ typedef enum cotten_dtype {
   COTTEN_BF16 = 1  /* bfloat16 I/O, fp32 norms and accumulation   */
 } cotten_dtype;
 
+typedef enum cotten_layout {
+  COTTEN_BHND = 0, /* [B, H, N, d_h]: every slice (b,h) is one contiguous block (default)   */
+  COTTEN_BNHD = 1  /* [B, N, H, d_h]: what the Q/K/V projections of a transformer layer
+                      write and what its output projection reads; the d_h elements of a
+                      row stay contiguous, the rows of a slice are H*d_h elements apart   */
+} cotten_layout;
+
 typedef enum cotten_status {
   COTTEN_OK = 0,
   COTTEN_ERR_NULL_POINTER = -1,         /* a required tensor pointer is NULL            */
-  COTTEN_ERR_BAD_SHAPE = -2,            /* B, H or N < 1, or sizes overflow the launch  */
+  COTTEN_ERR_BAD_SHAPE = -2,            /* B, H or N < 1, sizes overflow the launch, or
+                                           params->layout is not a cotten_layout         */
   COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64}                      */
   COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is neither COTTEN_F32 nor COTTEN_BF16  */
   COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
@@ -103,6 +113,7 @@ typedef struct cotten_params {
                                slice_scale[b*H+h] (finite, > 0) and `scale` is ignored      */
   float* dlog_scale;      /* backward only: device, [B*H] floats, or NULL.  When given it
                              receives sum_i dO_i . O_i of every slice (see above)          */
+  int layout;             /* a cotten_layout: applies to Q, K, V, O, dO, dQ, dK and dV     */
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):

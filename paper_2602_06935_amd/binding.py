@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libcotten_attn.so")
 
 COTTEN_F32 = 0
 COTTEN_BF16 = 1
+COTTEN_BHND = 0
+COTTEN_BNHD = 1
 
 EXPORTS = (
     "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
@@ -29,7 +31,8 @@ EXPORTS = (
 class CottenParams(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int), ("scale", ctypes.c_float), ("eps", ctypes.c_float),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p)]
+                ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p),
+                ("layout", ctypes.c_int)]
 
 
 class CottenError(RuntimeError):
@@ -117,11 +120,26 @@ def _f32_vector(name: str, t: Optional[torch.Tensor], numel: int, dev) -> Option
     return t.data_ptr()
 
 
+def _dims(Q: torch.Tensor, layout: str) -> Tuple[int, int, int, int]:
+    """(B, H, N, d_h) of a tensor stored as `layout` ("bhnd" or "bnhd")."""
+    if Q.dim() != 4:
+        raise ValueError("expected a 4-d tensor")
+    if layout == "bhnd":
+        B, H, N, d = Q.shape
+    elif layout == "bnhd":
+        B, N, H, d = Q.shape
+    else:
+        raise ValueError("layout must be 'bhnd' or 'bnhd'")
+    return B, H, N, d
+
+
 def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
             slice_scale: Optional[torch.Tensor] = None,
-            dlog_scale: Optional[torch.Tensor] = None) -> CottenParams:
+            dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd") -> CottenParams:
     p = CottenParams()
-    slices = Q.shape[0] * Q.shape[1]
+    B, H, _, _ = _dims(Q, layout)
+    p.layout = COTTEN_BNHD if layout == "bnhd" else COTTEN_BHND
+    slices = B * H
     p.slice_scale = _f32_vector("slice_scale", slice_scale, slices, Q.device)
     p.dlog_scale = _f32_vector("dlog_scale", dlog_scale, slices, Q.device)
     p.dtype = _dtype_code(Q)
@@ -150,18 +168,18 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     mask: Optional[torch.Tensor], O: Optional[torch.Tensor] = None, *,
                     scale: Optional[float] = None, eps: Optional[float] = None,
                     stream=None, workspace: Optional[torch.Tensor] = None,
-                    slice_scale: Optional[torch.Tensor] = None) -> torch.Tensor:
+                    slice_scale: Optional[torch.Tensor] = None,
+                    layout: str = "bhnd") -> torch.Tensor:
     """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O.
-    `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`."""
+    `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`;
+    `layout` "bnhd" means all tensors are [B,N,H,d_h] instead of [B,H,N,d_h]."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q)
-    if Q.dim() != 4:
-        raise ValueError("expected [B,H,N,d_h]")
-    B, H, N, d = Q.shape
+    B, H, N, d = _dims(Q, layout)
     if O is None:
         O = torch.empty_like(Q)
     _prep("O", O, Q)
-    prm = _params(Q, scale, eps, workspace, slice_scale)
+    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
@@ -176,20 +194,18 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     eps: Optional[float] = None, stream=None,
                     workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
-                    dlog_scale: Optional[torch.Tensor] = None
+                    dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd"
                     ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
     `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
     d loss / d log(scale) of every slice."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q); dO = _prep("dO", dO, Q)
-    if Q.dim() != 4:
-        raise ValueError("expected [B,H,N,d_h]")
-    B, H, N, d = Q.shape
+    B, H, N, d = _dims(Q, layout)
     dQ = torch.empty_like(Q) if dQ is None else _prep("dQ", dQ, Q)
     dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
     dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
-    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale)
+    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),

@@ -90,6 +90,20 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   } else if (need > 0) {
     if (int rc = own_workspace(need, &p.workspace)) return rc;
   }
+  if (prm->layout != COTTEN_BHND && prm->layout != COTTEN_BNHD) return COTTEN_ERR_BAD_SHAPE;
+  if (prm->layout == COTTEN_BHND) {
+    p.stride_batch = static_cast<long long>(H) * N * d_h;
+    p.stride_head = static_cast<long long>(N) * d_h;
+    p.stride_row = d_h;
+  } else {
+    p.stride_batch = static_cast<long long>(N) * H * d_h;
+    p.stride_head = d_h;
+    p.stride_row = static_cast<long long>(H) * d_h;
+  }
+  // the kernels address the rows of a slice with 31-bit byte offsets
+  if ((static_cast<long long>(N - 1) * p.stride_row + d_h) * (prm->dtype == COTTEN_F32 ? 4 : 2) >=
+      (1ll << 31))
+    return COTTEN_ERR_BAD_SHAPE;
   p.slice_scale = prm->slice_scale;
   p.dlog_scale = bwd ? prm->dlog_scale : nullptr;
   p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
@@ -107,7 +121,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 
-const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr};
+const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr, COTTEN_BHND};
 
 }  // namespace
 

@@ -20,11 +20,20 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kTileRows = kThreads / 8;  // 32
 
+// Element (b,h,n,c) of a tensor is at b*batch + h*head + n*row + c.
+struct ElemStrides {
+  long long batch, head, row;
+  __device__ __forceinline__ size_t slice_base(int bh, int H) const {
+    return static_cast<size_t>(bh / H) * batch + static_cast<size_t>(bh % H) * head;
+  }
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void state_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const uint8_t* __restrict__ mask, float* __restrict__ ws,
-    int H, int N, int splits, int rows_per_split, size_t second_offset, float eps) {
+    int H, int N, int splits, int rows_per_split, size_t second_offset, float eps,
+    ElemStrides lay) {
   constexpr int CH = D / 8;   // columns per lane when loading
   constexpr int R = D / 16;   // each thread accumulates an R x R block of the state
   __shared__ float xs[kTileRows][D];
@@ -34,7 +43,7 @@ __global__ __launch_bounds__(kThreads) void state_kernel(
   const int split = blockIdx.x % splits;
   const int bh = blockIdx.x / splits;
   const bool second = blockIdx.y == 1;  // (Q,dO) -> dS instead of (K,V) -> S
-  const size_t base = static_cast<size_t>(bh) * N * D;
+  const size_t base = lay.slice_base(bh, H);
   const T* __restrict__ X = (second ? Q : K) + base;
   const T* __restrict__ Y = (second ? dO : V) + base;
   const uint8_t* __restrict__ m =
@@ -59,8 +68,8 @@ __global__ __launch_bounds__(kThreads) void state_kernel(
 #pragma unroll
     for (int i = 0; i < CH; ++i) x[i] = y[i] = 0.0f;
     if (live) {
-      load_chunk<T, CH>(X + static_cast<size_t>(row) * D + chunk * CH, x);
-      load_chunk<T, CH>(Y + static_cast<size_t>(row) * D + chunk * CH, y);
+      load_chunk<T, CH>(X + static_cast<size_t>(row) * lay.row + chunk * CH, x);
+      load_chunk<T, CH>(Y + static_cast<size_t>(row) * lay.row + chunk * CH, y);
     }
     float ss = 0.0f;
 #pragma unroll
@@ -124,9 +133,9 @@ __device__ __forceinline__ void load_state(const float* __restrict__ state, floa
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
-    const T* __restrict__ Q, const float* __restrict__ states, T* __restrict__ O, int N,
+    const T* __restrict__ Q, const float* __restrict__ states, T* __restrict__ O, int H, int N,
     int splits, int rows_per_split, float scale, const float* __restrict__ slice_scale,
-    float eps) {
+    float eps, ElemStrides lay) {
   constexpr int CH = D / 8;
   __shared__ float S[D][D];
   __shared__ float qs[kTileRows][D + 4];
@@ -134,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
   const int tid = threadIdx.x;
   const int split = blockIdx.x % splits;
   const int bh = blockIdx.x / splits;
-  const size_t base = static_cast<size_t>(bh) * N * D;
+  const size_t base = lay.slice_base(bh, H);
   const int r_begin = split * rows_per_split;
   const int r_end = min(N, r_begin + rows_per_split);
   const int lrow = tid >> 3, chunk = tid & 7;
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
     float q[CH];
 #pragma unroll
     for (int i = 0; i < CH; ++i) q[i] = 0.0f;
-    if (live) load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * D + chunk * CH, q);
+    if (live) load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * lay.row + chunk * CH, q);
     float ss = 0.0f;
 #pragma unroll
     for (int i = 0; i < CH; ++i) ss += q[i] * q[i];
@@ -166,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
 #pragma unroll
       for (int i = 0; i < CH; ++i) o[i] += qa * S[a][chunk * CH + i];
     }
-    if (live) store_chunk<T, CH>(O + base + static_cast<size_t>(row) * D + chunk * CH, o);
+    if (live) store_chunk<T, CH>(O + base + static_cast<size_t>(row) * lay.row + chunk * CH, o);
     __syncthreads();
   }
 }
@@ -178,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
     const T* __restrict__ dO, const uint8_t* __restrict__ mask,
     const float* __restrict__ states, const float* __restrict__ dstates, T* __restrict__ dQ,
     T* __restrict__ dK, T* __restrict__ dV, int H, int N, int splits, int rows_per_split,
-    float scale, const float* __restrict__ slice_scale, float eps) {
+    float scale, const float* __restrict__ slice_scale, float eps, ElemStrides lay) {
   constexpr int CH = D / 8;
   __shared__ float M0[D][D];              // S^T (dQ blocks)  or dS   (dK/dV blocks)
   __shared__ float M1[D][D];              // unused           or dS^T
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
   const int tid = threadIdx.x;
   const int split = blockIdx.x % splits;
   const int bh = blockIdx.x / splits;
-  const size_t base = static_cast<size_t>(bh) * N * D;
+  const size_t base = lay.slice_base(bh, H);
   const int r_begin = split * rows_per_split;
   const int r_end = min(N, r_begin + rows_per_split);
   const int lrow = tid >> 3, chunk = tid & 7;
@@ -205,8 +214,8 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
 #pragma unroll
       for (int i = 0; i < CH; ++i) q[i] = g[i] = 0.0f;
       if (live) {
-        load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * D + c0, q);
-        load_chunk<T, CH>(dO + base + static_cast<size_t>(row) * D + c0, g);
+        load_chunk<T, CH>(Q + base + static_cast<size_t>(row) * lay.row + c0, q);
+        load_chunk<T, CH>(dO + base + static_cast<size_t>(row) * lay.row + c0, g);
       }
       float ss = 0.0f;
 #pragma unroll
@@ -231,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
       proj = sum8(proj);
 #pragma unroll
       for (int i = 0; i < CH; ++i) g[i] = (g[i] - q[i] * proj) * inv;
-      if (live) store_chunk<T, CH>(dQ + base + static_cast<size_t>(row) * D + c0, g);
+      if (live) store_chunk<T, CH>(dQ + base + static_cast<size_t>(row) * lay.row + c0, g);
       __syncthreads();
     }
   } else {
@@ -250,8 +259,8 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
 #pragma unroll
       for (int i = 0; i < CH; ++i) k[i] = v[i] = 0.0f;
       if (live) {
-        load_chunk<T, CH>(K + base + static_cast<size_t>(row) * D + c0, k);
-        load_chunk<T, CH>(V + base + static_cast<size_t>(row) * D + c0, v);
+        load_chunk<T, CH>(K + base + static_cast<size_t>(row) * lay.row + c0, k);
+        load_chunk<T, CH>(V + base + static_cast<size_t>(row) * lay.row + c0, v);
       }
       float ss = 0.0f;
 #pragma unroll
@@ -285,8 +294,8 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
         gv[i] = live ? gv[i] : 0.0f;
       }
       if (inrange) {
-        store_chunk<T, CH>(dK + base + static_cast<size_t>(row) * D + c0, h);
-        store_chunk<T, CH>(dV + base + static_cast<size_t>(row) * D + c0, gv);
+        store_chunk<T, CH>(dK + base + static_cast<size_t>(row) * lay.row + c0, h);
+        store_chunk<T, CH>(dV + base + static_cast<size_t>(row) * lay.row + c0, gv);
       }
       __syncthreads();
     }
@@ -354,6 +363,10 @@ const float* reduce_generic(const Problem& p, const Plan& plan, int nstates) {
   return reduced;
 }
 
+ElemStrides elem_strides(const Problem& p) {
+  return ElemStrides{p.stride_batch, p.stride_head, p.stride_row};
+}
+
 template <typename T, int D>
 hipError_t run_fwd(const Problem& p, const Plan& plan) {
   const int BH = p.B * p.H;
@@ -361,11 +374,13 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
   hipLaunchKernelGGL((state_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(nullptr), p.mask,
-                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps);
+                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps,
+                     elem_strides(p));
   const float* states = reduce_generic(p, plan, 1);
   hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
-                     static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.N,
-                     plan.splits, plan.rows_per_split, p.scale, p.slice_scale, p.eps);
+                     static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.H, p.N,
+                     plan.splits, plan.rows_per_split, p.scale, p.slice_scale, p.eps,
+                     elem_strides(p));
   return hipGetLastError();
 }
 
@@ -377,7 +392,8 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
   hipLaunchKernelGGL((state_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask,
-                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps);
+                     p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps,
+                     elem_strides(p));
   const float* states = reduce_generic(p, plan, 2);
   const float* dstates = states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * D * D);
   hipLaunchKernelGGL((apply_bwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
@@ -385,7 +401,7 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask, states,
                      dstates, static_cast<T*>(p.dQ), static_cast<T*>(p.dK),
                      static_cast<T*>(p.dV), p.H, p.N, plan.splits, plan.rows_per_split, p.scale,
-                     p.slice_scale, p.eps);
+                     p.slice_scale, p.eps, elem_strides(p));
   if (p.dlog_scale != nullptr)
     hipLaunchKernelGGL(state_inner_product_kernel, dim3(static_cast<unsigned>(BH)),
                        dim3(kThreads), 0, p.stream, states, dstates, D * D, p.scale,

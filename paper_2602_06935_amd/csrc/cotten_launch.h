@@ -18,7 +18,11 @@ struct Problem {
   void* dK;
   void* dV;
   int B, H, N, D;
+  // element (b,h,n,c) of every tensor is at b*stride_batch + h*stride_head + n*stride_row + c
+  // (in elements): [B,H,N,d] or [B,N,H,d]
+  long long stride_batch, stride_head, stride_row;
   int dtype;            // 0 = f32, 1 = bf16
+  long long elem_bytes() const { return dtype == 0 ? 4 : 2; }
   float scale, eps;
   const float* slice_scale;  // [B*H] or nullptr: per-slice scale instead of `scale`
   float* dlog_scale;         // backward only, [B*H] or nullptr: receives <S, dS> per slice

@@ -166,7 +166,7 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
 #pragma unroll
     for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
     const int row = row0 + L.i16;
-    if (row < rows.limit) store_product_row<F, STREAM>(O, row, L, o);
+    if (row < rows.limit) store_product_row<F, STREAM>(O, row, src.row, L, o);
     wave_lds_fence();
   });
 }
@@ -203,7 +203,7 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
     product_rows<F>(out, g);
     project_rows<F, false>(g, e, inv_r, L);
     const int row = row0 + L.i16;
-    if (row < rows.limit) store_product_row<F, STREAM>(dQ, row, L, g);
+    if (row < rows.limit) store_product_row<F, STREAM>(dQ, row, src.row, L, g);
     wave_lds_fence();
   });
 }
@@ -224,8 +224,8 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
 #pragma unroll
       for (int i = 0; i < 2 * F::EPL; ++i) zeros[i] = 0.0f;
       if (row < rows.limit) {
-        store_product_row<F, STREAM>(dK, row, L, zeros);
-        store_product_row<F, STREAM>(dV, row, L, zeros);
+        store_product_row<F, STREAM>(dK, row, src.row, L, zeros);
+        store_product_row<F, STREAM>(dV, row, src.row, L, zeros);
       }
       return;
     }
@@ -246,8 +246,8 @@ __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
     for (int i = 0; i < 2 * F::EPL; ++i) gv[i] *= inv_r;
     project_rows_raw<F>(hh, xk, inv_r, L);
     if (row < rows.limit) {
-      store_product_row<F, STREAM>(dK, row, L, hh);
-      store_product_row<F, STREAM>(dV, row, L, gv);
+      store_product_row<F, STREAM>(dK, row, src.row, L, hh);
+      store_product_row<F, STREAM>(dV, row, src.row, L, gv);
     }
     wave_lds_fence();
   });
@@ -390,6 +390,7 @@ struct Args {
   float* s_partials;
   float* ds_partials;
   int H, N, splits;
+  Strides st;
   float scale, eps;
   const float* scales;  // per-slice scale, or nullptr
   float* dlog;          // backward: sum_i dO_i . O_i per slice, or nullptr
@@ -418,12 +419,12 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int bh = blockIdx.x, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   const int n_tiles = (N + TR - 1) / TR;
   uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
-  const Src q_src(a.Q + base, a.Q + base, N), kv_src(a.K + base, a.V + base, N);
+  const Src q_src(a.Q + base, a.Q + base, N, a.st.row), kv_src(a.K + base, a.V + base, N, a.st.row);
 
   Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
   load_first<false>(qfirst, L, q_src, all);
@@ -451,14 +452,14 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int bh = blockIdx.x, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   const int n_tiles = (N + TR - 1) / TR;
   uint8_t* kflags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
   const StateSource<F> reduced{reinterpret_cast<const float*>(smem), false};
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
-  const Src q_src(a.Q + base, a.dO + base, N), kv_src(a.K + base, a.V + base, N);
+  const Src q_src(a.Q + base, a.dO + base, N, a.st.row), kv_src(a.K + base, a.V + base, N, a.st.row);
 
   COTTEN_TRACE_POINT(0);
   Raw qfirst, kfirst;
@@ -531,11 +532,11 @@ __global__ __launch_bounds__(kThreads, 2) void split_state_kernel(const Args a) 
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   COTTEN_TRACE_POINT(0);
   uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   const Rows rows = split_rows(N, split, a.splits, flags);
-  const Src src(a.K + base, a.V + base, N);
+  const Src src(a.K + base, a.V + base, N, a.st.row);
   if (flags != nullptr) {
     fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, rows);
     __syncthreads();
@@ -559,10 +560,10 @@ __global__ __launch_bounds__(kThreads, 2) void split_apply_fwd_kernel(const Args
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows all = split_rows(N, split, a.splits, nullptr);
-  const Src q_src(a.Q + base, a.Q + base, N);
+  const Src q_src(a.Q + base, a.Q + base, N, a.st.row);
   Raw first;
   load_first<false>(first, L, q_src, all);
   float* gathered = reinterpret_cast<float*>(smem);
@@ -583,10 +584,10 @@ __global__ __launch_bounds__(kThreads, 2) void split_q_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows all = split_rows(N, split, a.splits, nullptr);
-  const Src q_src(a.Q + base, a.dO + base, N);
+  const Src q_src(a.Q + base, a.dO + base, N, a.st.row);
   Raw first;
   load_first<true>(first, L, q_src, all);
   float* gathered = reinterpret_cast<float*>(smem);
@@ -608,12 +609,12 @@ __global__ __launch_bounds__(kThreads, 2) void split_kv_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits, N = a.N;
-  const size_t base = static_cast<size_t>(bh) * N * kRowBytes;
+  const size_t base = a.st.slice_base(bh, a.H);
   unsigned char* op0 = smem + Layout<F>::kImage0;
   unsigned char* op1 = smem + Layout<F>::kImage1;
   uint8_t* flags = a.mask != nullptr ? smem + Layout<F>::kFlags : nullptr;
   const Rows keys = split_rows(N, split, a.splits, flags);
-  const Src kv_src(a.K + base, a.V + base, N);
+  const Src kv_src(a.K + base, a.V + base, N, a.st.row);
   if (flags != nullptr) fill_flags(flags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
   float* gathered = reinterpret_cast<float*>(smem);
   gather_partials<F>(a.ds_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
@@ -676,6 +677,8 @@ Args make_args(const Problem& p, const Plan& plan, int D) {
   a.H = p.H;
   a.N = p.N;
   a.splits = plan.splits;
+  a.st = Strides{p.stride_batch * p.elem_bytes(), p.stride_head * p.elem_bytes(),
+                 static_cast<int>(p.stride_row * p.elem_bytes())};
   a.scale = p.scale;
   a.eps = p.eps;
   a.scales = p.slice_scale;

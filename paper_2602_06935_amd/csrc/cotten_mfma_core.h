@@ -15,7 +15,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int TR = 16;               // rows per wave tile
-constexpr int kRowBytes = 128;       // one row of Q, K, V ... in global memory
+constexpr int kRowBytes = 128;       // bytes of one row of Q, K, V ... (d_h elements)
 constexpr int kTileStride = 144;     // bytes per row of an LDS tile (128 + 16 of padding)
 constexpr int kTileBytes = TR * kTileStride;
 
@@ -444,10 +444,24 @@ struct Raw {
 // and causes no memory traffic: rows that do not take part are skipped without a branch, so
 // every tile issues the same number of load instructions and the hardware's in-order load
 // counter can tell "this tile has arrived" from "the tiles prefetched after it have not".
+// Where the rows of the slices are in global memory (bytes): slice (b,h) starts at
+// b*batch + h*head and its rows are `row` apart.  [B,H,N,d]: batch = H*N*128, head = N*128,
+// row = 128;  [B,N,H,d]: batch = N*H*128, head = 128, row = H*128.
+struct Strides {
+  long long batch, head;
+  int row;
+  __device__ __forceinline__ size_t slice_base(int bh, int H) const {
+    return static_cast<size_t>(bh / H) * batch + static_cast<size_t>(bh % H) * head;
+  }
+};
+
 struct Src {
   __amdgpu_buffer_rsrc_t x, y;
-  __device__ __forceinline__ Src(const unsigned char* X, const unsigned char* Y, int N) {
-    const int bytes = N * kRowBytes;
+  int row;  // bytes between rows
+  __device__ __forceinline__ Src(const unsigned char* X, const unsigned char* Y, int N,
+                                 int row_stride)
+      : row(row_stride) {
+    const int bytes = (N - 1) * row_stride + kRowBytes;
     x = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(X), 0, bytes, 0x00020000);
     y = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Y), 0, bytes, 0x00020000);
   }
@@ -467,7 +481,7 @@ __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const Src& src, 
     const int row = row0 + L.r8 + 8 * h;
     bool live = tile_ok && row < rows.limit;
     if (rows.flags != nullptr) live = live && rows.flags[tile_ok ? lt * TR + L.r8 + 8 * h : 0] != 0;
-    const uint32_t off = live ? static_cast<uint32_t>(row) * kRowBytes + L.ch * 16 : kOutOfBuffer;
+    const uint32_t off = live ? static_cast<uint32_t>(row) * src.row + L.ch * 16 : kOutOfBuffer;
     r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
     if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
     else r.y[h] = u32x4_t{0, 0, 0, 0};
@@ -572,14 +586,15 @@ __device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
 // better left with the default policy in every kernel here.
 template <class F, bool STREAM>
 __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ dst, int row,
-                                                  const Lane& L, const float (&p)[2 * F::EPL]) {
+                                                  int row_stride, const Lane& L,
+                                                  const float (&p)[2 * F::EPL]) {
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     float c[F::EPL];
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];
     u32x4_t* at =
-        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * kRowBytes + 64 * j + 16 * L.g16);
+        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * row_stride + 64 * j + 16 * L.g16);
     if (STREAM) __builtin_nontemporal_store(F::pack(c), at);
     else *at = F::pack(c);
   }

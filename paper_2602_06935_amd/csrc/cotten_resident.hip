@@ -65,6 +65,7 @@ struct Args {
   unsigned char* dK;
   unsigned char* dV;
   int H, N, slices;
+  Strides st;
   float scale, eps;
   const float* scales;  // per-slice scale, or nullptr
   float* dlog;          // backward: <S, dS> per slice, or nullptr
@@ -78,7 +79,7 @@ __device__ __forceinline__ void load_tile(Raw& r, const Lane& L, const Src& src,
   for (int h = 0; h < 2; ++h) {
     const int row = tile * TR + L.r8 + 8 * h;
     const uint32_t off =
-        ((want >> h) & 1) ? static_cast<uint32_t>(row) * kRowBytes + L.ch * 16 : kOutOfBuffer;
+        ((want >> h) & 1) ? static_cast<uint32_t>(row) * src.row + L.ch * 16 : kOutOfBuffer;
     r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
     if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
     else r.y[h] = u32x4_t{0, 0, 0, 0};
@@ -108,17 +109,17 @@ template <bool BWD, int PARTS = 3>
 __device__ __forceinline__ void fetch(Raw& rq, Raw& rk, const Args& a, const Lane& L, int slice,
                                       int tile, int keys) {
   const bool ok = slice < a.slices;
-  const size_t base = ok ? static_cast<size_t>(slice) * a.N * kRowBytes : 0;
+  const size_t base = ok ? a.st.slice_base(slice, a.H) : 0;
   int rows = 0;
 #pragma unroll
   for (int h = 0; h < 2; ++h)
     rows |= static_cast<int>(ok && tile * TR + L.r8 + 8 * h < a.N) << h;
   if (PARTS & 1) {
-    const Src kv_src(a.K + base, a.V + base, a.N);
+    const Src kv_src(a.K + base, a.V + base, a.N, a.st.row);
     load_tile<true>(rk, L, kv_src, tile, rows & keys);
   }
   if (PARTS & 2) {
-    const Src q_src(a.Q + base, (BWD ? a.dO : a.Q) + base, a.N);
+    const Src q_src(a.Q + base, (BWD ? a.dO : a.Q) + base, a.N, a.st.row);
     load_tile<BWD>(rq, L, q_src, tile, rows);
   }
 }
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
       const int row = tile * TR + L.i16;
       if (row < N)
-        store_product_row<F, true>(a.O + static_cast<size_t>(slice) * N * kRowBytes, row, L, o);
+        store_product_row<F, true>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
     }
   }
 }
@@ -262,7 +263,8 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
 template <class F>
 __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N,
                                            const typename F::Operand& W, const int* live,
-                                           const float* invs, unsigned char* dst) {
+                                           const float* invs, unsigned char* dst,
+                                           int row_stride) {
   const unsigned char* tb = smem + t * kBlockBytes;
   const int row = t * TR + L.i16;
   float p[2 * F::EPL];
@@ -281,7 +283,7 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
       project_rows<F, true>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
     }
   }
-  if (row < N) store_product_row<F, true>(dst, row, L, p);
+  if (row < N) store_product_row<F, true>(dst, row, row_stride, L, p);
 }
 
 // Backward, per slice (B = workgroup barrier):
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   int keys = key_rows(a, L0, slice + stride, tile);
   float* dots = reinterpret_cast<float*>(smem + Lds<F>::kDots);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
-    const size_t base = static_cast<size_t>(slice) * N * kRowBytes;
+    const size_t base = a.st.slice_base(slice, a.H);
     const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
     COTTEN_RTRACE_IT(1);
     if (mine) {
@@ -371,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       W.load(img_s, L);
 #pragma unroll 1
       for (int t = tile; t < n_tiles; t += kWaves - kB)
-        apply_tile<F>(L, 0, t, N, W, live, invs, a.dQ + base);
+        apply_tile<F>(L, 0, t, N, W, live, invs, a.dQ + base, a.st.row);
     }
     COTTEN_RTRACE_IT(6);
     __syncthreads();
@@ -385,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       W.load(kv_kind == 1 ? img_dst : img_ds, L);
       unsigned char* dst = (kv_kind == 1 ? a.dV : a.dK) + base;
 #pragma unroll 1
-      for (int t = tile >> 1; t < n_tiles; t += kWaves / 2) apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst);
+      for (int t = tile >> 1; t < n_tiles; t += kWaves / 2) apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst, a.st.row);
     }
     __syncthreads();  // the tiles and images are rewritten for the next slice
   }
@@ -406,6 +408,8 @@ hipError_t run(const Problem& p, bool bwd) {
   a.H = p.H;
   a.N = p.N;
   a.slices = p.B * p.H;
+  a.st = Strides{p.stride_batch * p.elem_bytes(), p.stride_head * p.elem_bytes(),
+                 static_cast<int>(p.stride_row * p.elem_bytes())};
   a.scale = p.scale;
   a.eps = p.eps;
   a.scales = p.slice_scale;

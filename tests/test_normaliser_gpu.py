@@ -98,3 +98,40 @@ def test_normaliser_argument_errors():
     assert lib.cotten_normaliser_fwd(None, None, None, 1, 1, 1, None) == -1
     assert lib.cotten_normaliser_bwd(None, None, None, 1, 1, 1, None) == -1
     assert lib.cotten_normaliser_fwd(m.data_ptr(), None, m.data_ptr(), 0, 1, 1, None) == -2
+
+
+@pytest.mark.parametrize("label,dtype,B,H,N,d", CASES)
+def test_bnhd_layout_equals_bhnd_bit_for_bit(label, dtype, B, H, N, d):
+    """[B,N,H,d_h] tensors (the per-head view of a d_model-wide projection): the same kernels
+    with other strides, so every output must equal the [B,H,N,d_h] call bit for bit."""
+    print(f"[layout] {label}: {dtype} B={B} H={H} N={N} d={d}", flush=True)
+    Q, K, V, dO, mask, lengths, m = _inputs(1900 + N + d, dtype, B, H, N, d)
+    tq, tk, tv, tg = (to_gpu(x, dtype) for x in (Q, K, V, dO))
+    tm = torch.from_numpy(mask).cuda()
+    ss = torch.rand(B, H, device="cuda") + 0.1
+    dlog = torch.empty(B, H, device="cuda")
+    O = binding.cotten_attn_fwd(tq, tk, tv, tm, slice_scale=ss)
+    grads = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, slice_scale=ss, dlog_scale=dlog)
+    sw = lambda t: t.permute(0, 2, 1, 3).contiguous()      # [B,H,N,d] -> [B,N,H,d]
+    dlog2 = torch.empty_like(dlog)
+    O2 = binding.cotten_attn_fwd(sw(tq), sw(tk), sw(tv), tm, slice_scale=ss, layout="bnhd")
+    grads2 = binding.cotten_attn_bwd(sw(tq), sw(tk), sw(tv), tm, sw(tg), slice_scale=ss,
+                                     dlog_scale=dlog2, layout="bnhd")
+    torch.cuda.synchronize()
+    assert O2.shape == (B, N, H, d)
+    assert torch.equal(sw(O), O2) and torch.equal(dlog, dlog2)
+    for a, c in zip(grads, grads2):
+        assert torch.equal(sw(a), c)
+
+
+def test_layout_argument_errors():
+    lib = binding.load_library()
+    t = torch.zeros(1, 1, 16, 32, device="cuda")
+    prm = binding.CottenParams()
+    prm.dtype, prm.scale, prm.eps, prm.layout = 0, 0.0, -1.0, 7
+    import ctypes
+    rc = lib.cotten_attn_fwd_ex(t.data_ptr(), t.data_ptr(), t.data_ptr(), None, t.data_ptr(),
+                                1, 1, 16, 32, None, ctypes.byref(prm))
+    assert rc == -2
+    with pytest.raises(ValueError):
+        binding.cotten_attn_fwd(t, t, t, None, layout="nhbd")
