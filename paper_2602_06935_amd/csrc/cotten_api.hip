@@ -82,14 +82,6 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
 
   cotten::Problem p{};
   if (int rc = resolve(prm, N, &p.scale, &p.eps)) return rc;
-  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
-  const size_t need = plan.workspace_floats * sizeof(float);
-  if (prm->workspace != nullptr) {
-    if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
-    p.workspace = static_cast<float*>(prm->workspace);
-  } else if (need > 0) {
-    if (int rc = own_workspace(need, &p.workspace)) return rc;
-  }
   if (prm->layout != COTTEN_BHND && prm->layout != COTTEN_BNHD) return COTTEN_ERR_BAD_SHAPE;
   if (prm->layout == COTTEN_BHND) {
     p.stride_batch = static_cast<long long>(H) * N * d_h;
@@ -104,6 +96,14 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   if ((static_cast<long long>(N - 1) * p.stride_row + d_h) * (prm->dtype == COTTEN_F32 ? 4 : 2) >=
       (1ll << 31))
     return COTTEN_ERR_BAD_SHAPE;
+  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
+  const size_t need = plan.workspace_floats * sizeof(float);
+  if (prm->workspace != nullptr) {
+    if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
+    p.workspace = static_cast<float*>(prm->workspace);
+  } else if (need > 0) {
+    if (int rc = own_workspace(need, &p.workspace)) return rc;
+  }
   p.slice_scale = prm->slice_scale;
   p.dlog_scale = bwd ? prm->dlog_scale : nullptr;
   p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;

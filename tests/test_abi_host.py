@@ -71,6 +71,19 @@ def test_validation_errors_touch_no_device(lib):
     assert _fwd(lib, prm=p) == -7
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, float("inf"), None, 0)
     assert _fwd(lib, prm=p) == -7
+    # layout must be one of the two enumerators
+    p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 5)
+    assert _fwd(lib, prm=p) == -2
+    # rows of a slice are addressed with 31-bit byte offsets: 2^24 rows of 128 bytes do not
+    # fit, nor do 2^22 rows that lie 8 heads x 128 bytes apart in the [B,N,H,d] layout
+    assert _fwd(lib, N=1 << 24) == -2
+    p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, binding.COTTEN_BNHD)
+    assert _fwd(lib, H=8, N=1 << 22, prm=p) == -2
+    # the normaliser entry points validate on the host as well
+    assert lib.cotten_normaliser_fwd(None, None, 0x1000, 4, 2, 50, None) == -1
+    assert lib.cotten_normaliser_fwd(0x1000, None, None, 4, 2, 50, None) == -1
+    assert lib.cotten_normaliser_bwd(0x1000, None, None, 4, 2, 50, None) == -1
+    assert lib.cotten_normaliser_bwd(0x1000, None, 0x2000, 0, 2, 50, None) == -2
 
 
 def test_workspace_rules(lib):
