@@ -79,7 +79,11 @@ extern "C" {
 
 typedef enum cotten_dtype {
   COTTEN_F32 = 0,  /* float I/O                                   */
-  COTTEN_BF16 = 1  /* bfloat16 I/O, fp32 norms and accumulation   */
+  COTTEN_BF16 = 1, /* bfloat16 I/O, fp32 norms and accumulation   */
+  COTTEN_F16 = 2   /* IEEE half I/O, fp32 norms and accumulation (the mixed-precision mode
+                      the paper trains in).  Results beyond +-65504 become Inf; the state
+                      scale*S handed to the matrix cores is held in half as well, so
+                      |scale * S| must stay in range (it does for scale ~ 1/N)           */
 } cotten_dtype;
 
 typedef enum cotten_layout {
@@ -95,7 +99,7 @@ typedef enum cotten_status {
   COTTEN_ERR_BAD_SHAPE = -2,            /* B, H or N < 1, sizes overflow the launch, or
                                            params->layout is not a cotten_layout         */
   COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64}                      */
-  COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is neither COTTEN_F32 nor COTTEN_BF16  */
+  COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is not a cotten_dtype                  */
   COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
   COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* params->workspace_bytes below the requirement */
   COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf   */

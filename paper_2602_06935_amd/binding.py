@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcotten_attn.so")
 
 COTTEN_F32 = 0
 COTTEN_BF16 = 1
+COTTEN_F16 = 2
 COTTEN_BHND = 0
 COTTEN_BNHD = 1
 
@@ -91,6 +92,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return COTTEN_F32
     if t.dtype == torch.bfloat16:
         return COTTEN_BF16
+    if t.dtype == torch.float16:
+        return COTTEN_F16
     raise TypeError(f"unsupported I/O dtype {t.dtype}")
 
 

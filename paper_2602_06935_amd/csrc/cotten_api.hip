@@ -18,7 +18,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // Shape checks shared by both directions.  Pure host arithmetic.
 int check_shape(int B, int H, int N, int d_h, int dtype) {
-  if (dtype != COTTEN_F32 && dtype != COTTEN_BF16) return COTTEN_ERR_BAD_DTYPE;
+  if (dtype != COTTEN_F32 && dtype != COTTEN_BF16 && dtype != COTTEN_F16)
+    return COTTEN_ERR_BAD_DTYPE;
   if (B < 1 || H < 1 || N < 1) return COTTEN_ERR_BAD_SHAPE;
   if (!head_dim_ok(d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
   const long long slices = static_cast<long long>(B) * H;
@@ -181,7 +182,7 @@ const char* cotten_status_string(int status) {
     case COTTEN_ERR_NULL_POINTER: return "a required pointer is NULL";
     case COTTEN_ERR_BAD_SHAPE: return "B, H and N must be >= 1 and within launch limits";
     case COTTEN_ERR_UNSUPPORTED_HEAD_DIM: return "d_h must be 16, 32 or 64";
-    case COTTEN_ERR_BAD_DTYPE: return "dtype must be COTTEN_F32 or COTTEN_BF16";
+    case COTTEN_ERR_BAD_DTYPE: return "dtype must be COTTEN_F32, COTTEN_BF16 or COTTEN_F16";
     case COTTEN_ERR_MISALIGNED: return "tensor and workspace pointers must be 16-byte aligned";
     case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";
     case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite";

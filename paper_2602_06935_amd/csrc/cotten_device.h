@@ -10,7 +10,15 @@ struct bf16 {
   uint16_t bits;
 };
 
+// IEEE half storage type.
+struct f16 {
+  uint16_t bits;
+};
+
 __device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(f16 x) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, x.bits));
+}
 __device__ __forceinline__ float to_float(bf16 x) {
   return __uint_as_float(static_cast<uint32_t>(x.bits) << 16);
 }
@@ -32,6 +40,14 @@ __device__ __forceinline__ bf16 from_float<bf16>(float x) {
     u += 0x7fffu + ((u >> 16) & 1u);
     r.bits = static_cast<uint16_t>(u >> 16);
   }
+  return r;
+}
+
+// Round to nearest even (hardware conversion); values beyond the half range become Inf.
+template <>
+__device__ __forceinline__ f16 from_float<f16>(float x) {
+  f16 r;
+  r.bits = __builtin_bit_cast(uint16_t, static_cast<_Float16>(x));
   return r;
 }
 

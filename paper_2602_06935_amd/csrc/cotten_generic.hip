@@ -486,11 +486,15 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
 }
 
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan) {
-  return p.dtype == 0 ? dispatch_d<float>(p, plan, false) : dispatch_d<bf16>(p, plan, false);
+  return p.dtype == 0   ? dispatch_d<float>(p, plan, false)
+         : p.dtype == 1 ? dispatch_d<bf16>(p, plan, false)
+                        : dispatch_d<f16>(p, plan, false);
 }
 
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan) {
-  return p.dtype == 0 ? dispatch_d<float>(p, plan, true) : dispatch_d<bf16>(p, plan, true);
+  return p.dtype == 0   ? dispatch_d<float>(p, plan, true)
+         : p.dtype == 1 ? dispatch_d<bf16>(p, plan, true)
+                        : dispatch_d<f16>(p, plan, true);
 }
 
 hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B,

@@ -21,7 +21,7 @@ struct Problem {
   // element (b,h,n,c) of every tensor is at b*stride_batch + h*stride_head + n*stride_row + c
   // (in elements): [B,H,N,d] or [B,N,H,d]
   long long stride_batch, stride_head, stride_row;
-  int dtype;            // 0 = f32, 1 = bf16
+  int dtype;            // 0 = f32, 1 = bf16, 2 = f16
   long long elem_bytes() const { return dtype == 0 ? 4 : 2; }
   float scale, eps;
   const float* slice_scale;  // [B*H] or nullptr: per-slice scale instead of `scale`
@@ -60,12 +60,12 @@ void launch_reduce_states(const float* partial, float* reduced, int splits, int 
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 
-// MFMA path: bf16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows).
+// MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows).
 bool mfma_supports(int dtype, int D);
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 
-// Resident kernels: short bf16 sequences (a slice fits the LDS of one compute unit).  With
+// Resident kernels: short bf16 / fp16 sequences (a slice fits the LDS of one compute unit).  With
 // fp32 rows the matrix cores, 16 times slower there, bound each of their phases and the
 // tile-streaming kernels are faster, so those keep all fp32 shapes.
 bool resident_supports(int dtype, int D, int N);

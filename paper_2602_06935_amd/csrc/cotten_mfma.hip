@@ -1,5 +1,5 @@
 // MFMA path of the cosine attention for 128-byte rows on gfx950:
-//     bf16 I/O with d_h = 64   and   fp32 I/O with d_h = 32.
+//     bf16 or fp16 I/O with d_h = 64   and   fp32 I/O with d_h = 32.
 //
 // Work unit: one wavefront streams 16-row tiles of a slice.  A tile is loaded with
 // 128-bit accesses (8 lanes per 128-byte row, 8 rows per instruction) and parked in a
@@ -730,14 +730,20 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
 
 }  // namespace
 
-bool mfma_supports(int dtype, int D) { return (dtype == 1 && D == 64) || (dtype == 0 && D == 32); }
+bool mfma_supports(int dtype, int D) {
+  return ((dtype == 1 || dtype == 2) && D == 64) || (dtype == 0 && D == 32);
+}
 
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan) {
-  return p.dtype == 1 ? run_fwd<Bf16x64>(p, plan) : run_fwd<F32x32>(p, plan);
+  return p.dtype == 1   ? run_fwd<Bf16x64>(p, plan)
+         : p.dtype == 2 ? run_fwd<F16x64>(p, plan)
+                        : run_fwd<F32x32>(p, plan);
 }
 
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan) {
-  return p.dtype == 1 ? run_bwd<Bf16x64>(p, plan) : run_bwd<F32x32>(p, plan);
+  return p.dtype == 1   ? run_bwd<Bf16x64>(p, plan)
+         : p.dtype == 2 ? run_bwd<F16x64>(p, plan)
+                        : run_bwd<F32x32>(p, plan);
 }
 
 }  // namespace cotten

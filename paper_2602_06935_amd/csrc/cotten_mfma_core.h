@@ -86,8 +86,62 @@ struct Lane {
 //                         an LDS image op[n][k] (k contiguous); F::apply(tile, W, out)
 //   F::write_image        builds such images from a reduced state
 
-struct Bf16x64 {
-  typedef bf16 io_t;
+// The two 16-bit element types of the d_h = 64 format: how a pair sits in a 32-bit word, and
+// the matrix-core and transposing-read instructions of the type.
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+struct Bf16Elem {
+  typedef bf16x8_t v8;
+  typedef bf16x4_t v4;
+  static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+  static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16(a, b); }
+  static __device__ __forceinline__ f32x16_t mfma32(v8 a, v8 b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ f32x4_t mfma16(v8 a, v8 b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ v4 read_tr(const unsigned char* p) {
+    typedef v4 __attribute__((address_space(3))) * lds_v4;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p));
+  }
+};
+
+struct F16Elem {
+  typedef f16x8_t v8;
+  typedef f16x4_t v4;
+  static __device__ __forceinline__ float lo(uint32_t w) {
+    return static_cast<float>(__builtin_bit_cast(f16x2_t, w)[0]);
+  }
+  static __device__ __forceinline__ float hi(uint32_t w) {
+    return static_cast<float>(__builtin_bit_cast(f16x2_t, w)[1]);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // round to nearest even
+    f16x2_t v;
+    v[0] = static_cast<_Float16>(a);
+    v[1] = static_cast<_Float16>(b);
+    return __builtin_bit_cast(uint32_t, v);
+  }
+  static __device__ __forceinline__ f32x16_t mfma32(v8 a, v8 b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ f32x4_t mfma16(v8 a, v8 b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ v4 read_tr(const unsigned char* p) {
+    typedef __fp16 raw4 __attribute__((ext_vector_type(4)));
+    typedef raw4 __attribute__((address_space(3))) * lds_v4;
+    return __builtin_bit_cast(v4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_v4)(p)));
+  }
+};
+
+template <class E>
+struct Half64 {
+  typedef typename E::v8 v8_t;
+  typedef typename E::v4 v4_t;
   static constexpr int D = 64, EPL = 8, NT = 4;
   // tiles in flight ahead of the one being processed, per pass (register budget permitting)
   static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 2, kDepthKV = 2, kDepthQAccum = 1;
@@ -107,28 +161,27 @@ struct Bf16x64 {
   static __device__ __forceinline__ void unpack(const u32x4_t r, float (&f)[8]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(r[i] << 16);
-      f[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+      f[2 * i] = E::lo(r[i]);
+      f[2 * i + 1] = E::hi(r[i]);
     }
   }
   static __device__ __forceinline__ u32x4_t pack(const float (&f)[8]) {
     u32x4_t r;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    for (int i = 0; i < 4; ++i) r[i] = E::pack2(f[2 * i], f[2 * i + 1]);
     return r;
   }
 
   // Operand of the 32x32x16 MFMA for a contraction over the 16 tile rows: lane gets, for
   // column cbase + lane%32, the 8 rows 8*(lane/32) .. +7 (two transposing reads of 4 rows).
-  static __device__ __forceinline__ bf16x8_t rows_operand(const unsigned char* T, const Lane& L,
+  static __device__ __forceinline__ v8_t rows_operand(const unsigned char* T, const Lane& L,
                                                           int cbase) {
     const int s = L.i16;
     const int row = 8 * (L.g16 >> 1) + (s >> 2);
     const int col = cbase + 16 * (L.g16 & 1) + 4 * (s & 3);
-    typedef bf16x4_t __attribute__((address_space(3))) * lds_v4;
     const unsigned char* p = T + row * kTileStride + col * 2;
-    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p));
-    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p + 4 * kTileStride));
+    const v4_t lo = E::read_tr(p);
+    const v4_t hi = E::read_tr(p + 4 * kTileStride);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 
@@ -145,7 +198,7 @@ struct Bf16x64 {
     // += (X tile)^T (Y tile)
     __device__ __forceinline__ void mfma(const unsigned char* Xt, const unsigned char* Yt,
                                          const Lane& L) {
-      bf16x8_t a[2], b[2];
+      v8_t a[2], b[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         a[t] = rows_operand(Xt, L, 32 * t);
@@ -155,7 +208,7 @@ struct Bf16x64 {
       for (int at = 0; at < 2; ++at)
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
-          v[at][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[at], b[ct], v[at][ct], 0, 0, 0);
+          v[at][ct] = E::mfma32(a[at], b[ct], v[at][ct]);
     }
     // group g = 0..15 of four consecutive state rows held by this lane, and where it lives
     __device__ __forceinline__ f32x4_t group(int g) const { return quad(v[g >> 3][(g >> 2) & 1], g & 3); }
@@ -169,13 +222,13 @@ struct Bf16x64 {
   };
 
   struct Operand {
-    bf16x8_t frag[4][2];
+    v8_t frag[4][2];
     __device__ __forceinline__ void load(const unsigned char* image, const Lane& L) {
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-          frag[nt][ks] = *reinterpret_cast<const bf16x8_t*>(
+          frag[nt][ks] = *reinterpret_cast<const v8_t*>(
               image + ((16 * nt + L.i16) * kImageStride + 8 * L.g16 + 32 * ks) * 2);
     }
   };
@@ -184,17 +237,17 @@ struct Bf16x64 {
   // holds bytes 64j + 16*g16 .. +15 (j = 0, 1) of row i16, the same columns an apply product
   // leaves it with, so a tile fetched this way also serves as the epilogue's row operand.
   struct TileRows {
-    bf16x8_t a[2];
+    v8_t a[2];
     __device__ __forceinline__ void load(const unsigned char* T, const Lane& L) {
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
-        a[ks] = *reinterpret_cast<const bf16x8_t*>(T + L.i16 * kTileStride + (8 * L.g16 + 32 * ks) * 2);
+        a[ks] = *reinterpret_cast<const v8_t*>(T + L.i16 * kTileStride + (8 * L.g16 + 32 * ks) * 2);
     }
     __device__ __forceinline__ void unpack(float (&f)[16]) const {
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         float h[8];
-        Bf16x64::unpack(__builtin_bit_cast(u32x4_t, a[ks]), h);
+        Half64::unpack(__builtin_bit_cast(u32x4_t, a[ks]), h);
 #pragma unroll
         for (int i = 0; i < 8; ++i) f[8 * ks + i] = h[i];
       }
@@ -206,7 +259,7 @@ struct Bf16x64 {
       for (int ks = 0; ks < 2; ++ks) {
         u32x4_t r = __builtin_bit_cast(u32x4_t, a[ks]);
         asm volatile("" : "+v"(r));
-        a[ks] = __builtin_bit_cast(bf16x8_t, r);
+        a[ks] = __builtin_bit_cast(v8_t, r);
       }
     }
   };
@@ -219,7 +272,7 @@ struct Bf16x64 {
       out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
-        out[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W.frag[nt][ks], X.a[ks], out[nt], 0, 0, 0);
+        out[nt] = E::mfma16(W.frag[nt][ks], X.a[ks], out[nt]);
     }
   }
   static __device__ __forceinline__ void apply(const unsigned char* T, const Operand& W,
@@ -239,7 +292,7 @@ struct Bf16x64 {
       for (int i = 0; i < 16; ++i) v[i] = 0.0f;
     }
     struct Frag {
-      bf16x8_t a, b;
+      v8_t a, b;
     };
     static __device__ __forceinline__ Frag fetch(const unsigned char* Xt, const unsigned char* Yt,
                                                  const Lane& L, int block) {
@@ -249,11 +302,11 @@ struct Bf16x64 {
       return f;
     }
     __device__ __forceinline__ void mma(const Frag& f) {
-      v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a, f.b, v, 0, 0, 0);
+      v = E::mfma32(f.a, f.b, v);
     }
     // += (Y block)^T (X block): the transpose of what mma() adds
     __device__ __forceinline__ void mma_swapped(const Frag& f) {
-      v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b, f.a, v, 0, 0, 0);
+      v = E::mfma32(f.b, f.a, v);
     }
     // The lane holds, of the accumulated block, column lane%32 and rows 8j + 4*(lane/32) .. +3:
     // four neighbours of image row (c0 + column), which go out as one 64-bit write.
@@ -266,8 +319,8 @@ struct Bf16x64 {
       for (int j = 0; j < 4; ++j) {
         const int r = r0 + 8 * j + 4 * (L.lane >> 5);
         uint32_t* p = reinterpret_cast<uint32_t*>(image + (image_row(c) * kImageStride + r) * 2);
-        p[0] = pack_bf16(v[4 * j] * scale, v[4 * j + 1] * scale);
-        p[1] = pack_bf16(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
+        p[0] = E::pack2(v[4 * j] * scale, v[4 * j + 1] * scale);
+        p[1] = E::pack2(v[4 * j + 2] * scale, v[4 * j + 3] * scale);
       }
     }
     // Sum over this lane's elements of (accumulated block) x (the block of another matrix
@@ -282,8 +335,8 @@ struct Bf16x64 {
         const uint32_t* p =
             reinterpret_cast<const uint32_t*>(image + (image_row(c) * kImageStride + r) * 2);
         const uint32_t lo = p[0], hi = p[1];
-        s += v[4 * j] * __uint_as_float(lo << 16) + v[4 * j + 1] * __uint_as_float(lo & 0xffff0000u);
-        s += v[4 * j + 2] * __uint_as_float(hi << 16) + v[4 * j + 3] * __uint_as_float(hi & 0xffff0000u);
+        s += v[4 * j] * E::lo(lo) + v[4 * j + 1] * E::hi(lo);
+        s += v[4 * j + 2] * E::lo(hi) + v[4 * j + 3] * E::hi(hi);
       }
       return s;
     }
@@ -294,15 +347,18 @@ struct Bf16x64 {
   // two neighbouring image elements (k, k+1) of image row n
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
                                                           float v0, float v1) {
-    *reinterpret_cast<uint32_t*>(image + (image_row(n) * kImageStride + k) * 2) = pack_bf16(v0, v1);
+    *reinterpret_cast<uint32_t*>(image + (image_row(n) * kImageStride + k) * 2) = E::pack2(v0, v1);
   }
   // element k of image row n
   static __device__ __forceinline__ float image_at(const unsigned char* image, int n, int k) {
     const uint32_t h =
         *reinterpret_cast<const uint16_t*>(image + (image_row(n) * kImageStride + k) * 2);
-    return __uint_as_float(h << 16);
+    return E::lo(h);
   }
 };
+
+typedef Half64<Bf16Elem> Bf16x64;
+typedef Half64<F16Elem> F16x64;
 
 struct F32x32 {
   typedef float io_t;

@@ -1,4 +1,4 @@
-// Resident kernels for short bf16 sequences (N <= 208, d_h = 64).
+// Resident kernels for short sequences of 16-bit elements (bf16 or fp16, N <= 208, d_h = 64).
 //
 // One persistent workgroup of 16 waves owns one slice at a time and keeps it in LDS: wave w
 // loads and stages the 16-row tile w, so every global load of the slice is issued at once and
@@ -431,11 +431,15 @@ hipError_t run(const Problem& p, bool bwd) {
 }  // namespace
 
 bool resident_supports(int dtype, int D, int N) {
-  return dtype == 1 && D == mfma::Bf16x64::D && N <= kMaxTiles * mfma::TR;
+  return (dtype == 1 || dtype == 2) && D == mfma::Bf16x64::D && N <= kMaxTiles * mfma::TR;
 }
 
-hipError_t launch_resident_fwd(const Problem& p) { return run<Bf16x64>(p, false); }
+hipError_t launch_resident_fwd(const Problem& p) {
+  return p.dtype == 1 ? run<Bf16x64>(p, false) : run<F16x64>(p, false);
+}
 
-hipError_t launch_resident_bwd(const Problem& p) { return run<Bf16x64>(p, true); }
+hipError_t launch_resident_bwd(const Problem& p) {
+  return p.dtype == 1 ? run<Bf16x64>(p, true) : run<F16x64>(p, true);
+}
 
 }  // namespace cotten

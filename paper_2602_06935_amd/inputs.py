@@ -94,6 +94,11 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return f32_from_bf16_bits(bf16_bits_from_f32(x)).reshape(np.shape(x))
 
 
+def round_to_f16(x: np.ndarray) -> np.ndarray:
+    """float32 array whose every value is exactly representable in IEEE half (RNE)."""
+    return np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
 def left_pad_mask(lengths: np.ndarray, N: int) -> np.ndarray:
     """[B,N] uint8 mask with the last lengths[b] positions of row b set to 1."""
     pos = np.arange(N, dtype=np.int64)[None, :]

@@ -9,6 +9,7 @@ from paper_2602_06935_amd import binding
 
 FP32_BAR = 1e-5     # relative L2 error allowed for fp32 I/O
 BF16_BAR = 2e-2     # relative L2 error allowed for bf16 I/O with fp32 accumulation
+F16_BAR = 2.5e-3    # fp16 I/O: the bf16 bar scaled by the ratio of the unit roundoffs (2^-11 / 2^-8)
 
 
 def rel_l2(got: np.ndarray, ref: np.ndarray) -> float:
@@ -19,12 +20,16 @@ def rel_l2(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def bar_for(dtype: str) -> float:
-    return FP32_BAR if dtype == "f32" else BF16_BAR
+    return {"f32": FP32_BAR, "bf16": BF16_BAR, "f16": F16_BAR}[dtype]
 
 
 def to_gpu(x: np.ndarray, dtype: str) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
-    return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
+    if dtype == "bf16":
+        return t.to(torch.bfloat16).contiguous()
+    if dtype == "f16":
+        return t.to(torch.float16).contiguous()
+    return t
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:

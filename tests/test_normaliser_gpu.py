@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2602_06935_amd import binding
-from paper_2602_06935_amd.inputs import round_to_bf16
+from paper_2602_06935_amd.inputs import round_to_bf16, round_to_f16
 
 from gpu_util import bar_for, rel_l2, to_f64, to_gpu
 
@@ -15,6 +15,8 @@ pytestmark = pytest.mark.gpu
 # (label, dtype, B, H, N, d): one shape per kernel family and element format
 CASES = [
     ("resident bf16", "bf16", 5, 4, 200, 64),
+    ("resident fp16", "f16", 5, 4, 120, 64),
+    ("split fp16", "f16", 2, 2, 1030, 64),
     ("fused f32", "f32", 5, 2, 200, 32),
     ("fused bf16 (N above the resident limit)", "bf16", 70, 4, 230, 64),
     ("split bf16", "bf16", 2, 2, 1030, 64),
@@ -29,6 +31,8 @@ def _inputs(seed, dtype, B, H, N, d):
     Q, K, V, dO = (rng.standard_normal((B, H, N, d)).astype(np.float32) for _ in range(4))
     if dtype == "bf16":
         Q, K, V, dO = (round_to_bf16(x) for x in (Q, K, V, dO))
+    if dtype == "f16":
+        Q, K, V, dO = (round_to_f16(x) for x in (Q, K, V, dO))
     lengths = rng.integers(1, N + 1, size=B)
     lengths[0] = N
     mask = np.zeros((B, N), np.uint8)

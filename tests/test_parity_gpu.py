@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2602_06935_amd import binding
-from paper_2602_06935_amd.inputs import WORKLOADS, make_batch, round_to_bf16
+from paper_2602_06935_amd.inputs import WORKLOADS, make_batch, round_to_bf16, round_to_f16
 
 from gpu_util import FP32_BAR, bar_for, gpu_bwd, gpu_fwd, rel_l2, to_f64, to_gpu
 
@@ -97,6 +97,8 @@ def _case(seed, B, H, N, d, dtype="f32", sigma=1.0):
     Q, K, V, dO = (rng.standard_normal((B, H, N, d)).astype(np.float32) * np.float32(sigma) for _ in range(4))
     if dtype == "bf16":
         Q, K, V, dO = (round_to_bf16(x) for x in (Q, K, V, dO))
+    if dtype == "f16":
+        Q, K, V, dO = (round_to_f16(x) for x in (Q, K, V, dO))
     return Q, K, V, dO
 
 
@@ -264,6 +266,22 @@ def test_extreme_shapes(oracle, dtype, d):
     mask[0, 12345:] = 1
     mask[0, 30000:30100] = 0
     _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"one sequence of {N} rows, d={d}")
+
+
+@pytest.mark.parametrize("B,H,N,d", [(6, 4, 200, 64), (3, 2, 77, 64), (70, 4, 230, 64), (2, 2, 1030, 64),
+                                     (3, 2, 70, 32), (2, 2, 300, 16)])
+def test_fp16_io(oracle, B, H, N, d):
+    """IEEE half I/O (the mixed-precision mode of the paper's training runs) on every kernel
+    family: resident (N <= 208), fused and split streamers (d_h = 64), vector-ALU (d_h = 32, 16).
+    Bar 2.5e-3: unit roundoff 2^-11 against bf16's 2^-8 and its bar of 2e-2."""
+    Q, K, V, dO = _case(8000 + N + d, B, H, N, d, "f16")
+    rng = np.random.default_rng(N)
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        mask[b, N - int(rng.integers(1, N + 1)):] = 1
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, "f16", label=f"fp16 N={N} d={d}")
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], got_o.shape)
+    assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
 
 
 def test_binding_reports_library_errors():
