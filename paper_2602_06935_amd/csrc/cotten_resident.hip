@@ -205,7 +205,9 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
   //      stage Q and issue the loads of the next slice                               B
   //   3  wave w finishes the O rows of tile w (phase 1 of the next slice may start at once:
   //      it writes only the K, V tiles, which nobody reads any more)
-  for (; slice < a.slices; slice += stride) {
+  COTTEN_RTRACE(0);
+  for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
+    COTTEN_RTRACE_IT(1);
     if (mine) {
       const Lane L = L0.again();
       float inv[2];
@@ -214,7 +216,9 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       else
         clear_tiles(L, blk + kKt, blk + kVt);
     }
+    COTTEN_RTRACE_IT(2);
     __syncthreads();
+    COTTEN_RTRACE_IT(3);
     {
       const Lane L = L0.again();
       constexpr int kB = F::BlockAcc::kBlocks;
@@ -232,7 +236,9 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
         keys = key_rows(a, L, slice + 2 * stride, tile);
       }
     }
+    COTTEN_RTRACE_IT(4);
     __syncthreads();
+    COTTEN_RTRACE_IT(5);
     if (mine) {
       const Lane L = L0.again();
       typename F::TileRows xq;
@@ -250,6 +256,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       if (row < N)
         store_product_row<F, true>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
     }
+    COTTEN_RTRACE_IT(6);
   }
 }
 
