@@ -293,13 +293,14 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
   if (row < N) store_product_row<F, true>(dst, row, row_stride, L, p);
 }
 
-// Backward, per slice (B = workgroup barrier):
-//   1  tile waves stage K, V                                                        B
-//   2  waves 12-15 build S (one block each, at raised priority: everyone waits for it);
-//      tile waves stage Q, dO and issue the loads of the next slice                 B
-//   3  waves 12-15 build dS;  waves 0-11 apply dQ (tiles w, w+12), which needs only S B
-//   4  all waves apply dV and dK: waves 2i, 2i+1 take tiles i and i+8, one product
-//      each, alternating so that every SIMD gets both kinds                         B
+// Backward, per slice (B = workgroup barrier).  Q and dO come first because their loads do not
+// wait for the mask bytes, so for a workgroup's first slice they arrive first:
+//   1  tile waves stage Q, dO                                                        B
+//   2  waves 12-15 build dS (one block each, at raised priority: everyone waits for it);
+//      tile waves stage K, V and issue the loads of the next slice                   B
+//   3  waves 12-15 build S;  waves 0-11 apply dV and dK, which need only dS: waves 2i, 2i+1
+//      take tiles i, i+6, i+12, one product each, so that every SIMD gets both kinds    B
+//   4  wave w applies dQ of tile w                                                    B
 template <class F>
 __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   const Lane L0;
@@ -316,14 +317,13 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
     clear_tiles(L0, blk + kKt, blk + kVt);
     clear_tiles(L0, blk + kQt, blk + kGt);
   }
-  constexpr int kB = F::BlockAcc::kBlocks;
+  constexpr int kB = F::BlockAcc::kBlocks, kApplyWaves = kWaves - kB;
   static_assert(kB == 4 && kWaves == 16 && kMaxTiles <= 16, "wave roles below");
-  const int kv_kind = 1 + (((tile >> 2) + tile) & 1);  // phase 4: dV or dK
+  const int kv_kind = 1 + ((tile + (tile >> 2)) & 1);  // phase 3: dV or dK
 
   int slice = blockIdx.x;
   Raw rq, rk;
   COTTEN_RTRACE(0);
-  // The first slice: Q and dO do not have to wait for the mask bytes that select the K, V rows.
   fetch<true, 2>(rq, rk, a, L0, slice, tile, 0);
   fetch<true, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
@@ -333,32 +333,33 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
     const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
     COTTEN_RTRACE_IT(1);
     if (mine) {
-      // A tile without a valid key adds nothing to S, and its dK, dV rows are plain zeros.
       const Lane L = L0.again();
-      const bool any_key = __ballot(rk.live != 0) != 0;
-      if (any_key) {
-        float inv[2];
-        stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
-        publish_inv(invs + tile * 2 * TR + TR, L, inv);
-      } else {
-        clear_tiles(L, blk + kKt, blk + kVt);
-      }
-      if (L.lane == 0) live[tile] = any_key;
+      float inv[2];
+      stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
+      publish_inv(invs + tile * 2 * TR, L, inv);
     }
     COTTEN_RTRACE_IT(2);
     __syncthreads();
     COTTEN_RTRACE_IT(3);
     {
       const Lane L = L0.again();
-      if (tile >= kWaves - kB) {  // g = dO S^T: contraction over columns of S -> natural image
+      if (tile >= kApplyWaves) {
+        // dV = khat dS -> transposed image;  h = v dS^T -> natural image
         __builtin_amdgcn_s_setprio(3);  // the other waves wait for this at the next barrier
-        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, scale, img_s, nullptr);
+        build_state<F>(L, tile - kApplyWaves, kQt, kGt, scale, img_ds, img_dst);
         __builtin_amdgcn_s_setprio(0);
       }
       if (mine) {
-        float inv[2];
-        stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
-        publish_inv(invs + tile * 2 * TR, L, inv);
+        // A tile without a valid key adds nothing to S, and its dK, dV rows are plain zeros.
+        const bool any_key = __ballot(rk.live != 0) != 0;
+        if (any_key) {
+          float inv[2];
+          stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
+          publish_inv(invs + tile * 2 * TR + TR, L, inv);
+        } else {
+          clear_tiles(L, blk + kKt, blk + kVt);
+        }
+        if (L.lane == 0) live[tile] = any_key;
         fetch<true>(rq, rk, a, L, slice + stride, tile, keys);
         keys = key_rows(a, L, slice + 2 * stride, tile);
       }
@@ -366,35 +367,34 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
     COTTEN_RTRACE_IT(4);
     __syncthreads();
     COTTEN_RTRACE_IT(5);
-    if (tile >= kWaves - kB) {
-      // dV = khat dS -> transposed image;  h = v dS^T -> natural image
+    if (tile >= kApplyWaves) {
+      // g = dO S^T: contraction over columns of S -> natural image.  With dlog wanted: this
+      // block of <sum_j khat_j^T v_j, scale * dS (its image)>
       const Lane L = L0.again();
       __builtin_amdgcn_s_setprio(3);
-      // with dlog wanted: this block of <scale * S (its image), sum_i qhat_i^T dO_i>
-      build_state<F>(L, tile - (kWaves - kB), kQt, kGt, scale, img_ds, img_dst, img_s,
-                     a.dlog != nullptr ? dots + (tile - (kWaves - kB)) : nullptr);
+      build_state<F>(L, tile - kApplyWaves, kKt, kVt, scale, img_s, nullptr, img_ds,
+                     a.dlog != nullptr ? dots + (tile - kApplyWaves) : nullptr);
       __builtin_amdgcn_s_setprio(0);
     } else {
-      const Lane L = L0.again();
-      typename F::Operand W;
-      W.load(img_s, L);
-#pragma unroll 1
-      for (int t = tile; t < n_tiles; t += kWaves - kB)
-        apply_tile<F>(L, 0, t, N, W, live, invs, a.dQ + base, a.st.row);
-    }
-    COTTEN_RTRACE_IT(6);
-    __syncthreads();
-    COTTEN_RTRACE_IT(7);
-    // d loss / d log(scale) = sum_i dO_i . O_i = <scale * S, sum_i qhat_i^T dO_i>, blocks in order
-    if (a.dlog != nullptr && threadIdx.x == 0)
-      a.dlog[slice] = ((dots[0] + dots[1]) + dots[2]) + dots[3];
-    {
       const Lane L = L0.again();
       typename F::Operand W;
       W.load(kv_kind == 1 ? img_dst : img_ds, L);
       unsigned char* dst = (kv_kind == 1 ? a.dV : a.dK) + base;
 #pragma unroll 1
-      for (int t = tile >> 1; t < n_tiles; t += kWaves / 2) apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst, a.st.row);
+      for (int t = tile >> 1; t < n_tiles; t += kApplyWaves / 2)
+        apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst, a.st.row);
+    }
+    COTTEN_RTRACE_IT(6);
+    __syncthreads();
+    COTTEN_RTRACE_IT(7);
+    // d loss / d log(scale) = sum_i dO_i . O_i = <S, scale * dS>, blocks in order
+    if (a.dlog != nullptr && threadIdx.x == 0)
+      a.dlog[slice] = ((dots[0] + dots[1]) + dots[2]) + dots[3];
+    if (mine) {
+      const Lane L = L0.again();
+      typename F::Operand W;
+      W.load(img_s, L);
+      apply_tile<F>(L, 0, tile, N, W, live, invs, a.dQ + base, a.st.row);
     }
     __syncthreads();  // the tiles and images are rewritten for the next slice
   }
