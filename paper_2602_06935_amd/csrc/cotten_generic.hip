@@ -476,7 +476,8 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
   plan.splits = static_cast<int>(splits);
   plan.rows_per_split = static_cast<int>(rows);
   if (plan.path == Plan::kSplit) {
-    plan.workspace_floats = static_cast<size_t>(BH) * D * D * splits * nstates;
+    const size_t side = mfma_state_dim(dtype);
+    plan.workspace_floats = static_cast<size_t>(BH) * side * side * splits * nstates;
   } else {
     // partial states, plus the reduced states when there is more than one partial
     plan.workspace_floats =

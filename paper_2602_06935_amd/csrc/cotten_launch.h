@@ -60,8 +60,10 @@ void launch_reduce_states(const float* partial, float* reduced, int splits, int 
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 
-// MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows).
+// MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows), and
+// the half-width shapes (16-bit d_h = 32, fp32 d_h = 16) zero-padded onto the same kernels.
 bool mfma_supports(int dtype, int D);
+int mfma_state_dim(int dtype);  // side of the (possibly zero-padded) state the MFMA kernels keep
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 

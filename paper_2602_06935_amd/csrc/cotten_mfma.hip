@@ -678,7 +678,8 @@ Args make_args(const Problem& p, const Plan& plan, int D) {
   a.N = p.N;
   a.splits = plan.splits;
   a.st = Strides{p.stride_batch * p.elem_bytes(), p.stride_head * p.elem_bytes(),
-                 static_cast<int>(p.stride_row * p.elem_bytes())};
+                 RowAddr{static_cast<int>(p.stride_row * p.elem_bytes()),
+                         static_cast<int>(p.D * p.elem_bytes())}};
   a.scale = p.scale;
   a.eps = p.eps;
   a.scales = p.slice_scale;
@@ -730,9 +731,12 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
 
 }  // namespace
 
+// Full-width rows (128 bytes) and half-width rows (64 bytes, run zero-padded on the same formats).
 bool mfma_supports(int dtype, int D) {
-  return ((dtype == 1 || dtype == 2) && D == 64) || (dtype == 0 && D == 32);
+  return dtype == 0 ? (D == 32 || D == 16) : (D == 64 || D == 32);
 }
+
+int mfma_state_dim(int dtype) { return dtype == 0 ? F32x32::D : Bf16x64::D; }
 
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan) {
   return p.dtype == 1   ? run_fwd<Bf16x64>(p, plan)

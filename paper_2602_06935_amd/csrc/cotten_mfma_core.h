@@ -15,7 +15,8 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int TR = 16;               // rows per wave tile
-constexpr int kRowBytes = 128;       // bytes of one row of Q, K, V ... (d_h elements)
+constexpr int kRowBytes = 128;       // bytes of one tile row: d_h elements, or d_h/2 elements
+                                     // followed by zeros (half-width rows)
 constexpr int kTileStride = 144;     // bytes per row of an LDS tile (128 + 16 of padding)
 constexpr int kTileBytes = TR * kTileStride;
 
@@ -500,12 +501,20 @@ struct Raw {
 // and causes no memory traffic: rows that do not take part are skipped without a branch, so
 // every tile issues the same number of load instructions and the hardware's in-order load
 // counter can tell "this tile has arrived" from "the tiles prefetched after it have not".
-// Where the rows of the slices are in global memory (bytes): slice (b,h) starts at
-// b*batch + h*head and its rows are `row` apart.  [B,H,N,d]: batch = H*N*128, head = N*128,
-// row = 128;  [B,N,H,d]: batch = N*H*128, head = 128, row = H*128.
+// How the rows of a slice are addressed in global memory: `stride` bytes apart, `bytes` bytes
+// each (128, or 64 for half-width rows: d_h = 32 with 16-bit elements, d_h = 16 with fp32 -
+// those run on the full-width formats with the upper half of every tile row held at zero,
+// which leaves all results unchanged).
+struct RowAddr {
+  int stride, bytes;
+};
+
+// Where the slices are (bytes): slice (b,h) starts at b*batch + h*head.
+// [B,H,N,d]: batch = H*N*row bytes, head = N*row bytes, stride = row bytes;
+// [B,N,H,d]: batch = N*H*row bytes, head = row bytes, stride = H*row bytes.
 struct Strides {
   long long batch, head;
-  int row;
+  RowAddr row;
   __device__ __forceinline__ size_t slice_base(int bh, int H) const {
     return static_cast<size_t>(bh / H) * batch + static_cast<size_t>(bh % H) * head;
   }
@@ -513,16 +522,23 @@ struct Strides {
 
 struct Src {
   __amdgpu_buffer_rsrc_t x, y;
-  int row;  // bytes between rows
+  RowAddr row;
   __device__ __forceinline__ Src(const unsigned char* X, const unsigned char* Y, int N,
-                                 int row_stride)
-      : row(row_stride) {
-    const int bytes = (N - 1) * row_stride + kRowBytes;
+                                 RowAddr row_addr)
+      : row(row_addr) {
+    const int bytes = (N - 1) * row.stride + row.bytes;
     x = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(X), 0, bytes, 0x00020000);
     y = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Y), 0, bytes, 0x00020000);
   }
+  // byte offset of the lane's 16 bytes of `row`, outside the buffer (zeros, no traffic) when
+  // the row does not take part or the lane's columns are padding
+  __device__ __forceinline__ uint32_t offset(int row_index, bool live, const Lane& L) const;
 };
 constexpr uint32_t kOutOfBuffer = 0x80000000u;
+__device__ __forceinline__ uint32_t Src::offset(int row_index, bool live, const Lane& L) const {
+  return (live && L.ch * 16 < row.bytes) ? static_cast<uint32_t>(row_index) * row.stride + L.ch * 16
+                                         : kOutOfBuffer;
+}
 
 // Loads local tile lt (all zeros, and no traffic, if lt is not one of the workgroup's tiles).
 // A row takes part when it is below rows.limit and, if rows.flags is given, its flag is set.
@@ -537,7 +553,7 @@ __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const Src& src, 
     const int row = row0 + L.r8 + 8 * h;
     bool live = tile_ok && row < rows.limit;
     if (rows.flags != nullptr) live = live && rows.flags[tile_ok ? lt * TR + L.r8 + 8 * h : 0] != 0;
-    const uint32_t off = live ? static_cast<uint32_t>(row) * src.row + L.ch * 16 : kOutOfBuffer;
+    const uint32_t off = src.offset(row, live, L);
     r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
     if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
     else r.y[h] = u32x4_t{0, 0, 0, 0};
@@ -642,15 +658,16 @@ __device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
 // better left with the default policy in every kernel here.
 template <class F, bool STREAM>
 __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ dst, int row,
-                                                  int row_stride, const Lane& L,
+                                                  RowAddr addr, const Lane& L,
                                                   const float (&p)[2 * F::EPL]) {
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
+    if (64 * j >= addr.bytes) break;  // half-width rows: the second piece is padding
     float c[F::EPL];
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];
     u32x4_t* at =
-        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * row_stride + 64 * j + 16 * L.g16);
+        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * addr.stride + 64 * j + 16 * L.g16);
     if (STREAM) __builtin_nontemporal_store(F::pack(c), at);
     else *at = F::pack(c);
   }

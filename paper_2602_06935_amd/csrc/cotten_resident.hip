@@ -79,7 +79,7 @@ __device__ __forceinline__ void load_tile(Raw& r, const Lane& L, const Src& src,
   for (int h = 0; h < 2; ++h) {
     const int row = tile * TR + L.r8 + 8 * h;
     const uint32_t off =
-        ((want >> h) & 1) ? static_cast<uint32_t>(row) * src.row + L.ch * 16 : kOutOfBuffer;
+        src.offset(row, (want >> h) & 1, L);
     r.x[h] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off, 0, 0);
     if (USE_Y) r.y[h] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off, 0, 0);
     else r.y[h] = u32x4_t{0, 0, 0, 0};
@@ -271,7 +271,7 @@ template <class F>
 __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N,
                                            const typename F::Operand& W, const int* live,
                                            const float* invs, unsigned char* dst,
-                                           int row_stride) {
+                                           RowAddr row_addr) {
   const unsigned char* tb = smem + t * kBlockBytes;
   const int row = t * TR + L.i16;
   float p[2 * F::EPL];
@@ -290,7 +290,7 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
       project_rows<F, true>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
     }
   }
-  if (row < N) store_product_row<F, true>(dst, row, row_stride, L, p);
+  if (row < N) store_product_row<F, true>(dst, row, row_addr, L, p);
 }
 
 // Backward, per slice (B = workgroup barrier).  Q and dO come first because their loads do not
@@ -416,7 +416,8 @@ hipError_t run(const Problem& p, bool bwd) {
   a.N = p.N;
   a.slices = p.B * p.H;
   a.st = Strides{p.stride_batch * p.elem_bytes(), p.stride_head * p.elem_bytes(),
-                 static_cast<int>(p.stride_row * p.elem_bytes())};
+                 RowAddr{static_cast<int>(p.stride_row * p.elem_bytes()),
+                         static_cast<int>(p.D * p.elem_bytes())}};
   a.scale = p.scale;
   a.eps = p.eps;
   a.scales = p.slice_scale;
@@ -438,7 +439,7 @@ hipError_t run(const Problem& p, bool bwd) {
 }  // namespace
 
 bool resident_supports(int dtype, int D, int N) {
-  return (dtype == 1 || dtype == 2) && D == mfma::Bf16x64::D && N <= kMaxTiles * mfma::TR;
+  return (dtype == 1 || dtype == 2) && (D == 64 || D == 32) && N <= kMaxTiles * mfma::TR;
 }
 
 hipError_t launch_resident_fwd(const Problem& p) {

@@ -21,8 +21,11 @@ CASES = [
     ("fused bf16 (N above the resident limit)", "bf16", 70, 4, 230, 64),
     ("split bf16", "bf16", 2, 2, 1030, 64),
     ("split f32", "f32", 2, 2, 1030, 32),
-    ("vector-ALU f32 d=16", "f32", 3, 2, 70, 16),
-    ("vector-ALU bf16 d=32, several splits", "bf16", 2, 2, 300, 32),
+    ("half-width rows f32 d=16 (fused)", "f32", 3, 2, 70, 16),
+    ("half-width rows bf16 d=32 (resident)", "bf16", 3, 2, 150, 32),
+    ("half-width rows bf16 d=32 (split)", "bf16", 2, 2, 1030, 32),
+    ("vector-ALU f32 d=64", "f32", 3, 2, 70, 64),
+    ("vector-ALU bf16 d=16, several splits", "bf16", 2, 2, 300, 16),
 ]
 
 
