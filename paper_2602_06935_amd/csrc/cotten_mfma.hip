@@ -731,9 +731,10 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
 
 }  // namespace
 
-// Full-width rows (128 bytes) and half-width rows (64 bytes, run zero-padded on the same formats).
+// Full-width rows (128 bytes) and narrower rows (64 or 32 bytes, run zero-padded on the same
+// formats).
 bool mfma_supports(int dtype, int D) {
-  return dtype == 0 ? (D == 32 || D == 16) : (D == 64 || D == 32);
+  return dtype == 0 ? (D == 32 || D == 16) : (D == 64 || D == 32 || D == 16);
 }
 
 int mfma_state_dim(int dtype) { return dtype == 0 ? F32x32::D : Bf16x64::D; }

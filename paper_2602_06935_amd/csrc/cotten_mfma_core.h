@@ -502,8 +502,8 @@ struct Raw {
 // every tile issues the same number of load instructions and the hardware's in-order load
 // counter can tell "this tile has arrived" from "the tiles prefetched after it have not".
 // How the rows of a slice are addressed in global memory: `stride` bytes apart, `bytes` bytes
-// each (128, or 64 for half-width rows: d_h = 32 with 16-bit elements, d_h = 16 with fp32 -
-// those run on the full-width formats with the upper half of every tile row held at zero,
+// each (128, or 64 / 32 for narrower rows: d_h = 32 or 16 with 16-bit elements, d_h = 16 with
+// fp32 - those run on the full-width formats with the rest of every tile row held at zero,
 // which leaves all results unchanged).
 struct RowAddr {
   int stride, bytes;
@@ -662,7 +662,7 @@ __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ ds
                                                   const float (&p)[2 * F::EPL]) {
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    if (64 * j >= addr.bytes) break;  // half-width rows: the second piece is padding
+    if (64 * j + 16 * L.g16 >= addr.bytes) break;  // narrower rows: the rest is padding
     float c[F::EPL];
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];

@@ -439,7 +439,7 @@ hipError_t run(const Problem& p, bool bwd) {
 }  // namespace
 
 bool resident_supports(int dtype, int D, int N) {
-  return (dtype == 1 || dtype == 2) && (D == 64 || D == 32) && N <= kMaxTiles * mfma::TR;
+  return (dtype == 1 || dtype == 2) && (D == 64 || D == 32 || D == 16) && N <= kMaxTiles * mfma::TR;
 }
 
 hipError_t launch_resident_fwd(const Problem& p) {

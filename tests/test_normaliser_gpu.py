@@ -25,7 +25,8 @@ CASES = [
     ("half-width rows bf16 d=32 (resident)", "bf16", 3, 2, 150, 32),
     ("half-width rows bf16 d=32 (split)", "bf16", 2, 2, 1030, 32),
     ("vector-ALU f32 d=64", "f32", 3, 2, 70, 64),
-    ("vector-ALU bf16 d=16, several splits", "bf16", 2, 2, 300, 16),
+    ("quarter-width rows bf16 d=16 (split)", "bf16", 2, 2, 300, 16),
+    ("vector-ALU f32 d=64, several splits", "f32", 2, 2, 300, 64),
 ]
 
 
