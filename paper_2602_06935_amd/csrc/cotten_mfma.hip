@@ -117,13 +117,63 @@ __device__ __forceinline__ void for_each_tile(const Lane& L, const Src& src, con
   }
 }
 
+// For short sequences (at most 4 tiles per wave) a wave can simply keep all its tiles of a
+// tensor pair in registers: every load is issued at the start of the kernel, and a second
+// walk over the same tiles (K, V in the backward) costs no memory traffic.
+struct Kept {
+  static constexpr int kTiles = 4;
+  Raw t[kTiles];
+};
+
+template <bool USE_Y>
+__device__ __forceinline__ void load_kept(Kept& k, const Lane& L, const Src& src, const Rows& rows) {
+#pragma unroll
+  for (int i = 0; i < Kept::kTiles; ++i) load_raw<USE_Y>(k.t[i], L, src, rows, L.wave + i * kWaves);
+}
+
+template <bool USE_Y, int DEPTH, typename Body>
+__device__ __forceinline__ void for_each_tile(const Lane& L, const Src&, const Rows& rows,
+                                              Kept& kept, Body&& body) {
+#pragma unroll
+  for (int i = 0; i < Kept::kTiles; ++i) {
+    const int t = L.wave + i * kWaves;
+    if (t >= rows.n_tiles) return;
+    body(kept.t[i], rows.row0(t));
+  }
+}
+
+// Uniform spelling for the kernels that exist in both variants.
+template <bool USE_Y>
+__device__ __forceinline__ void load_tiles(Raw& r, const Lane& L, const Src& src, const Rows& rows) {
+  load_first<USE_Y>(r, L, src, rows);
+}
+template <bool USE_Y>
+__device__ __forceinline__ void load_tiles(Kept& k, const Lane& L, const Src& src, const Rows& rows) {
+  load_kept<USE_Y>(k, L, src, rows);
+}
+// before a second walk over the same tiles
+template <bool USE_Y>
+__device__ __forceinline__ void reload_tiles(Raw& r, const Lane& L, const Src& src, const Rows& rows) {
+  load_first<USE_Y>(r, L, src, rows);
+}
+template <bool USE_Y>
+__device__ __forceinline__ void reload_tiles(Kept&, const Lane&, const Src&, const Rows&) {}
+template <bool SHORT>
+struct TilesOf {
+  typedef Raw type;
+};
+template <>
+struct TilesOf<true> {
+  typedef Kept type;
+};
+
 // ---- passes -------------------------------------------------------------------------------
-// Every pass takes the wave's first tile already loaded in `first`.
+// Every pass takes the wave's first tile already loaded in `first` (or all its tiles, Kept).
 
 // acc += sum over live rows of xhat^T y
-template <class F, int DEPTH>
+template <class F, int DEPTH, class First>
 __device__ __forceinline__ void state_pass(const Lane& L, const WaveLds<F>& W,
-                                           const Src& src, const Rows rows, float eps, Raw& first,
+                                           const Src& src, const Rows rows, float eps, First& first,
                                            typename F::Acc& acc) {
   for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int) {
     if (__ballot(r.live != 0) == 0) return;  // no live row in this tile (uniform)
@@ -148,10 +198,10 @@ __device__ __forceinline__ float inv_by_row(const WaveLds<F>& W, const Lane& L,
 }
 
 // O rows = (q rows x W) / r   (W = scale * S, image op[c][a])
-template <class F, int DEPTH, bool STREAM>
+template <class F, int DEPTH, bool STREAM, class First>
 __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& W,
                                                const Src& src, unsigned char* __restrict__ O,
-                                               const Rows rows, float eps, Raw& first,
+                                               const Rows rows, float eps, First& first,
                                                const typename F::Operand& Sop) {
   for_each_tile<false, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
     float inv[2];
@@ -172,11 +222,11 @@ __device__ __forceinline__ void fwd_apply_pass(const Lane& L, const WaveLds<F>& 
 }
 
 // dQ rows from (Q, dO) and W = scale * S (image op[a][c]); with ACCUM also dsacc += qhat^T dO.
-template <class F, bool ACCUM, int DEPTH, bool STREAM>
+template <class F, bool ACCUM, int DEPTH, bool STREAM, class First>
 __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
                                            const Src& src, unsigned char* __restrict__ dQ,
                                            const Rows rows,
-                                           float eps, Raw& first, const unsigned char* Simage,
+                                           float eps, First& first, const unsigned char* Simage,
                                            typename F::Acc& dsacc) {
   // With the state accumulators live, a large operand is re-read from LDS for every tile;
   // otherwise it stays in registers.
@@ -210,11 +260,11 @@ __device__ __forceinline__ void bwd_q_pass(const Lane& L, const WaveLds<F>& W,
 
 // dK, dV rows from (K, V) and scale * dS: dV = (k dS)/r (image op[c][a]),
 // h = v dS^T (image op[a][c]).  Rows below the limit that are masked get zeros.
-template <class F, int DEPTH, bool STREAM>
+template <class F, int DEPTH, bool STREAM, class First>
 __device__ __forceinline__ void bwd_kv_pass(const Lane& L, const WaveLds<F>& W,
                                             const Src& src, unsigned char* __restrict__ dK,
                                             unsigned char* __restrict__ dV, const Rows rows,
-                                            float eps, Raw& first,
+                                            float eps, First& first,
                                             const typename F::Operand& dSop_v,
                                             const typename F::Operand& dSop_h) {
   for_each_tile<true, DEPTH>(L, src, rows, first, [&](const Raw& r, int row0) {
@@ -414,7 +464,8 @@ __device__ __forceinline__ float block_sum(float x, float* scratch) {
   return total;
 }
 
-template <class F>
+// SHORT: at most 16 tiles (256 rows), every wave keeps all its tiles in registers (see Kept).
+template <class F, bool SHORT>
 __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
@@ -426,13 +477,14 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   const Rows keys{0, 1, n_tiles, N, kflags}, all{0, 1, n_tiles, N, nullptr};
   const Src q_src(a.Q + base, a.Q + base, N, a.st.row), kv_src(a.K + base, a.V + base, N, a.st.row);
 
-  Raw qfirst, kfirst;  // the query tile does not depend on the mask: issue it right away
-  load_first<false>(qfirst, L, q_src, all);
+  typename TilesOf<SHORT>::type qfirst, kfirst;
+  // the query tiles do not depend on the mask: issue them right away
+  load_tiles<false>(qfirst, L, q_src, all);
   if (kflags != nullptr) {
     fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
-  load_first<true>(kfirst, L, kv_src, keys);
+  load_tiles<true>(kfirst, L, kv_src, keys);
 
   typename F::Acc acc;
   acc.zero();
@@ -447,7 +499,7 @@ __global__ __launch_bounds__(kThreads, 2) void fused_fwd_kernel(const Args a) {
   fwd_apply_pass<F, F::kDepthFwd, true>(L, W, q_src, a.O + base, all, a.eps, qfirst, Sop);
 }
 
-template <class F>
+template <class F, bool SHORT>
 __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   const Lane L;
   const WaveLds<F> W(smem, L.wave);
@@ -462,14 +514,14 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
   const Src q_src(a.Q + base, a.dO + base, N, a.st.row), kv_src(a.K + base, a.V + base, N, a.st.row);
 
   COTTEN_TRACE_POINT(0);
-  Raw qfirst, kfirst;
-  load_first<true>(qfirst, L, q_src, all);
+  typename TilesOf<SHORT>::type qfirst, kfirst;
+  load_tiles<true>(qfirst, L, q_src, all);
   if (kflags != nullptr) {
     fill_flags(kflags, a.mask + static_cast<size_t>(bh / a.H) * N, keys);
     __syncthreads();
   }
   COTTEN_TRACE_POINT(1);
-  load_first<true>(kfirst, L, kv_src, keys);
+  load_tiles<true>(kfirst, L, kv_src, keys);
 
   typename F::Acc acc;
   acc.zero();
@@ -486,7 +538,8 @@ __global__ __launch_bounds__(kThreads, 2) void fused_bwd_kernel(const Args a) {
                                        qfirst, op0, acc);
   COTTEN_TRACE_POINT(5);
   // the key/value tiles are walked again: get the first one moving before the reduction
-  load_first<true>(kfirst, L, kv_src, keys);
+  // (nothing to do when they were kept)
+  reload_tiles<true>(kfirst, L, kv_src, keys);
   wg_reduce<F>(L, smem, acc);
   COTTEN_TRACE_POINT(6);
   if (a.dlog != nullptr) {
@@ -687,6 +740,13 @@ Args make_args(const Problem& p, const Plan& plan, int D) {
   return a;
 }
 
+// Short fp32 sequences use the kernels that keep every tile in registers (the 16-bit formats
+// of that length are served by the resident kernels, and would not have the registers).
+template <class F>
+bool keeps_tiles(int N) {
+  return F::kShortKernels && (N + TR - 1) / TR <= Kept::kTiles * kWaves;
+}
+
 template <class F>
 hipError_t run_fwd(const Problem& p, const Plan& plan) {
   const Args a = make_args(p, plan, F::D);
@@ -694,8 +754,14 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
   hipError_t err;
   if (plan.path == Plan::kFused) {
     const size_t lds = lds_bytes<F>((p.N + TR - 1) / TR * TR);
-    if ((err = allow_lds(fused_fwd_kernel<F>, lds)) != hipSuccess) return err;
-    hipLaunchKernelGGL(fused_fwd_kernel<F>, dim3(BH), dim3(kThreads), lds, p.stream, a);
+    if (keeps_tiles<F>(p.N)) {
+      if ((err = allow_lds(fused_fwd_kernel<F, F::kShortKernels>, lds)) != hipSuccess) return err;
+      hipLaunchKernelGGL((fused_fwd_kernel<F, F::kShortKernels>), dim3(BH), dim3(kThreads), lds,
+                         p.stream, a);
+    } else {
+      if ((err = allow_lds(fused_fwd_kernel<F, false>, lds)) != hipSuccess) return err;
+      hipLaunchKernelGGL((fused_fwd_kernel<F, false>), dim3(BH), dim3(kThreads), lds, p.stream, a);
+    }
     return hipGetLastError();
   }
   const size_t lds = lds_bytes<F>(plan.rows_per_split);
@@ -714,8 +780,14 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
   hipError_t err;
   if (plan.path == Plan::kFused) {
     const size_t lds = lds_bytes<F>((p.N + TR - 1) / TR * TR);
-    if ((err = allow_lds(fused_bwd_kernel<F>, lds)) != hipSuccess) return err;
-    hipLaunchKernelGGL(fused_bwd_kernel<F>, dim3(BH), dim3(kThreads), lds, p.stream, a);
+    if (keeps_tiles<F>(p.N)) {
+      if ((err = allow_lds(fused_bwd_kernel<F, F::kShortKernels>, lds)) != hipSuccess) return err;
+      hipLaunchKernelGGL((fused_bwd_kernel<F, F::kShortKernels>), dim3(BH), dim3(kThreads), lds,
+                         p.stream, a);
+    } else {
+      if ((err = allow_lds(fused_bwd_kernel<F, false>, lds)) != hipSuccess) return err;
+      hipLaunchKernelGGL((fused_bwd_kernel<F, false>), dim3(BH), dim3(kThreads), lds, p.stream, a);
+    }
     return hipGetLastError();
   }
   const size_t lds = lds_bytes<F>(plan.rows_per_split);
