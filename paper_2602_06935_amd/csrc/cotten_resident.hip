@@ -37,7 +37,6 @@ namespace {
 using namespace mfma;
 
 constexpr int kWaves = 16;
-constexpr int kWorkgroups = 256;                // one per compute unit (LDS admits no second)
 constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxTiles = 13;                  // N <= 208
 constexpr int kBlockBytes = 4 * kTileBytes;    // [khat | v | q(hat) | dO] tiles of 16 rows
@@ -400,6 +399,22 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   }
 }
 
+// Persistent workgroups: one per compute unit of the current device (the LDS admits no second
+// one), 256 on MI355X.  Asked once per device.
+int compute_units() {
+  constexpr int kMaxDevices = 64;
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 template <class F>
 hipError_t run(const Problem& p, bool bwd) {
   Args a{};
@@ -422,7 +437,8 @@ hipError_t run(const Problem& p, bool bwd) {
   a.eps = p.eps;
   a.scales = p.slice_scale;
   a.dlog = p.dlog_scale;
-  const dim3 grid(static_cast<unsigned>(a.slices < kWorkgroups ? a.slices : kWorkgroups));
+  const int units = compute_units();
+  const dim3 grid(static_cast<unsigned>(a.slices < units ? a.slices : units));
   const size_t lds = Lds<F>::kBytes;
   const void* kern = bwd ? reinterpret_cast<const void*>(resident_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(resident_fwd_kernel<F>);
