@@ -353,32 +353,36 @@ struct StateSource {
 template <class F>
 __device__ __forceinline__ void gather_partials(const float* __restrict__ partials, int splits,
                                                 float* dst) {
-  constexpr int DD = F::D * F::D, kPer = DD / kThreads;
-  float sum[kPer];
+  constexpr int DD = F::D * F::D, kPer = DD / 4 / kThreads;  // 128-bit pieces per thread
+  static_assert(kPer >= 1 && DD % (4 * kThreads) == 0, "state size");
+  const f32x4_t* __restrict__ src = reinterpret_cast<const f32x4_t*>(partials);
+  f32x4_t sum[kPer];
 #pragma unroll
-  for (int i = 0; i < kPer; ++i) sum[i] = 0.0f;
+  for (int i = 0; i < kPer; ++i) sum[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   int p = 0;
   for (; p + 4 <= splits; p += 4) {
-    float v[4][kPer];
+    f32x4_t v[4][kPer];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
       for (int i = 0; i < kPer; ++i)
-        v[q][i] = partials[static_cast<size_t>(p + q) * DD + threadIdx.x + i * kThreads];
+        v[q][i] = src[static_cast<size_t>(p + q) * (DD / 4) + threadIdx.x + i * kThreads];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
       for (int i = 0; i < kPer; ++i) sum[i] += v[q][i];
   }
   for (; p < splits; ++p) {
-    float v[kPer];
+    f32x4_t v[kPer];
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) v[i] = partials[static_cast<size_t>(p) * DD + threadIdx.x + i * kThreads];
+    for (int i = 0; i < kPer; ++i)
+      v[i] = src[static_cast<size_t>(p) * (DD / 4) + threadIdx.x + i * kThreads];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) sum[i] += v[i];
   }
 #pragma unroll
-  for (int i = 0; i < kPer; ++i) dst[threadIdx.x + i * kThreads] = sum[i];
+  for (int i = 0; i < kPer; ++i)
+    reinterpret_cast<f32x4_t*>(dst)[threadIdx.x + i * kThreads] = sum[i];
 }
 
 // Builds operand images of scale * M for the apply products:
@@ -389,35 +393,38 @@ __device__ __forceinline__ void make_operands(const StateSource<F> src, float sc
                                               unsigned char* natural, unsigned char* transposed) {
   constexpr int D = F::D;
   constexpr int kPer = D * D / 2 / kThreads;  // element pairs per thread
-  // Thread -> element maps chosen so that consecutive lanes walk consecutive state rows m,
-  // which are contiguous in the column-major reduction images.
+  // Thread -> element maps chosen so that consecutive lanes walk what is contiguous in the
+  // source: state rows m in the column-major reduction images, state columns n in a gathered
+  // row-major state (anything else lands all lanes of a wave in one LDS bank).
   if (natural != nullptr) {
     float lo[kPer], hi[kPer];
+    int mm[kPer], nn[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = e % D, n = (e / D) * 2;
-      lo[i] = src.at(m, n);
-      hi[i] = src.at(m, n + 1);
+      const int e = threadIdx.x + i * kThreads;
+      mm[i] = src.row_major ? e / (D / 2) : e % D;
+      nn[i] = src.row_major ? (e % (D / 2)) * 2 : (e / D) * 2;
+      lo[i] = src.at(mm[i], nn[i]);
+      hi[i] = src.at(mm[i], nn[i] + 1);
     }
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = e % D, n = (e / D) * 2;
-      F::write_image_pair(natural, m, n, lo[i] * scale, hi[i] * scale);
-    }
+    for (int i = 0; i < kPer; ++i)
+      F::write_image_pair(natural, mm[i], nn[i], lo[i] * scale, hi[i] * scale);
   }
   if (transposed != nullptr) {
     float lo[kPer], hi[kPer];
+    int mm[kPer], nn[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = (e % (D / 2)) * 2, n = e / (D / 2);
-      lo[i] = src.at(m, n);
-      hi[i] = src.at(m + 1, n);
+      const int e = threadIdx.x + i * kThreads;
+      mm[i] = src.row_major ? (e / D) * 2 : (e % (D / 2)) * 2;
+      nn[i] = src.row_major ? e % D : e / (D / 2);
+      lo[i] = src.at(mm[i], nn[i]);
+      hi[i] = src.at(mm[i] + 1, nn[i]);
     }
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int e = threadIdx.x + i * kThreads, m = (e % (D / 2)) * 2, n = e / (D / 2);
-      F::write_image_pair(transposed, n, m, lo[i] * scale, hi[i] * scale);
-    }
+    for (int i = 0; i < kPer; ++i)
+      F::write_image_pair(transposed, nn[i], mm[i], lo[i] * scale, hi[i] * scale);
   }
 }
 
@@ -641,18 +648,24 @@ __global__ __launch_bounds__(kThreads, 2) void split_q_kernel(const Args a) {
   unsigned char* op0 = smem + Layout<F>::kImage0;
   const Rows all = split_rows(N, split, a.splits, nullptr);
   const Src q_src(a.Q + base, a.dO + base, N, a.st.row);
+  COTTEN_TRACE_POINT(0);
   Raw first;
   load_first<true>(first, L, q_src, all);
   float* gathered = reinterpret_cast<float*>(smem);
   gather_partials<F>(a.s_partials + static_cast<size_t>(bh) * a.splits * DD, a.splits, gathered);
   __syncthreads();
+  COTTEN_TRACE_POINT(1);
   make_operands<F>(StateSource<F>{gathered, true}, slice_scale(a, bh), op0, nullptr);
   __syncthreads();
+  COTTEN_TRACE_POINT(2);
   typename F::Acc acc;
   acc.zero();
   bwd_q_pass<F, true, F::kDepthQAccum, kSplitStream>(L, W, q_src, a.dQ + base, all, a.eps, first, op0, acc);
+  COTTEN_TRACE_POINT(3);
   wg_reduce<F>(L, smem, acc);
+  COTTEN_TRACE_POINT(4);
   publish_partial<F>(a.ds_partials, bh, split, a.splits);
+  COTTEN_TRACE_POINT(5);
 }
 
 // Backward, step 3: dK, dV of this workgroup's (K,V) tiles from the complete dS.
