@@ -98,7 +98,7 @@ typedef enum cotten_status {
   COTTEN_ERR_NULL_POINTER = -1,         /* a required tensor pointer is NULL            */
   COTTEN_ERR_BAD_SHAPE = -2,            /* B, H or N < 1, sizes overflow the launch, or
                                            params->layout is not a cotten_layout         */
-  COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64}                      */
+  COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64, 128}                 */
   COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is not a cotten_dtype                  */
   COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
   COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* params->workspace_bytes below the requirement */

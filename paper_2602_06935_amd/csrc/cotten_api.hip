@@ -13,7 +13,7 @@ namespace {
 constexpr float kDefaultEps = 1e-6f;
 constexpr int kMaxDevices = 64;
 
-bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64; }
+bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape checks shared by both directions.  Pure host arithmetic.
@@ -181,7 +181,7 @@ const char* cotten_status_string(int status) {
     case COTTEN_OK: return "ok";
     case COTTEN_ERR_NULL_POINTER: return "a required pointer is NULL";
     case COTTEN_ERR_BAD_SHAPE: return "B, H and N must be >= 1 and within launch limits";
-    case COTTEN_ERR_UNSUPPORTED_HEAD_DIM: return "d_h must be 16, 32 or 64";
+    case COTTEN_ERR_UNSUPPORTED_HEAD_DIM: return "d_h must be 16, 32, 64 or 128";
     case COTTEN_ERR_BAD_DTYPE: return "dtype must be COTTEN_F32, COTTEN_BF16 or COTTEN_F16";
     case COTTEN_ERR_MISALIGNED: return "tensor and workspace pointers must be 16-byte aligned";
     case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";

@@ -137,8 +137,9 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
     int splits, int rows_per_split, float scale, const float* __restrict__ slice_scale,
     float eps, ElemStrides lay) {
   constexpr int CH = D / 8;
-  __shared__ float S[D][D];
-  __shared__ float qs[kTileRows][D + 4];
+  extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
+  float (*S)[D] = reinterpret_cast<float (*)[D]>(dyn_lds);
+  float (*qs)[D + 4] = reinterpret_cast<float (*)[D + 4]>(dyn_lds + D * D);
 
   const int tid = threadIdx.x;
   const int split = blockIdx.x % splits;
@@ -180,7 +181,19 @@ __global__ __launch_bounds__(kThreads) void apply_fwd_kernel(
   }
 }
 
-// blockIdx.y == 0: dQ from (Q, dO, S).   blockIdx.y == 1: dK, dV from (K, V, dS).
+// LDS of the backward apply kernel, in floats: the state matrices a block needs, then the
+// tile buffers.  d_h = 128 does not have room for dS and dS^T together, so there dV and dK
+// are computed by separate blocks (grid.y = 3 instead of 2).
+template <int D>
+constexpr int bwd_apply_lds_floats() {
+  return (D <= 64 ? 2 : 1) * D * D + 2 * kTileRows * (D + 4);
+}
+template <int D>
+constexpr int bwd_apply_grid_y() {
+  return D <= 64 ? 2 : 3;
+}
+
+// blockIdx.y == 0: dQ from (Q, dO, S).   Other blocks: dK and/or dV from (K, V, dS).
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
@@ -189,10 +202,13 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
     T* __restrict__ dK, T* __restrict__ dV, int H, int N, int splits, int rows_per_split,
     float scale, const float* __restrict__ slice_scale, float eps, ElemStrides lay) {
   constexpr int CH = D / 8;
-  __shared__ float M0[D][D];              // S^T (dQ blocks)  or dS   (dK/dV blocks)
-  __shared__ float M1[D][D];              // unused           or dS^T
-  __shared__ float t0[kTileRows][D + 4];  // dO rows          or khat rows
-  __shared__ float t1[kTileRows][D + 4];  // unused           or v rows
+  constexpr bool kTogether = D <= 64;  // dV and dK in one block
+  extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
+  float (*M0)[D] = reinterpret_cast<float (*)[D]>(dyn_lds);  // S^T (dQ), dS (dV) or dS^T (dK alone)
+  float (*M1)[D] = reinterpret_cast<float (*)[D]>(dyn_lds + D * D);  // dS^T when together
+  float* tiles = dyn_lds + (kTogether ? 2 : 1) * D * D;
+  float (*t0)[D + 4] = reinterpret_cast<float (*)[D + 4]>(tiles);  // dO rows or khat rows
+  float (*t1)[D + 4] = reinterpret_cast<float (*)[D + 4]>(tiles + kTileRows * (D + 4));  // v rows
 
   const int tid = threadIdx.x;
   const int split = blockIdx.x % splits;
@@ -244,9 +260,13 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
       __syncthreads();
     }
   } else {
+    const bool do_dv = kTogether || blockIdx.y == 1;
+    const bool do_dk = kTogether || blockIdx.y == 2;
     const float* __restrict__ ds = dstates + static_cast<size_t>(bh) * D * D;
-    load_state<D, false>(ds, scale, M0);  // dS[a][c]
-    load_state<D, true>(ds, scale, M1);   // dS^T[c][a]
+    float (*Mv)[D] = M0;                   // dS[a][c]
+    float (*Mk)[D] = kTogether ? M1 : M0;  // dS^T[c][a]
+    if (do_dv) load_state<D, false>(ds, scale, Mv);
+    if (do_dk) load_state<D, true>(ds, scale, Mk);
     const uint8_t* __restrict__ m =
         mask == nullptr ? nullptr : mask + static_cast<size_t>(bh / H) * N;
     __syncthreads();
@@ -260,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
       for (int i = 0; i < CH; ++i) k[i] = v[i] = 0.0f;
       if (live) {
         load_chunk<T, CH>(K + base + static_cast<size_t>(row) * lay.row + c0, k);
-        load_chunk<T, CH>(V + base + static_cast<size_t>(row) * lay.row + c0, v);
+        if (do_dk) load_chunk<T, CH>(V + base + static_cast<size_t>(row) * lay.row + c0, v);
       }
       float ss = 0.0f;
 #pragma unroll
@@ -274,14 +294,20 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
         gv[i] = h[i] = 0.0f;
       }
       __syncthreads();
+      if (do_dv) {
 #pragma unroll 8
-      for (int a = 0; a < D; ++a) {
-        const float ka = t0[lrow][a];  // dV_c = sum_a khat_a dS[a][c]
-        const float va = t1[lrow][a];  // h_a  = sum_c v_c dS[a][c] = sum_c v_c dS^T[c][a]
+        for (int a = 0; a < D; ++a) {
+          const float ka = t0[lrow][a];  // dV_c = sum_a khat_a dS[a][c]
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-          gv[i] += ka * M0[a][c0 + i];
-          h[i] += va * M1[a][c0 + i];
+          for (int i = 0; i < CH; ++i) gv[i] += ka * Mv[a][c0 + i];
+        }
+      }
+      if (do_dk) {
+#pragma unroll 8
+        for (int a = 0; a < D; ++a) {
+          const float va = t1[lrow][a];  // h_a  = sum_c v_c dS[a][c] = sum_c v_c dS^T[c][a]
+#pragma unroll
+          for (int i = 0; i < CH; ++i) h[i] += va * Mk[a][c0 + i];
         }
       }
       float proj = 0.0f;
@@ -294,8 +320,8 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
         gv[i] = live ? gv[i] : 0.0f;
       }
       if (inrange) {
-        store_chunk<T, CH>(dK + base + static_cast<size_t>(row) * lay.row + c0, h);
-        store_chunk<T, CH>(dV + base + static_cast<size_t>(row) * lay.row + c0, gv);
+        if (do_dk) store_chunk<T, CH>(dK + base + static_cast<size_t>(row) * lay.row + c0, h);
+        if (do_dv) store_chunk<T, CH>(dV + base + static_cast<size_t>(row) * lay.row + c0, gv);
       }
       __syncthreads();
     }
@@ -363,6 +389,14 @@ const float* reduce_generic(const Problem& p, const Plan& plan, int nstates) {
   return reduced;
 }
 
+// Dynamic LDS above 64 KB has to be granted per kernel first.
+template <typename Kern>
+hipError_t allow_lds(Kern kern, size_t bytes) {
+  if (bytes <= 64 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+}
+
 ElemStrides elem_strides(const Problem& p) {
   return ElemStrides{p.stride_batch, p.stride_head, p.stride_row};
 }
@@ -377,7 +411,9 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps,
                      elem_strides(p));
   const float* states = reduce_generic(p, plan, 1);
-  hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+  constexpr size_t lds = (D * D + kTileRows * (D + 4)) * sizeof(float);
+  if (hipError_t err = allow_lds(apply_fwd_kernel<T, D>, lds)) return err;
+  hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), lds, p.stream,
                      static_cast<const T*>(p.Q), states, static_cast<T*>(p.O), p.H, p.N,
                      plan.splits, plan.rows_per_split, p.scale, p.slice_scale, p.eps,
                      elem_strides(p));
@@ -388,6 +424,7 @@ template <typename T, int D>
 hipError_t run_bwd(const Problem& p, const Plan& plan) {
   const int BH = p.B * p.H;
   const dim3 grid(static_cast<unsigned>(BH) * plan.splits, 2, 1);
+  const dim3 apply_grid(grid.x, bwd_apply_grid_y<D>(), 1);
   const size_t second = static_cast<size_t>(BH) * plan.splits * D * D;
   hipLaunchKernelGGL((state_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
@@ -396,7 +433,9 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
                      elem_strides(p));
   const float* states = reduce_generic(p, plan, 2);
   const float* dstates = states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * D * D);
-  hipLaunchKernelGGL((apply_bwd_kernel<T, D>), grid, dim3(kThreads), 0, p.stream,
+  constexpr size_t lds = bwd_apply_lds_floats<D>() * sizeof(float);
+  if (hipError_t err = allow_lds(apply_bwd_kernel<T, D>, lds)) return err;
+  hipLaunchKernelGGL((apply_bwd_kernel<T, D>), apply_grid, dim3(kThreads), lds, p.stream,
                      static_cast<const T*>(p.Q), static_cast<const T*>(p.K),
                      static_cast<const T*>(p.V), static_cast<const T*>(p.dO), p.mask, states,
                      dstates, static_cast<T*>(p.dQ), static_cast<T*>(p.dK),
@@ -415,6 +454,7 @@ hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
     case 16: return bwd ? run_bwd<T, 16>(p, plan) : run_fwd<T, 16>(p, plan);
     case 32: return bwd ? run_bwd<T, 32>(p, plan) : run_fwd<T, 32>(p, plan);
     case 64: return bwd ? run_bwd<T, 64>(p, plan) : run_fwd<T, 64>(p, plan);
+    case 128: return bwd ? run_bwd<T, 128>(p, plan) : run_fwd<T, 128>(p, plan);
     default: return hipErrorInvalidValue;
   }
 }

@@ -61,7 +61,8 @@ def test_validation_errors_touch_no_device(lib):
     assert _fwd(lib, N=-5) == -2
     assert _bwd(lib, H=0) == -2
     assert _fwd(lib, d=48) == -3
-    assert _fwd(lib, d=128) == -3
+    assert _fwd(lib, d=256) == -3
+    assert _fwd(lib, d=96) == -3
     assert _bwd(lib, d=0) == -3
     assert _fwd(lib, K=0x2004) == -5
     assert _bwd(lib, dV=0x7008) == -5

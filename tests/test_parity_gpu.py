@@ -284,6 +284,20 @@ def test_fp16_io(oracle, B, H, N, d):
     assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("N", [33, 200, 700])
+def test_head_dim_128(oracle, dtype, N):
+    """d_h = 128 (d_model 256 with two heads): served by the vector-ALU kernels, whose backward
+    splits dV and dK over separate blocks at this size."""
+    B, H, d = 2, 2, 128
+    Q, K, V, dO = _case(9100 + N, B, H, N, d, dtype)
+    mask = (np.random.default_rng(N).random((B, N)) < 0.7).astype(np.uint8)
+    mask[:, -1] = 1
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"d=128 N={N}")
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], got_o.shape)
+    assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
+
+
 def test_binding_reports_library_errors():
     x = torch.zeros(1, 1, 8, 48, device="cuda")
     with pytest.raises(binding.CottenError) as ei:
