@@ -194,8 +194,8 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
 
   int slice = blockIdx.x;
   Raw rq, rk;
-  // The first slice: Q does not have to wait for the mask bytes that select the K, V rows.
-  fetch<false, 2>(rq, rk, a, L0, slice, tile, 0);
+  // The first slice: only K and V are requested at once (every compute unit asks at the same
+  // moment, and the first phase needs nothing else); Q follows when those have arrived.
   fetch<false, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
   // Per slice (B = workgroup barrier):
@@ -207,13 +207,16 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
   COTTEN_RTRACE(0);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
     COTTEN_RTRACE_IT(1);
-    if (mine) {
+    {
       const Lane L = L0.again();
-      float inv[2];
-      if (__ballot(rk.live != 0) != 0)
-        stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
-      else
-        clear_tiles(L, blk + kKt, blk + kVt);
+      if (mine) {
+        float inv[2];
+        if (__ballot(rk.live != 0) != 0)
+          stage<F, kXNormalized, true>(rk, L, a.eps, blk + kKt, blk + kVt, inv);
+        else
+          clear_tiles(L, blk + kKt, blk + kVt);
+      }
+      if (iter == 0) fetch<false, 2>(rq, rk, a, L, slice, tile, 0);
     }
     COTTEN_RTRACE_IT(2);
     __syncthreads();
@@ -323,19 +326,25 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   int slice = blockIdx.x;
   Raw rq, rk;
   COTTEN_RTRACE(0);
+  // The first slice: only Q and dO are requested at once (every compute unit asks at the same
+  // moment, and the first phase needs nothing else); K and V follow when those have arrived
+  // and travel while Q, dO are staged and dS is built.
+  const int first_keys = key_rows(a, L0, slice, tile);
   fetch<true, 2>(rq, rk, a, L0, slice, tile, 0);
-  fetch<true, 1>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
   int keys = key_rows(a, L0, slice + stride, tile);
   float* dots = reinterpret_cast<float*>(smem + Lds<F>::kDots);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
     const size_t base = a.st.slice_base(slice, a.H);
     const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
     COTTEN_RTRACE_IT(1);
-    if (mine) {
+    {
       const Lane L = L0.again();
-      float inv[2];
-      stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
-      publish_inv(invs + tile * 2 * TR, L, inv);
+      if (mine) {
+        float inv[2];
+        stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
+        publish_inv(invs + tile * 2 * TR, L, inv);
+      }
+      if (iter == 0) fetch<true, 1>(rq, rk, a, L, slice, tile, first_keys);
     }
     COTTEN_RTRACE_IT(2);
     __syncthreads();
