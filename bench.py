@@ -147,10 +147,11 @@ def measured_traffic(workload, kernel_tags):
         return None
     total, seen = 0.0, 0
     for line in open(paths[-1]):
-        parts = line.strip().split(",")
-        if len(parts) == 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") \
-                and any(t in parts[1] for t in kernel_tags) and parts[2].endswith("MB per launch"):
-            total += float(parts[2].split()[0]) * 1e6
+        parts = line.strip().split(",")      # kernel names may contain commas themselves
+        if len(parts) >= 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") \
+                and any(t in ",".join(parts[1:-1]) for t in kernel_tags) \
+                and parts[-1].endswith("MB per launch"):
+            total += float(parts[-1].split()[0]) * 1e6
             seen += 1
     return int(total) if seen else None
 

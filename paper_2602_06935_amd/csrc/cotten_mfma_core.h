@@ -654,24 +654,32 @@ __device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
   for (int c = 0; c < 2 * F::EPL; ++c) p[c] = p[c] * inv_r - x[c] * proj;
 }
 
-// STREAM: non-temporal stores.  Results are not read again by these kernels, and written this
-// way they do not displace the inputs still on their way through L2 (measured: a clear gain
-// where a workgroup owns a whole slice, none where long sequences are cut up).  Loads are
-// better left with the default policy in every kernel here.
-template <class F, bool STREAM>
+// Cache policy of the result stores.  Results are not read again by these kernels, and with
+// the default policy the written lines displace the inputs still on their way through L2.
+// Measured at N = 200 on the benchmark's alternating forward / backward steps (tokens/s of the
+// step, fp32 fused and bf16 resident kernels): default 1.6 G and 0.77 G; nt 1.88 G and 0.90 G;
+// sc0 sc1 nt 1.91 G and 0.93 G; sc0 sc1 without nt is the best for a forward run on its own
+// but loses 8 % in the step.  Where long sequences are cut up (split kernels) every policy but
+// the default loses a few percent.  Loads are better left with the default policy everywhere.
+constexpr int kStoreDefault = 0, kStoreStreamed = 19;  // aux bits: sc0 = 1, nt = 2, sc1 = 16
+
+template <class F, int POLICY>
 __device__ __forceinline__ void store_product_row(unsigned char* __restrict__ dst, int row,
                                                   RowAddr addr, const Lane& L,
                                                   const float (&p)[2 * F::EPL]) {
+  // dst is a slice base: the byte offsets of its rows fit 31 bits (checked by the caller of
+  // the library entry point)
+  __amdgpu_buffer_rsrc_t out;
+  if (POLICY != kStoreDefault) out = __builtin_amdgcn_make_buffer_rsrc(dst, 0, 0x7fffffff, 0x00020000);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     if (64 * j + 16 * L.g16 >= addr.bytes) break;  // narrower rows: the rest is padding
     float c[F::EPL];
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) c[i] = p[F::EPL * j + i];
-    u32x4_t* at =
-        reinterpret_cast<u32x4_t*>(dst + static_cast<size_t>(row) * addr.stride + 64 * j + 16 * L.g16);
-    if (STREAM) __builtin_nontemporal_store(F::pack(c), at);
-    else *at = F::pack(c);
+    const uint32_t off = static_cast<uint32_t>(row) * addr.stride + 64 * j + 16 * L.g16;
+    if (POLICY != kStoreDefault) __builtin_amdgcn_raw_buffer_store_b128(F::pack(c), out, off, 0, POLICY);
+    else *reinterpret_cast<u32x4_t*>(dst + off) = F::pack(c);
   }
 }
 

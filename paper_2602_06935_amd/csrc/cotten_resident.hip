@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
       const int row = tile * TR + L.i16;
       if (row < N)
-        store_product_row<F, true>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
+        store_product_row<F, kStoreStreamed>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
     }
     COTTEN_RTRACE_IT(6);
   }
@@ -292,7 +292,7 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
       project_rows<F, true>(p, e, invs[t * 2 * TR + (kind == 0 ? 0 : TR) + L.i16], L);
     }
   }
-  if (row < N) store_product_row<F, true>(dst, row, row_addr, L, p);
+  if (row < N) store_product_row<F, kStoreStreamed>(dst, row, row_addr, L, p);
 }
 
 // Backward, per slice (B = workgroup barrier).  Q and dO come first because their loads do not
