@@ -659,8 +659,8 @@ __device__ __forceinline__ void project_rows_raw(float (&p)[2 * F::EPL],
 // Measured at N = 200 on the benchmark's alternating forward / backward steps (tokens/s of the
 // step, fp32 fused and bf16 resident kernels): default 1.6 G and 0.77 G; nt 1.88 G and 0.90 G;
 // sc0 sc1 nt 1.91 G and 0.93 G; sc0 sc1 without nt is the best for a forward run on its own
-// but loses 8 % in the step.  Where long sequences are cut up (split kernels) every policy but
-// the default loses a few percent.  Loads are better left with the default policy everywhere.
+// but loses 8 % in the step.  The split kernels (N = 4096): default 0.64 G, nt 0.63 G, sc0 sc1
+// 0.63 G, sc0 sc1 nt 0.67 G.  Loads are better left with the default policy everywhere.
 constexpr int kStoreDefault = 0, kStoreStreamed = 19;  // aux bits: sc0 = 1, nt = 2, sc1 = 16
 
 template <class F, int POLICY>
