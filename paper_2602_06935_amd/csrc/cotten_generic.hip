@@ -294,15 +294,25 @@ __global__ __launch_bounds__(kThreads) void apply_bwd_kernel(
         gv[i] = h[i] = 0.0f;
       }
       __syncthreads();
-      if (do_dv) {
+      if (kTogether) {
 #pragma unroll 8
         for (int a = 0; a < D; ++a) {
           const float ka = t0[lrow][a];  // dV_c = sum_a khat_a dS[a][c]
+          const float va = t1[lrow][a];  // h_a  = sum_c v_c dS[a][c] = sum_c v_c dS^T[c][a]
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            gv[i] += ka * Mv[a][c0 + i];
+            h[i] += va * Mk[a][c0 + i];
+          }
+        }
+      } else if (do_dv) {
+#pragma unroll 8
+        for (int a = 0; a < D; ++a) {
+          const float ka = t0[lrow][a];
 #pragma unroll
           for (int i = 0; i < CH; ++i) gv[i] += ka * Mv[a][c0 + i];
         }
-      }
-      if (do_dk) {
+      } else {
 #pragma unroll 8
         for (int a = 0; a < D; ++a) {
           const float va = t1[lrow][a];  // h_a  = sum_c v_c dS[a][c] = sum_c v_c dS^T[c][a]
