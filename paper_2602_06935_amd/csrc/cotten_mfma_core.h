@@ -146,7 +146,9 @@ struct Half64 {
   static constexpr int D = 64, EPL = 8, NT = 4;
   // tiles in flight ahead of the one being processed, per pass (register budget permitting)
   static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 2, kDepthKV = 2, kDepthQAccum = 1;
-  static constexpr bool kShortKernels = false;  // keep-all-tiles-in-registers variants
+  // keep-all-tiles-in-registers variants of the fused kernels: forward only (the backward
+  // does not have the registers)
+  static constexpr bool kShortFwd = true, kShortBwd = false;
   static constexpr int kImageStride = 72;                 // elements per image row
   static constexpr int kImageBytes = D * kImageStride * 2;
   // Apply products leave lane (i16, g16) with the columns 32j + 8*g16 .. +7 (j = 0, 1) of tile
@@ -366,7 +368,7 @@ struct F32x32 {
   typedef float io_t;
   static constexpr int D = 32, EPL = 4, NT = 2;
   static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 3, kDepthKV = 2, kDepthQAccum = 2;
-  static constexpr bool kShortKernels = true;
+  static constexpr bool kShortFwd = true, kShortBwd = true;
   static constexpr int kImageStride = 36;
   static constexpr int kImageBytes = D * kImageStride * 4;
   // Apply products leave lane (i16, g16) with the columns 16j + 4*g16 .. +3 (j = 0, 1) of tile
