@@ -298,6 +298,23 @@ def test_head_dim_128(oracle, dtype, N):
     assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
 
 
+@pytest.mark.parametrize("dtype,d,N", [("f16", 64, 200), ("bf16", 32, 180), ("bf16", 16, 208), ("bf16", 64, 161)])
+def test_many_short_slices_16bit(oracle, dtype, d, N):
+    """256 slices and more of 16-bit sequences above 160 rows: the forward runs on the fused
+    kernel that keeps its tiles in registers, the backward on the resident kernel."""
+    B, H = 64, 4
+    Q, K, V, dO = _case(9500 + N + d, B, H, N, d, dtype)
+    rng = np.random.default_rng(N + d)
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        mask[b, N - int(rng.integers(1, N + 1)):] = 1
+    mask[5] = 0
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"256 slices {dtype} d={d} N={N}")
+    assert np.all(got_o[5] == 0.0)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], got_o.shape)
+    assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
+
+
 def test_binding_reports_library_errors():
     x = torch.zeros(1, 1, 8, 48, device="cuda")
     with pytest.raises(binding.CottenError) as ei:
