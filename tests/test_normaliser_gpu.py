@@ -143,3 +143,22 @@ def test_layout_argument_errors():
     assert rc == -2
     with pytest.raises(ValueError):
         binding.cotten_attn_fwd(t, t, t, None, layout="nhbd")
+
+
+def test_autograd_wrapper(oracle):
+    """The autograd plumbing: gradients of sum(O * dO) with respect to Q, K, V and the
+    per-slice scales equal what the backward entry point returns and what the oracle says."""
+    from paper_2602_06935_amd.autograd import cosine_attention
+    B, H, N, d = 4, 2, 120, 32
+    Q, K, V, dO, mask, lengths, m = _inputs(77, "f32", B, H, N, d)
+    tq, tk, tv, tg = (to_gpu(x, "f32").requires_grad_(i < 3) for i, x in enumerate((Q, K, V, dO)))
+    tm = torch.from_numpy(mask).cuda()
+    ss = (torch.rand(B, H, device="cuda") + 0.2).requires_grad_(True)
+    O = cosine_attention(tq, tk, tv, tm, slice_scale=ss)
+    (O * tg).sum().backward()
+    torch.cuda.synchronize()
+    s64 = ss.detach().double().cpu().numpy()
+    ref = oracle.scaled_bwd(Q, K, V, dO, s64, mask)
+    for got, want in zip((tq.grad, tk.grad, tv.grad), ref[:3]):
+        assert rel_l2(to_f64(got), want) <= 1e-5
+    assert rel_l2(ss.grad.double().cpu().numpy(), ref[3] / s64) <= 1e-5
