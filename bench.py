@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # dense, published
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 640 << 20       # rotate over at least this many bytes of tensors
 
@@ -67,6 +68,10 @@ class DeviceBatch:
         self.bytes_fwd_dense = 4 * self.tensor_bytes
         self.bytes_bwd_dense = 7 * self.tensor_bytes
         self.tokens = w.B * batch.Q.shape[2]
+        # algorithmic flops of the backward call per token-head: S (2 d^2, valid keys only), dS
+        # and g (2 d^2 each, every row), dV and h (4 d^2, valid keys only)
+        rows = w.B * w.H * batch.Q.shape[2]
+        self.flops_bwd = rows * w.d_h * w.d_h * (4 + 6 * f)
 
 
 def run_steps(db, binding, n, first=0, fwd=True, bwd=True):
@@ -275,6 +280,11 @@ def main():
                         "launch_us": round(res["fwd_us"], 2), "algorithmic_bytes_per_launch": int(db.bytes_fwd)},
             "step": {"achieved": round(res["step_gbs"], 1), "frac": round(res["step_gbs"] / HBM_PEAK_GBS, 4),
                      "achieved_dense_bytes": round(res["step_gbs_dense"], 1)},
+            # the contractions run on the matrix cores: how much of their peak the call uses
+            "matrix_cores": {"achieved": round(db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12, 2),
+                             "peak": MFMA_PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
+                             "frac": round(db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12
+                                           / MFMA_PEAK_TFLOPS[w.dtype], 4)},
         },
         "cpu_baseline": cpu,
         "other_workloads": others,
