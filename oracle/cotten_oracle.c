@@ -28,6 +28,11 @@
  * returns d/d(log s_bh) = sum_i dO_i . O_i (O is linear in s), and
  * cotten_oracle_normaliser_bwd turns that into dm_h = -sum_b ln(n_b) dlog_s_bh.
  *
+ * The causal variant (what the paper's bidirectional model removes, "no causal mask": row i
+ * attends keys j <= i only) is stated here from its definition with all N x N cosines,
+ * cotten_oracle_causal_fwd / _bwd, so that the prefix-state kernels can be checked against
+ * something that has no prefix state in it.
+ *
  * Pins (tests/test_oracle_pins.py): linear == quadratic on small inputs;
  * closed forms; unit norms; masked-key invariance; permutation equivariance;
  * fp64 autograd of the library expression; central finite differences and an
@@ -251,5 +256,107 @@ void cotten_oracle_normaliser_bwd(const double* dlog_s, const double* n, double*
     double acc = 0.0;
     for (int b = 0; b < B; ++b) acc += log(n[b]) * dlog_s[(size_t)b * H + h];
     dm[h] = -acc;
+  }
+}
+
+/* ---- causal variant: row i sees keys j <= i ---------------------------------- */
+
+/* P[i][j] = cos(q_i, k_j) for j <= i and valid key j, else 0 (row-major N x N). */
+static void causal_cosines(const double* q, const double* k, const uint8_t* mask, int b, int N,
+                           int d, double eps, double* P, double* rq, double* rk) {
+  for (int i = 0; i < N; ++i) {
+    rq[i] = row_norm(q + (size_t)i * d, d, eps);
+    rk[i] = row_norm(k + (size_t)i * d, d, eps);
+  }
+  for (int i = 0; i < N; ++i)
+    for (int j = 0; j < N; ++j) {
+      double p = 0.0;
+      if (j <= i && key_valid(mask, b, N, j)) {
+        for (int a = 0; a < d; ++a) p += q[(size_t)i * d + a] * k[(size_t)j * d + a];
+        p /= rq[i] * rk[j];
+      }
+      P[(size_t)i * N + j] = p;
+    }
+}
+
+/* O_i = scale * sum_{j <= i} m_j cos(q_i, k_j) v_j */
+void cotten_oracle_causal_fwd(const double* Q, const double* K, const double* V,
+                              const uint8_t* mask, double* O, int B, int H, int N, int d,
+                              double scale, double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const size_t off = (size_t)bh * N * d;
+    double* P = (double*)malloc(sizeof(double) * (size_t)N * N);
+    double* rq = (double*)malloc(sizeof(double) * N);
+    double* rk = (double*)malloc(sizeof(double) * N);
+    causal_cosines(Q + off, K + off, mask, bh / H, N, d, eps, P, rq, rk);
+    for (int i = 0; i < N; ++i)
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int j = 0; j <= i; ++j) acc += P[(size_t)i * N + j] * V[off + (size_t)j * d + c];
+        O[off + (size_t)i * d + c] = scale * acc;
+      }
+    free(P); free(rq); free(rk);
+  }
+}
+
+/* Backward of the same expression through the N x N matrix: with P as above and
+ * G[i][j] = scale * (dO_i . v_j) on the same support,
+ *   dV_j = scale * sum_i P[i][j] dO_i,  dqhat_i = sum_j G[i][j] khat_j,
+ *   dkhat_j = sum_i G[i][j] qhat_i,  and  dx = (dxhat - xhat (xhat . dxhat)) / r. */
+void cotten_oracle_causal_bwd(const double* Q, const double* K, const double* V,
+                              const uint8_t* mask, const double* dO, double* dQ, double* dK,
+                              double* dV, int B, int H, int N, int d, double scale,
+                              double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const double *q = Q + off, *k = K + off, *v = V + off, *go = dO + off;
+    double* P = (double*)malloc(sizeof(double) * (size_t)N * N);
+    double* G = (double*)malloc(sizeof(double) * (size_t)N * N);
+    double* rq = (double*)malloc(sizeof(double) * N);
+    double* rk = (double*)malloc(sizeof(double) * N);
+    double* xh = (double*)malloc(sizeof(double) * d);
+    double* gh = (double*)malloc(sizeof(double) * d);
+    causal_cosines(q, k, mask, b, N, d, eps, P, rq, rk);
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j < N; ++j) {
+        double g = 0.0;
+        if (j <= i && key_valid(mask, b, N, j)) {
+          for (int c = 0; c < d; ++c) g += go[(size_t)i * d + c] * v[(size_t)j * d + c];
+          g *= scale;
+        }
+        G[(size_t)i * N + j] = g;
+      }
+    for (int j = 0; j < N; ++j)
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int i = j; i < N; ++i) acc += P[(size_t)i * N + j] * go[(size_t)i * d + c];
+        dV[off + (size_t)j * d + c] = scale * acc;
+      }
+    for (int i = 0; i < N; ++i) {
+      double proj = 0.0;
+      for (int a = 0; a < d; ++a) {
+        xh[a] = q[(size_t)i * d + a] / rq[i];
+        double acc = 0.0;
+        for (int j = 0; j <= i; ++j) acc += G[(size_t)i * N + j] * k[(size_t)j * d + a] / rk[j];
+        gh[a] = acc;
+        proj += xh[a] * acc;
+      }
+      for (int a = 0; a < d; ++a) dQ[off + (size_t)i * d + a] = (gh[a] - xh[a] * proj) / rq[i];
+    }
+    for (int j = 0; j < N; ++j) {
+      double proj = 0.0;
+      for (int a = 0; a < d; ++a) {
+        xh[a] = k[(size_t)j * d + a] / rk[j];
+        double acc = 0.0;
+        for (int i = j; i < N; ++i) acc += G[(size_t)i * N + j] * q[(size_t)i * d + a] / rq[i];
+        gh[a] = acc;
+        proj += xh[a] * acc;
+      }
+      for (int a = 0; a < d; ++a) dK[off + (size_t)j * d + a] = (gh[a] - xh[a] * proj) / rk[j];
+    }
+    free(P); free(G); free(rq); free(rk); free(xh); free(gh);
   }
 }

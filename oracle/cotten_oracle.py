@@ -51,6 +51,10 @@ def _load():
         lib.cotten_oracle_scaled_fwd.restype = None
         lib.cotten_oracle_scaled_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, dp, dp, i, i, i, i, f]
         lib.cotten_oracle_scaled_bwd.restype = None
+        lib.cotten_oracle_causal_fwd.argtypes = [dp, dp, dp, bp, dp, i, i, i, i, f, f]
+        lib.cotten_oracle_causal_fwd.restype = None
+        lib.cotten_oracle_causal_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, i, i, i, i, f, f]
+        lib.cotten_oracle_causal_bwd.restype = None
         lib.cotten_oracle_threads.argtypes = []
         lib.cotten_oracle_threads.restype = ctypes.c_int
         _lib = lib
@@ -154,3 +158,20 @@ def scaled_bwd(Q, K, V, dO, s, mask=None, eps: float = 1e-6):
     _load().cotten_oracle_scaled_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(s), _ptr(dO), _ptr(dQ),
                                      _ptr(dK), _ptr(dV), _ptr(dlog), B, H, N, d, float(eps))
     return dQ, dK, dV, dlog
+
+
+def causal_fwd(Q, K, V, mask=None, scale: Optional[float] = None, eps: float = 1e-6):
+    """Causal variant from its definition: row i attends the valid keys j <= i."""
+    return _fwd("cotten_oracle_causal_fwd", Q, K, V, mask, scale, eps)
+
+
+def causal_bwd(Q, K, V, dO, mask=None, scale: Optional[float] = None, eps: float = 1e-6):
+    """(dQ, dK, dV) of the causal variant, through the N x N matrix."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    B, H, N, d = Q.shape
+    s = 1.0 / N if scale is None else float(scale)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(dO), _ptr(dQ), _ptr(dK),
+                                     _ptr(dV), B, H, N, d, s, float(eps))
+    return dQ, dK, dV

@@ -390,3 +390,55 @@ def test_normaliser_gradient_against_autograd_and_differences(oracle):
         assert abs((lp - lm) / (2 * step) - dm[h]) < 1e-6 * max(1.0, abs(dm[h]))
     # n = 1 for every sequence: ln n = 0, the exponent has no effect
     assert np.all(oracle.normaliser_bwd(dlog, np.ones(B)) == 0.0)
+
+
+# --------------------------------------------------------------- causal variant pins
+
+def test_causal_rows_are_bidirectional_prefixes(oracle):
+    """Row i of the causal output is row i of the bidirectional attention over the first i+1
+    rows only (the pinned quadratic definition on a truncated sequence)."""
+    Q, K, V, _, mask = _small_case(61, N=12, d=6)
+    O = oracle.causal_fwd(Q, K, V, mask, scale=0.4, eps=1e-6)
+    for i in (0, 3, 7, 11):
+        ref = oracle.fwd_quadratic(Q[:, :, :i + 1], K[:, :, :i + 1], V[:, :, :i + 1], mask[:, :i + 1],
+                                   scale=0.4, eps=1e-6)
+        assert _rel(O[:, :, i], ref[:, :, i]) < 1e-13
+    # the last row sees everything: it is the bidirectional row
+    full = oracle.fwd_linear(Q, K, V, mask, scale=0.4, eps=1e-6)
+    assert _rel(O[:, :, -1], full[:, :, -1]) < 1e-13
+    # no mask == all-ones mask
+    assert _rel(oracle.causal_fwd(Q, K, V, None, scale=0.4), oracle.causal_fwd(Q, K, V, np.ones_like(mask), scale=0.4)) < 1e-15
+
+
+def test_causal_backward_against_autograd_and_differences(oracle):
+    import torch
+    Q, K, V, dO, mask = _small_case(62, B=2, H=2, N=14, d=6)
+    eps, s = 1e-6, 0.37
+    dQ, dK, dV = oracle.causal_bwd(Q, K, V, dO, mask, scale=s, eps=eps)
+    t = lambda x: torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True)
+    q, k, v = t(Q), t(K), t(V)
+    qh = q / torch.sqrt((q * q).sum(-1, keepdim=True) + eps)
+    kh = k / torch.sqrt((k * k).sum(-1, keepdim=True) + eps)
+    N = Q.shape[2]
+    allowed = torch.tril(torch.ones(N, N, dtype=torch.float64))[None, None] * torch.tensor(mask.astype(np.float64))[:, None, None, :]
+    O = s * torch.matmul(torch.matmul(qh, kh.transpose(-1, -2)) * allowed, v)
+    assert _rel(oracle.causal_fwd(Q, K, V, mask, scale=s, eps=eps), O.detach().numpy()) < 1e-13
+    O.backward(torch.tensor(dO))
+    assert _rel(dQ, q.grad.numpy()) < 1e-12 and _rel(dK, k.grad.numpy()) < 1e-12 and _rel(dV, v.grad.numpy()) < 1e-12
+    masked = np.broadcast_to((mask == 0)[:, None, :, None], dK.shape)
+    assert np.all(dK[masked] == 0.0) and np.all(dV[masked] == 0.0)
+    # central differences on a few coordinates
+    loss = lambda q_, k_, v_: np.sum(dO * oracle.causal_fwd(q_, k_, v_, mask, scale=s, eps=eps))
+    rng = np.random.default_rng(1)
+    for name, X, G in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for _ in range(4):
+            idx = tuple(int(rng.integers(n)) for n in X.shape)
+            if name != "Q" and mask[idx[0], idx[2]] == 0:
+                continue
+            Xp, Xm = X.copy(), X.copy()
+            Xp[idx] += 1e-6
+            Xm[idx] -= 1e-6
+            args = {"Q": (Xp, K, V), "K": (Q, Xp, V), "V": (Q, K, Xp)}[name]
+            argm = {"Q": (Xm, K, V), "K": (Q, Xm, V), "V": (Q, K, Xm)}[name]
+            fd = (loss(*args) - loss(*argm)) / 2e-6
+            assert abs(fd - G[idx]) < 1e-6 * max(1.0, abs(G[idx]))
