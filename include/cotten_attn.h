@@ -102,7 +102,8 @@ typedef enum cotten_status {
   COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is not a cotten_dtype                  */
   COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
   COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* params->workspace_bytes below the requirement */
-  COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf   */
+  COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf, or
+                                           an option combination that is not available   */
   COTTEN_ERR_LAUNCH = -8,               /* the HIP runtime refused a launch             */
   COTTEN_ERR_ALLOC = -9                 /* the library-owned workspace could not grow   */
 } cotten_status;
@@ -118,6 +119,11 @@ typedef struct cotten_params {
   float* dlog_scale;      /* backward only: device, [B*H] floats, or NULL.  When given it
                              receives sum_i dO_i . O_i of every slice (see above)          */
   int layout;             /* a cotten_layout: applies to Q, K, V, O, dO, dQ, dK and dV     */
+  int causal;             /* 0: bidirectional (the paper's model).  1: row i attends only the
+                             valid keys j <= i (the variant the paper's model leaves out, "no
+                             causal mask"): O_i = scale * qhat_i sum_{j<=i} m_j khat_j^T v_j
+                             and its exact gradients.  d_h in {16, 32, 64}; no workspace;
+                             dlog_scale is not available (COTTEN_ERR_BAD_PARAM)            */
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):

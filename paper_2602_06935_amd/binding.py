@@ -33,7 +33,7 @@ class CottenParams(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int), ("scale", ctypes.c_float), ("eps", ctypes.c_float),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p),
-                ("layout", ctypes.c_int)]
+                ("layout", ctypes.c_int), ("causal", ctypes.c_int)]
 
 
 class CottenError(RuntimeError):
@@ -138,8 +138,10 @@ def _dims(Q: torch.Tensor, layout: str) -> Tuple[int, int, int, int]:
 
 def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
             slice_scale: Optional[torch.Tensor] = None,
-            dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd") -> CottenParams:
+            dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
+            causal: bool = False) -> CottenParams:
     p = CottenParams()
+    p.causal = int(bool(causal))
     B, H, _, _ = _dims(Q, layout)
     p.layout = COTTEN_BNHD if layout == "bnhd" else COTTEN_BHND
     slices = B * H
@@ -172,7 +174,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     scale: Optional[float] = None, eps: Optional[float] = None,
                     stream=None, workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
-                    layout: str = "bhnd") -> torch.Tensor:
+                    layout: str = "bhnd", causal: bool = False) -> torch.Tensor:
     """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O.
     `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`;
     `layout` "bnhd" means all tensors are [B,N,H,d_h] instead of [B,H,N,d_h]."""
@@ -182,7 +184,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     if O is None:
         O = torch.empty_like(Q)
     _prep("O", O, Q)
-    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout)
+    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
@@ -197,8 +199,8 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     eps: Optional[float] = None, stream=None,
                     workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
-                    dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd"
-                    ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+                    dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
+                    causal: bool = False) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
     `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
     d loss / d log(scale) of every slice."""
@@ -208,7 +210,7 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     dQ = torch.empty_like(Q) if dQ is None else _prep("dQ", dQ, Q)
     dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
     dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
-    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout)
+    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),

@@ -97,6 +97,17 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   if ((static_cast<long long>(N - 1) * p.stride_row + d_h) * (prm->dtype == COTTEN_F32 ? 4 : 2) >=
       (1ll << 31))
     return COTTEN_ERR_BAD_SHAPE;
+  if (prm->causal != 0) {
+    if (prm->causal != 1 || (bwd && prm->dlog_scale != nullptr)) return COTTEN_ERR_BAD_PARAM;
+    if (!cotten::causal_supports(d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
+    p.slice_scale = prm->slice_scale;
+    p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
+    p.O = O; p.dQ = dQ; p.dK = dK; p.dV = dV;
+    p.B = B; p.H = H; p.N = N; p.D = d_h;
+    p.dtype = prm->dtype;
+    p.stream = static_cast<hipStream_t>(stream);
+    return cotten::launch_causal(p, bwd) == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
+  }
   const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
   const size_t need = plan.workspace_floats * sizeof(float);
   if (prm->workspace != nullptr) {
@@ -122,7 +133,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 
-const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr, COTTEN_BHND};
+const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr, COTTEN_BHND, 0};
 
 }  // namespace
 
@@ -185,7 +196,7 @@ const char* cotten_status_string(int status) {
     case COTTEN_ERR_BAD_DTYPE: return "dtype must be COTTEN_F32, COTTEN_BF16 or COTTEN_F16";
     case COTTEN_ERR_MISALIGNED: return "tensor and workspace pointers must be 16-byte aligned";
     case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";
-    case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite";
+    case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite; option combination not available";
     case COTTEN_ERR_LAUNCH: return "HIP kernel launch failed";
     case COTTEN_ERR_ALLOC: return "could not allocate the library-owned workspace";
     default: return "unknown status";

@@ -81,4 +81,8 @@ hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_
 hipError_t launch_normaliser_bwd(const float* dlog, const int32_t* n, float* dm, int B, int H,
                                  int N, hipStream_t stream);
 
+// Causal variant (row i attends keys j <= i): vector-ALU scan kernels, d_h in {16, 32, 64}.
+bool causal_supports(int D);
+hipError_t launch_causal(const Problem& p, bool bwd);
+
 }  // namespace cotten
