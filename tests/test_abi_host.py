@@ -80,6 +80,11 @@ def test_validation_errors_touch_no_device(lib):
     assert _fwd(lib, N=1 << 24) == -2
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, binding.COTTEN_BNHD)
     assert _fwd(lib, H=8, N=1 << 22, prm=p) == -2
+    # the causal variant: flag must be 0 or 1, d_h at most 64
+    p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 2)
+    assert _fwd(lib, prm=p) == -7
+    p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 1)
+    assert _fwd(lib, d=128, prm=p) == -3
     # the normaliser entry points validate on the host as well
     assert lib.cotten_normaliser_fwd(None, None, 0x1000, 4, 2, 50, None) == -1
     assert lib.cotten_normaliser_fwd(0x1000, None, None, 4, 2, 50, None) == -1
