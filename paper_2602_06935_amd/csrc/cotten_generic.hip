@@ -503,7 +503,11 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
       plan.workspace_floats = 0;
       return plan;
     }
-    if (N <= kFusedMaxN && (BH >= 256 || N <= 256)) {
+    // Long sequences stay on one workgroup per slice as well when there are slices enough
+    // (measured at N = 3000 ... 4096: the backward from 256 slices on, the forward from 512).
+    constexpr long kFusedLongMaxN = 16384;  // key flags of the slice must fit LDS
+    const bool fused_long = N <= kFusedLongMaxN && BH >= (is_bwd ? 256 : 512);
+    if ((N <= kFusedMaxN && (BH >= 256 || N <= 256)) || fused_long) {
       plan.path = Plan::kFused;
       plan.splits = 1;
       plan.rows_per_split = N;

@@ -315,6 +315,18 @@ def test_many_short_slices_16bit(oracle, dtype, d, N):
     assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
 
 
+def test_long_sequences_with_many_slices(oracle):
+    """256 slices of more than 2048 rows: the backward stays on one workgroup per slice (fused
+    streaming kernel), the forward is cut into splits."""
+    B, H, N, d = 128, 2, 2100, 32
+    Q, K, V, dO = _case(9700, B, H, N, d, "f32")
+    rng = np.random.default_rng(3)
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        mask[b, N - int(rng.integers(1, N + 1)):] = 1
+    _check_case(oracle, Q, K, V, dO, mask, "f32", label="256 slices x 2100 rows")
+
+
 def test_binding_reports_library_errors():
     x = torch.zeros(1, 1, 8, 48, device="cuda")
     with pytest.raises(binding.CottenError) as ei:
