@@ -73,6 +73,8 @@ hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 bool resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_fwd(const Problem& p);
 hipError_t launch_resident_bwd(const Problem& p);
+// The causal variant on the matrix cores, for the shapes resident_supports() accepts.
+hipError_t launch_resident_causal(const Problem& p, bool bwd);
 
 // Learnable normaliser: slice_scale[b*H+h] = n_b^(-m_h), and dm[h] = -sum_b ln(n_b) dlog[b*H+h].
 // n may be nullptr (n_b = N).

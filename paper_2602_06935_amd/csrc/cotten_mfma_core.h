@@ -13,6 +13,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int TR = 16;               // rows per wave tile
 constexpr int kRowBytes = 128;       // bytes of one tile row: d_h elements, or d_h/2 elements
@@ -109,6 +110,18 @@ struct Bf16Elem {
     typedef v4 __attribute__((address_space(3))) * lds_v4;
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p));
   }
+  // 16x16x16: A lane (i = lane%16, k = 4*(lane/16) + e), B lane (j = lane%16, same k): the k
+  // a lane holds is the row group it holds of a 16x16 result, so a result (rounded) can be fed
+  // back as the B operand without moving between lanes
+  static __device__ __forceinline__ f32x4_t mfma_k16(v4 a, v4 b, f32x4_t c) {
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a),
+                                                     __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ v4 pack4(f32x4_t x) {
+    u32x2_t r = {pack2(x[0], x[1]), pack2(x[2], x[3])};
+    return __builtin_bit_cast(v4, r);
+  }
 };
 
 struct F16Elem {
@@ -137,10 +150,18 @@ struct F16Elem {
     typedef raw4 __attribute__((address_space(3))) * lds_v4;
     return __builtin_bit_cast(v4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_v4)(p)));
   }
+  static __device__ __forceinline__ f32x4_t mfma_k16(v4 a, v4 b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ v4 pack4(f32x4_t x) {
+    u32x2_t r = {pack2(x[0], x[1]), pack2(x[2], x[3])};
+    return __builtin_bit_cast(v4, r);
+  }
 };
 
 template <class E>
 struct Half64 {
+  typedef E Elem;
   typedef typename E::v8 v8_t;
   typedef typename E::v4 v4_t;
   static constexpr int D = 64, EPL = 8, NT = 4;

@@ -408,6 +408,210 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   }
 }
 
+// ---- causal variant on the matrix cores ------------------------------------------------------
+// Row i attends the valid keys j <= i.  With the whole slice in LDS this is done tile pair by
+// tile pair, (query tile t, key tile u <= t), all pairs independent:
+//
+//     P^T  = Khat_u Q_t^T          16 keys x 16 queries, two 16x16x32 MFMAs (contraction over d)
+//     O_t^T += V_u^T P^T           16x16x16 MFMAs, one per 16 output columns
+//
+// A 16x16 MFMA result leaves lane (j, g) with rows 4g .. 4g+3 of column j - exactly the k a
+// lane of a 16x16x16 B operand holds - so P (rounded to the element type, diagonal tile cut to
+// its lower triangle) goes into the second product without moving between lanes; the A
+// operand V_u^T comes from the transposing LDS read, with its columns picked so that the
+// result lands in the product layout of the other kernels.  Wave t owns query tile t (and,
+// in the backward, key tile t: t + 1 pairs in one role, n - t in the other, the same work for
+// every wave).  Backward, with G^T = V_u dO_t^T on the same support:
+//     dQhat_t^T += Khat_u^T G^T                         (as query tile t, over u <= t)
+//     dV_u^T    += dO_t^T P,    H_u^T += Qhat_t^T G     (as key tile u, over t >= u)
+// and the row-norm Jacobians as everywhere else.
+
+// The operand X^T for 16 output columns (group nt of the product layout) of the 16-row tile
+// at `T`: lane i of a 16-lane group gets rows 4g .. 4g+3 of column out_col(nt, i/4) + i%4.
+template <class F>
+__device__ __forceinline__ typename F::v4_t transposed_rows(const unsigned char* T, const Lane& L,
+                                                            int nt) {
+  return F::Elem::read_tr(T + (4 * L.g16 + (L.i16 >> 2)) * kTileStride +
+                          F::out_col(nt, L.i16 & 3) * 2);
+}
+
+// X_a X_b^T for two tiles held as TileRows: lane (j, g) gets rows 4g .. 4g+3 (rows of a) of
+// column j (row of b).
+template <class F>
+__device__ __forceinline__ f32x4_t tile_dots(const typename F::TileRows& a,
+                                             const typename F::TileRows& b) {
+  f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) d = F::Elem::mfma16(a.a[ks], b.a[ks], d);
+  return d;
+}
+
+template <class F>
+__global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
+  const Lane L0;
+  const int N = a.N, tile = L0.wave, slice = blockIdx.x;
+  const int n_tiles = (N + TR - 1) / TR;
+  unsigned char* blk = smem + tile * kBlockBytes;
+  int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
+  float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv) + tile * 2 * TR;
+  const bool mine = tile < n_tiles;
+  Raw rq, rk;
+  fetch<false>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  if (mine) {
+    float inv[2];
+    const bool any_key = __ballot(rk.live != 0) != 0;
+    if (any_key) stage<F, kXNormalized, true>(rk, L0, a.eps, blk + kKt, blk + kVt, inv);
+    if (L0.lane == 0) live[tile] = any_key;
+    stage<F, kXRaw, false>(rq, L0, a.eps, blk + kQt, blk + kGt, inv);
+    publish_inv(invs, L0, inv);
+  }
+  __syncthreads();
+  if (!mine) return;
+  const Lane L = L0.again();
+  typename F::TileRows xq;
+  xq.load(blk + kQt, L);
+  f32x4_t out[F::NT];
+#pragma unroll
+  for (int nt = 0; nt < F::NT; ++nt) out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int u = 0; u <= tile; ++u) {
+    if (live[u] == 0) continue;  // no valid key in the tile (uniform)
+    const unsigned char* ub = smem + u * kBlockBytes;
+    typename F::TileRows xk;
+    xk.load(ub + kKt, L);
+    f32x4_t pt = tile_dots<F>(xk, xq);  // [key 4g+v][query i16]
+    if (u == tile) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (4 * L.g16 + v > L.i16) pt[v] = 0.0f;
+    }
+    const typename F::v4_t pb = F::Elem::pack4(pt);
+#pragma unroll
+    for (int nt = 0; nt < F::NT; ++nt)
+      out[nt] = F::Elem::mfma_k16(transposed_rows<F>(ub + kVt, L, nt), pb, out[nt]);
+  }
+  float o[2 * F::EPL];
+  product_rows<F>(out, o);
+  const float factor = invs[L.i16] * (a.scales != nullptr ? a.scales[slice] : a.scale);
+#pragma unroll
+  for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= factor;
+  const int row = tile * TR + L.i16;
+  if (row < N)
+    store_product_row<F, kStoreStreamed>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
+}
+
+template <class F>
+__global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
+  const Lane L0;
+  const int N = a.N, tile = L0.wave, slice = blockIdx.x;
+  const int n_tiles = (N + TR - 1) / TR;
+  unsigned char* blk = smem + tile * kBlockBytes;
+  int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
+  float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv) + tile * 2 * TR;
+  const bool mine = tile < n_tiles;
+  Raw rq, rk;
+  fetch<true>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  if (mine) {
+    float inv[2];
+    stage<F, kXNormalized, true>(rq, L0, a.eps, blk + kQt, blk + kGt, inv);
+    publish_inv(invs, L0, inv);
+    const bool any_key = __ballot(rk.live != 0) != 0;
+    if (any_key) {
+      stage<F, kXNormalized, true>(rk, L0, a.eps, blk + kKt, blk + kVt, inv);
+      publish_inv(invs + TR, L0, inv);
+    }
+    if (L0.lane == 0) live[tile] = any_key;
+  }
+  __syncthreads();
+  if (!mine) return;
+  const Lane L = L0.again();
+  const size_t base = a.st.slice_base(slice, a.H);
+  const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
+  const int row = tile * TR + L.i16;
+
+  {  // as query tile: dQ
+    typename F::TileRows xg;
+    xg.load(blk + kGt, L);
+    f32x4_t acc[F::NT];
+#pragma unroll
+    for (int nt = 0; nt < F::NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u <= tile; ++u) {
+      if (live[u] == 0) continue;
+      const unsigned char* ub = smem + u * kBlockBytes;
+      typename F::TileRows xv;
+      xv.load(ub + kVt, L);
+      f32x4_t gt = tile_dots<F>(xv, xg);  // [key 4g+v][query i16] = v_key . dO_query
+      if (u == tile) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (4 * L.g16 + v > L.i16) gt[v] = 0.0f;
+      }
+      const typename F::v4_t gb = F::Elem::pack4(gt);
+#pragma unroll
+      for (int nt = 0; nt < F::NT; ++nt)
+        acc[nt] = F::Elem::mfma_k16(transposed_rows<F>(ub + kKt, L, nt), gb, acc[nt]);
+    }
+    float g[2 * F::EPL];
+    product_rows<F>(acc, g);
+#pragma unroll
+    for (int i = 0; i < 2 * F::EPL; ++i) g[i] *= scale;
+    typename F::TileRows e;
+    e.load(blk + kQt, L);
+    project_rows<F, false>(g, e, invs[L.i16], L);
+    if (row < N) store_product_row<F, kStoreStreamed>(a.dQ + base, row, a.st.row, L, g);
+  }
+
+  {  // as key tile: dK, dV
+    float dk[2 * F::EPL], dv[2 * F::EPL];
+    if (live[tile] == 0) {
+#pragma unroll
+      for (int i = 0; i < 2 * F::EPL; ++i) dk[i] = dv[i] = 0.0f;
+    } else {
+      typename F::TileRows xk, xv;
+      xk.load(blk + kKt, L);
+      xv.load(blk + kVt, L);
+      f32x4_t av[F::NT], ah[F::NT];
+#pragma unroll
+      for (int nt = 0; nt < F::NT; ++nt) av[nt] = ah[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      for (int t = tile; t < n_tiles; ++t) {
+        const unsigned char* tb = smem + t * kBlockBytes;
+        typename F::TileRows xq, xg;
+        xq.load(tb + kQt, L);
+        xg.load(tb + kGt, L);
+        f32x4_t p = tile_dots<F>(xq, xk);   // [query 4g+v][key i16] = qhat_query . khat_key
+        f32x4_t gg = tile_dots<F>(xg, xv);  // [query 4g+v][key i16] = dO_query . v_key
+        if (t == tile) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (L.i16 > 4 * L.g16 + v) p[v] = gg[v] = 0.0f;
+        }
+        const typename F::v4_t pb = F::Elem::pack4(p), gb = F::Elem::pack4(gg);
+#pragma unroll
+        for (int nt = 0; nt < F::NT; ++nt) {
+          av[nt] = F::Elem::mfma_k16(transposed_rows<F>(tb + kGt, L, nt), pb, av[nt]);
+          ah[nt] = F::Elem::mfma_k16(transposed_rows<F>(tb + kQt, L, nt), gb, ah[nt]);
+        }
+      }
+      product_rows<F>(av, dv);
+      product_rows<F>(ah, dk);
+#pragma unroll
+      for (int i = 0; i < 2 * F::EPL; ++i) {
+        dv[i] *= scale;
+        dk[i] *= scale;
+      }
+      // 1/r is zero on masked rows, whose khat and v rows are zero too: exact zeros there
+      project_rows<F, false>(dk, xk, invs[TR + L.i16], L);
+      if (invs[TR + L.i16] == 0.0f) {
+#pragma unroll
+        for (int i = 0; i < 2 * F::EPL; ++i) dv[i] = 0.0f;
+      }
+    }
+    if (row < N) {
+      store_product_row<F, kStoreStreamed>(a.dK + base, row, a.st.row, L, dk);
+      store_product_row<F, kStoreStreamed>(a.dV + base, row, a.st.row, L, dv);
+    }
+  }
+}
+
 // Persistent workgroups: one per compute unit of the current device (the LDS admits no second
 // one), 256 on MI355X.  Asked once per device.
 int compute_units() {
@@ -424,8 +628,7 @@ int compute_units() {
   return cached[dev];
 }
 
-template <class F>
-hipError_t run(const Problem& p, bool bwd) {
+Args make_args(const Problem& p) {
   Args a{};
   a.Q = static_cast<const unsigned char*>(p.Q);
   a.K = static_cast<const unsigned char*>(p.K);
@@ -446,6 +649,12 @@ hipError_t run(const Problem& p, bool bwd) {
   a.eps = p.eps;
   a.scales = p.slice_scale;
   a.dlog = p.dlog_scale;
+  return a;
+}
+
+template <class F>
+hipError_t run(const Problem& p, bool bwd) {
+  const Args a = make_args(p);
   const int units = compute_units();
   const dim3 grid(static_cast<unsigned>(a.slices < units ? a.slices : units));
   const size_t lds = Lds<F>::kBytes;
@@ -463,8 +672,29 @@ hipError_t run(const Problem& p, bool bwd) {
 
 }  // namespace
 
+template <class F>
+hipError_t run_causal(const Problem& p, bool bwd) {
+  const Args a = make_args(p);
+  const dim3 grid(static_cast<unsigned>(a.slices));
+  const size_t lds = Lds<F>::kBytes;
+  const void* kern = bwd ? reinterpret_cast<const void*>(causal_bwd_kernel<F>)
+                         : reinterpret_cast<const void*>(causal_fwd_kernel<F>);
+  const hipError_t err =
+      hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  if (err != hipSuccess) return err;
+  if (bwd)
+    hipLaunchKernelGGL(causal_bwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  else
+    hipLaunchKernelGGL(causal_fwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
+  return hipGetLastError();
+}
+
 bool resident_supports(int dtype, int D, int N) {
   return (dtype == 1 || dtype == 2) && (D == 64 || D == 32 || D == 16) && N <= kMaxTiles * mfma::TR;
+}
+
+hipError_t launch_resident_causal(const Problem& p, bool bwd) {
+  return p.dtype == 1 ? run_causal<Bf16x64>(p, bwd) : run_causal<F16x64>(p, bwd);
 }
 
 hipError_t launch_resident_fwd(const Problem& p) {
