@@ -57,11 +57,14 @@
  *
  * Workspace.  Long sequences are split over several workgroups per slice; the
  * partial d_h x d_h states travel through a workspace of
- * cotten_attn_workspace_bytes(...) bytes (0 when a shape needs none).  The *_ex
- * entry points take it from cotten_params; when params->workspace is NULL (and
- * for the plain entry points) the library keeps one buffer per device that it
- * allocates with hipMalloc on first need, grows when a larger shape arrives and
- * never frees; calls that share it must be ordered on one stream.
+ * cotten_attn_workspace_bytes(...) bytes (0 when a shape needs none: every
+ * sequence of at most 256 rows, and longer ones when B*H fills the device).  The
+ * library never allocates, frees or synchronises: the caller brings the
+ * workspace through cotten_params (its contents need no initialisation and mean
+ * nothing afterwards; calls that share one must be ordered on one stream).  A
+ * call whose shape needs a workspace and has none - params->workspace NULL, or
+ * one of the plain entry points, which carry no params - returns
+ * COTTEN_ERR_WORKSPACE_TOO_SMALL and enqueues nothing.
  *
  * Errors.  Every entry point returns a cotten_status; 0 is success, negative
  * values are listed below.  Argument validation happens on the host before any
@@ -101,18 +104,19 @@ typedef enum cotten_status {
   COTTEN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* d_h not in {16, 32, 64, 128}                 */
   COTTEN_ERR_BAD_DTYPE = -4,            /* dtype is not a cotten_dtype                  */
   COTTEN_ERR_MISALIGNED = -5,           /* a tensor or workspace pointer not 16-B aligned */
-  COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* params->workspace_bytes below the requirement */
+  COTTEN_ERR_WORKSPACE_TOO_SMALL = -6,  /* the shape needs a workspace and params->workspace is
+                                           NULL or params->workspace_bytes is too small  */
   COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf, or
                                            an option combination that is not available   */
-  COTTEN_ERR_LAUNCH = -8,               /* the HIP runtime refused a launch             */
-  COTTEN_ERR_ALLOC = -9                 /* the library-owned workspace could not grow   */
+  COTTEN_ERR_LAUNCH = -8                /* the HIP runtime refused a launch             */
 } cotten_status;
 
 typedef struct cotten_params {
   int dtype;              /* a cotten_dtype                                             */
   float scale;            /* scalar normaliser s; <= 0 selects the default 1/N          */
   float eps;              /* epsilon inside the square root; < 0 selects 1e-6; 0 allowed */
-  void* workspace;        /* device buffer, 16-byte aligned, or NULL = library-owned    */
+  void* workspace;        /* device buffer, 16-byte aligned; may be NULL when
+                             cotten_attn_workspace_bytes() is 0 for the call            */
   size_t workspace_bytes; /* size of `workspace` (ignored when it is NULL)              */
   const float* slice_scale; /* device, [B*H] floats, or NULL.  When given, slice (b,h) uses
                                slice_scale[b*H+h] (finite, > 0) and `scale` is ignored      */
@@ -127,13 +131,15 @@ typedef struct cotten_params {
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):
- * O = scale * Qhat (Khat^T V) under the key mask.  fp32 I/O, scale = 1/N, eps = 1e-6. */
+ * O = scale * Qhat (Khat^T V) under the key mask.  fp32 I/O, scale = 1/N, eps = 1e-6.
+ * Shapes for which cotten_attn_workspace_bytes() is not 0 need the _ex form. */
 int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
                     void* O, int B, int H, int N, int d_h, void* stream);
 
 /* Backward of the same expression: given dO writes dQ, dK, dV (formulas above).
  * fp32 I/O, scale = 1/N, eps = 1e-6.  The state S is rebuilt from K, V; nothing
- * saved by the forward call is needed. */
+ * saved by the forward call is needed.  Shapes for which
+ * cotten_attn_workspace_bytes() is not 0 need the _ex form. */
 int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
                     const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
                     int d_h, void* stream);

@@ -1,6 +1,7 @@
 """torch.autograd plumbing around the C-ABI binding: forward calls cotten_attn_fwd, backward
 calls cotten_attn_bwd (which rebuilds the d x d state from K, V: nothing but the inputs is
-saved).  No arithmetic here except what autograd itself does with the returned gradients."""
+saved).  The kernels return d loss / d log(scale) per slice; the one piece of arithmetic done
+here, in torch, is its conversion to d loss / d scale (a division by the scale, [B,H] values)."""
 from __future__ import annotations
 
 from typing import Optional

@@ -4,6 +4,11 @@ Argument marshalling only: every arithmetic step runs in the HIP kernels.  torch
 used for device memory (`torch.empty`, `.data_ptr()`) and for the current stream.
 There is no CPU fallback: if the library cannot be loaded, or a tensor is not on
 the GPU, the call raises.
+
+The library allocates nothing.  Shapes that need a workspace (long sequences cut over
+several workgroups) get one from here when the caller passes none: a `torch.empty` buffer
+kept per (device, stream), grown when a larger shape arrives; while a stream is being
+captured into a graph the buffer is a fresh temporary from the graph's own pool instead.
 """
 from __future__ import annotations
 
@@ -161,6 +166,32 @@ def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
     return p
 
 
+_workspaces = {}    # (device index, stream handle) -> uint8 tensor
+_retired = []       # outgrown buffers: work already enqueued may still use them
+
+
+def _workspace(Q: torch.Tensor, dims, is_bwd: bool, stream_handle: int,
+               given: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    """The workspace tensor of a call: the caller's, or one of this module's."""
+    if given is not None:
+        return given
+    B, H, N, d = dims
+    need = cotten_attn_workspace_bytes(B, H, N, d, _dtype_code(Q), is_bwd)
+    if need == 0:
+        return None
+    with torch.cuda.device(Q.device):
+        if torch.cuda.is_current_stream_capturing():
+            return torch.empty(need, dtype=torch.uint8, device=Q.device)
+        key = (Q.device.index, stream_handle)
+        ws = _workspaces.get(key)
+        if ws is None or ws.numel() < need:
+            if ws is not None:
+                _retired.append(ws)
+            ws = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=Q.device)
+            _workspaces[key] = ws
+        return ws
+
+
 def _stream_handle(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -184,11 +215,14 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     if O is None:
         O = torch.empty_like(Q)
     _prep("O", O, Q)
+    handle = _stream_handle(stream)
+    if not causal:
+        workspace = _workspace(Q, (B, H, N, d), False, handle, workspace)
     prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
-                                      B, H, N, d, _stream_handle(stream), ctypes.byref(prm)))
+                                      B, H, N, d, handle, ctypes.byref(prm)))
     return O
 
 
@@ -210,12 +244,15 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     dQ = torch.empty_like(Q) if dQ is None else _prep("dQ", dQ, Q)
     dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
     dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
+    handle = _stream_handle(stream)
+    if not causal:
+        workspace = _workspace(Q, (B, H, N, d), True, handle, workspace)
     prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),
                                       dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                      B, H, N, d, _stream_handle(stream), ctypes.byref(prm)))
+                                      B, H, N, d, handle, ctypes.byref(prm)))
     return dQ, dK, dV
 
 

@@ -2,6 +2,7 @@
 // See include/cotten_attn.h for the contract of every function.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <mutex>
 
@@ -11,7 +12,6 @@
 namespace {
 
 constexpr float kDefaultEps = 1e-6f;
-constexpr int kMaxDevices = 64;
 
 bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -28,39 +28,16 @@ int check_shape(int B, int H, int N, int d_h, int dtype) {
   return COTTEN_OK;
 }
 
-// Library-owned workspace: one buffer per device, grown on demand, never freed.
-struct DeviceWorkspace {
-  void* ptr = nullptr;
-  size_t bytes = 0;
+// Kernels whose dynamic-LDS attribute has been set, and on which devices (bit d = device d).
+// Entries are appended under the mutex and never change place, so readers need no lock.
+struct Granted {
+  std::atomic<const void*> kernel{nullptr};
+  std::atomic<uint64_t> devices{0};
 };
-DeviceWorkspace g_ws[kMaxDevices];
-std::mutex g_ws_mutex;
-
-int own_workspace(size_t need, float** out) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return COTTEN_ERR_ALLOC;
-  std::lock_guard<std::mutex> lock(g_ws_mutex);
-  DeviceWorkspace& w = g_ws[dev];
-  if (w.bytes < need) {
-    // Work already enqueued may still read the old buffer: drain before replacing it.
-    if (w.ptr != nullptr) {
-      if (hipDeviceSynchronize() != hipSuccess) return COTTEN_ERR_ALLOC;
-      (void)hipFree(w.ptr);
-      w.ptr = nullptr;
-      w.bytes = 0;
-    }
-    size_t cap = need < (size_t{1} << 20) ? (size_t{1} << 20) : need;
-    void* p = nullptr;
-    if (hipMalloc(&p, cap) != hipSuccess) {
-      (void)hipGetLastError();
-      return COTTEN_ERR_ALLOC;
-    }
-    w.ptr = p;
-    w.bytes = cap;
-  }
-  *out = static_cast<float*>(w.ptr);
-  return COTTEN_OK;
-}
+constexpr int kMaxGranted = 256;
+Granted g_granted[kMaxGranted];
+std::atomic<int> g_granted_count{0};
+std::mutex g_grant_mutex;
 
 int resolve(const cotten_params* prm, int N, float* scale, float* eps) {
   *scale = prm->scale > 0.0f ? prm->scale : 1.0f / static_cast<float>(N);
@@ -114,7 +91,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
     if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
     p.workspace = static_cast<float*>(prm->workspace);
   } else if (need > 0) {
-    if (int rc = own_workspace(need, &p.workspace)) return rc;
+    return COTTEN_ERR_WORKSPACE_TOO_SMALL;  // the library allocates nothing: the caller brings it
   }
   p.slice_scale = prm->slice_scale;
   p.dlog_scale = bwd ? prm->dlog_scale : nullptr;
@@ -136,6 +113,41 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
 const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr, COTTEN_BHND, 0};
 
 }  // namespace
+
+namespace cotten {
+
+hipError_t grant_dynamic_lds(const void* kernel, int bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t{1} << dev : 0;
+  const int known = g_granted_count.load(std::memory_order_acquire);
+  int slot = -1;
+  for (int i = 0; i < known; ++i)
+    if (g_granted[i].kernel.load(std::memory_order_relaxed) == kernel) {
+      if (g_granted[i].devices.load(std::memory_order_acquire) & bit) return hipSuccess;
+      slot = i;
+      break;
+    }
+  std::lock_guard<std::mutex> lock(g_grant_mutex);
+  const hipError_t err =
+      hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (err != hipSuccess) return err;
+  if (slot < 0) {
+    const int n = g_granted_count.load(std::memory_order_relaxed);
+    for (int i = 0; i < n && slot < 0; ++i)
+      if (g_granted[i].kernel.load(std::memory_order_relaxed) == kernel) slot = i;
+    if (slot < 0 && n < kMaxGranted) {
+      slot = n;
+      g_granted[n].kernel.store(kernel, std::memory_order_relaxed);
+      g_granted_count.store(n + 1, std::memory_order_release);
+    }
+  }
+  // a full table only means the attribute is set again on the next call
+  if (slot >= 0) g_granted[slot].devices.fetch_or(bit, std::memory_order_release);
+  return hipSuccess;
+}
+
+}  // namespace cotten
 
 extern "C" {
 
@@ -198,7 +210,6 @@ const char* cotten_status_string(int status) {
     case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";
     case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite; option combination not available";
     case COTTEN_ERR_LAUNCH: return "HIP kernel launch failed";
-    case COTTEN_ERR_ALLOC: return "could not allocate the library-owned workspace";
     default: return "unknown status";
   }
 }

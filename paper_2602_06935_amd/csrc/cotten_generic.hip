@@ -403,8 +403,7 @@ const float* reduce_generic(const Problem& p, const Plan& plan, int nstates) {
 template <typename Kern>
 hipError_t allow_lds(Kern kern, size_t bytes) {
   if (bytes <= 64 * 1024) return hipSuccess;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+  return grant_dynamic_lds(reinterpret_cast<const void*>(kern), static_cast<int>(bytes));
 }
 
 ElemStrides elem_strides(const Problem& p) {

@@ -51,6 +51,12 @@ struct Plan {
 
 Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd);
 
+// Grants `kernel` `bytes` of dynamic LDS (kernels that use more than 64 KB must be granted it
+// before their first launch).  The attribute is set once per kernel and device: later calls
+// with the same kernel on the same device return at once, without a runtime call.  A kernel
+// is always granted the same size.
+hipError_t grant_dynamic_lds(const void* kernel, int bytes);
+
 // reduced[s][e] = partial[s][0][e] + partial[s][1][e] + ... in split order, for `slices`
 // slices of dd floats each.
 void launch_reduce_states(const float* partial, float* reduced, int splits, int dd, size_t slices,

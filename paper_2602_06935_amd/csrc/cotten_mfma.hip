@@ -22,22 +22,6 @@
 #include "cotten_launch.h"
 #include "cotten_mfma_core.h"
 
-// Optional phase timestamps for tuning builds (-DCOTTEN_TRACE): wave w of workgroup b < 8
-// stores the shader clock at trace point i.  Compiles to nothing otherwise.
-#ifdef COTTEN_TRACE
-__device__ long long cotten_trace_buf[8 * 4 * 16];
-#define COTTEN_TRACE_POINT(i)                                                        \
-  do {                                                                               \
-    if (blockIdx.x < 8 && blockIdx.y == 0 && (threadIdx.x & 63) == 0 && threadIdx.x < 256) \
-      cotten_trace_buf[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
-  } while (0)
-extern "C" int cotten_trace_read(long long* host, int n) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(cotten_trace_buf), n * sizeof(long long)));
-}
-#else
-#define COTTEN_TRACE_POINT(i) do {} while (0)
-#endif
-
 // The implementation is compiled twice: 4 waves per workgroup (every kernel), and 8 waves per
 // workgroup for the short fp32 kernels that keep their tiles in registers (half as many tiles
 // per wave: the chain of a workgroup is that much shorter).

@@ -14,23 +14,6 @@
 #include "cotten_launch.h"
 #include "cotten_mfma_core.h"
 
-// Optional phase timestamps for tuning builds (-DCOTTEN_TRACE), see cotten_mfma.hip.
-#ifdef COTTEN_TRACE
-__device__ long long cotten_rtrace_buf[2 * 16 * 16];
-#define COTTEN_RTRACE(i)                                                                   \
-  do {                                                                                     \
-    if ((blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && (threadIdx.x & 63) == 0)       \
-      cotten_rtrace_buf[((blockIdx.x != 0) * 16 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
-  } while (0)
-extern "C" int cotten_rtrace_read(long long* host, int n) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(cotten_rtrace_buf), n * sizeof(long long)));
-}
-#define COTTEN_RTRACE_IT(i) do { if (iter < 2) COTTEN_RTRACE(8 * iter + (i)); } while (0)
-#else
-#define COTTEN_RTRACE(i) do {} while (0)
-#define COTTEN_RTRACE_IT(i) do {} while (0)
-#endif
-
 namespace cotten {
 namespace {
 
@@ -204,9 +187,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
   //      stage Q and issue the loads of the next slice                               B
   //   3  wave w finishes the O rows of tile w (phase 1 of the next slice may start at once:
   //      it writes only the K, V tiles, which nobody reads any more)
-  COTTEN_RTRACE(0);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
-    COTTEN_RTRACE_IT(1);
     {
       const Lane L = L0.again();
       if (mine) {
@@ -218,9 +199,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       }
       if (iter == 0) fetch<false, 2>(rq, rk, a, L, slice, tile, 0);
     }
-    COTTEN_RTRACE_IT(2);
     __syncthreads();
-    COTTEN_RTRACE_IT(3);
     {
       const Lane L = L0.again();
       constexpr int kB = F::BlockAcc::kBlocks;
@@ -238,9 +217,7 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
         keys = key_rows(a, L, slice + 2 * stride, tile);
       }
     }
-    COTTEN_RTRACE_IT(4);
     __syncthreads();
-    COTTEN_RTRACE_IT(5);
     if (mine) {
       const Lane L = L0.again();
       typename F::TileRows xq;
@@ -258,7 +235,6 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       if (row < N)
         store_product_row<F, kStoreStreamed>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
     }
-    COTTEN_RTRACE_IT(6);
   }
 }
 
@@ -325,7 +301,6 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
 
   int slice = blockIdx.x;
   Raw rq, rk;
-  COTTEN_RTRACE(0);
   // The first slice: only Q and dO are requested at once (every compute unit asks at the same
   // moment, and the first phase needs nothing else); K and V follow when those have arrived
   // and travel while Q, dO are staged and dS is built.
@@ -336,7 +311,6 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
     const size_t base = a.st.slice_base(slice, a.H);
     const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
-    COTTEN_RTRACE_IT(1);
     {
       const Lane L = L0.again();
       if (mine) {
@@ -346,9 +320,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       }
       if (iter == 0) fetch<true, 1>(rq, rk, a, L, slice, tile, first_keys);
     }
-    COTTEN_RTRACE_IT(2);
     __syncthreads();
-    COTTEN_RTRACE_IT(3);
     {
       const Lane L = L0.again();
       if (tile >= kApplyWaves) {
@@ -372,9 +344,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
         keys = key_rows(a, L, slice + 2 * stride, tile);
       }
     }
-    COTTEN_RTRACE_IT(4);
     __syncthreads();
-    COTTEN_RTRACE_IT(5);
     if (tile >= kApplyWaves) {
       // g = dO S^T: contraction over columns of S -> natural image.  With dlog wanted: this
       // block of <sum_j khat_j^T v_j, scale * dS (its image)>
@@ -392,9 +362,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       for (int t = tile >> 1; t < n_tiles; t += kApplyWaves / 2)
         apply_tile<F>(L, kv_kind, t, N, W, live, invs, dst, a.st.row);
     }
-    COTTEN_RTRACE_IT(6);
     __syncthreads();
-    COTTEN_RTRACE_IT(7);
     // d loss / d log(scale) = sum_i dO_i . O_i = <S, scale * dS>, blocks in order
     if (a.dlog != nullptr && threadIdx.x == 0)
       a.dlog[slice] = ((dots[0] + dots[1]) + dots[2]) + dots[3];
@@ -660,8 +628,7 @@ hipError_t run(const Problem& p, bool bwd) {
   const size_t lds = Lds<F>::kBytes;
   const void* kern = bwd ? reinterpret_cast<const void*>(resident_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(resident_fwd_kernel<F>);
-  const hipError_t err =
-      hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  const hipError_t err = grant_dynamic_lds(kern, static_cast<int>(lds));
   if (err != hipSuccess) return err;
   if (bwd)
     hipLaunchKernelGGL(resident_bwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);
@@ -679,8 +646,7 @@ hipError_t run_causal(const Problem& p, bool bwd) {
   const size_t lds = Lds<F>::kBytes;
   const void* kern = bwd ? reinterpret_cast<const void*>(causal_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(causal_fwd_kernel<F>);
-  const hipError_t err =
-      hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  const hipError_t err = grant_dynamic_lds(kern, static_cast<int>(lds));
   if (err != hipSuccess) return err;
   if (bwd)
     hipLaunchKernelGGL(causal_bwd_kernel<F>, grid, dim3(kThreads), lds, p.stream, a);

@@ -23,6 +23,42 @@ def bar_for(dtype: str) -> float:
     return {"f32": FP32_BAR, "bf16": BF16_BAR, "f16": F16_BAR}[dtype]
 
 
+# Finer bounds behind the whole-tensor figure, so that a few bad rows or one bad slice cannot
+# hide in a large tensor: every slice (b,h) on its own stays within the bar, and every row
+# within ROW_FACTOR times the bar.  A row's error is taken relative to its own norm, but not
+# to less than ROW_FLOOR times the root-mean-square row norm of its slice: rows that come
+# out small by cancellation (a gradient nearly parallel to its unit row) carry the absolute
+# rounding error of ordinary rows.
+ROW_FACTOR = 4.0
+ROW_FLOOR = 0.25
+
+
+def check_tensor(name: str, got: np.ndarray, ref: np.ndarray, bar: float) -> dict:
+    """Whole-tensor, per-slice and per-row relative L2 errors of a [B,H,N,d] result against
+    the oracle; asserts all three bounds and returns the figures."""
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape and got.ndim == 4
+    assert np.isfinite(got).all(), f"{name}: non-finite values"
+    diff2 = ((got - ref) ** 2).sum(axis=-1)          # [B,H,N]
+    ref2 = (ref ** 2).sum(axis=-1)
+    whole = float(np.sqrt(diff2.sum() / ref2.sum())) if ref2.sum() > 0 else float(np.sqrt(diff2.sum()))
+    sl_num, sl_den = np.sqrt(diff2.sum(axis=-1)), np.sqrt(ref2.sum(axis=-1))     # [B,H]
+    zero = sl_den == 0
+    assert np.all(sl_num[zero] == 0), f"{name}: a slice that must be zero is not"
+    per_slice = np.where(zero, 0.0, sl_num / np.where(zero, 1.0, sl_den))
+    rms_row = np.sqrt(ref2.mean(axis=-1, keepdims=True))                          # [B,H,1]
+    den = np.maximum(np.sqrt(ref2), ROW_FLOOR * rms_row)
+    per_row = np.where(den > 0, np.sqrt(diff2) / np.where(den > 0, den, 1.0), 0.0)
+    out = {"whole": whole, "slice": float(per_slice.max()), "row": float(per_row.max())}
+    assert whole <= bar, f"{name}: rel L2 {whole:.3e} above {bar:.0e}"
+    worst = np.unravel_index(np.argmax(per_slice), per_slice.shape)
+    assert out["slice"] <= bar, f"{name}: slice {worst} rel L2 {out['slice']:.3e} above {bar:.0e}"
+    worst = np.unravel_index(np.argmax(per_row), per_row.shape)
+    assert out["row"] <= ROW_FACTOR * bar, \
+        f"{name}: row {worst} error {out['row']:.3e} above {ROW_FACTOR * bar:.0e}"
+    return out
+
+
 def to_gpu(x: np.ndarray, dtype: str) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
     if dtype == "bf16":

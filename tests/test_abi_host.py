@@ -32,11 +32,11 @@ def test_exports_every_declared_symbol(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(0, -10, -1):
+    for code in range(0, -9, -1):
         s = binding.cotten_status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 10
+    assert len(seen) == 9
     assert binding.cotten_status_string(-99) == "unknown status"
 
 
@@ -110,6 +110,36 @@ def test_workspace_rules(lib):
         p = binding.CottenParams(binding.COTTEN_BF16, 0.0, -1.0, 0x10004, need)
         assert lib.cotten_attn_bwd_ex(0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000,
                                       16, 4, 4096, 64, None, ctypes.byref(p)) == -5
+
+
+def test_library_never_allocates_a_workspace(lib):
+    """A shape that needs a workspace and comes without one is refused on the host, before any
+    device work: with params->workspace NULL, and through the plain entry points, which have
+    no way to pass one.  (Runs without a GPU: the pointers are never dereferenced.)"""
+    f = binding.cotten_attn_workspace_bytes
+    ptrs = (0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000)
+    for bwd in (False, True):
+        assert f(16, 4, 4096, 64, binding.COTTEN_BF16, bwd) > 0      # cfg5's shape
+        p = binding.CottenParams(binding.COTTEN_BF16, 0.0, -1.0, None, 0)
+        if bwd:
+            assert lib.cotten_attn_bwd_ex(*ptrs, 16, 4, 4096, 64, None, ctypes.byref(p)) == -6
+        else:
+            assert lib.cotten_attn_fwd_ex(*ptrs[:5], 16, 4, 4096, 64, None, ctypes.byref(p)) == -6
+        # the same length in fp32 with d_h = 32 through the plain entry points
+        assert f(16, 4, 4096, 32, binding.COTTEN_F32, bwd) > 0
+    assert lib.cotten_attn_fwd(*ptrs[:5], 16, 4, 4096, 32, None) == -6
+    assert lib.cotten_attn_bwd(*ptrs, 16, 4, 4096, 32, None) == -6
+
+
+def test_sources_hold_no_allocation_or_synchronisation():
+    """The boundary's contract: the library never allocates, frees or synchronises."""
+    csrc = os.path.join(ROOT, "paper_2602_06935_amd", "csrc")
+    banned = re.compile(r"\b(hipMalloc\w*|hipFree\w*|hipDeviceSynchronize|hipStreamSynchronize|"
+                        r"hipHostMalloc|hipExtMallocWithFlags)\b")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        text = re.sub(r"//.*", "", text)
+        assert not banned.search(text), name
 
 
 def test_binding_refuses_cpu_tensors():

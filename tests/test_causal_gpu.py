@@ -9,7 +9,7 @@ import torch
 from paper_2602_06935_amd import binding
 from paper_2602_06935_amd.inputs import round_to_bf16, round_to_f16
 
-from gpu_util import bar_for, rel_l2, to_f64, to_gpu
+from gpu_util import bar_for, check_tensor, rel_l2, to_f64, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,36 @@ def test_causal_parity(oracle, dtype, d, N):
     full = binding.cotten_attn_fwd(tq, tk, tv, tm, scale=0.3)
     torch.cuda.synchronize()
     assert rel_l2(to_f64(O)[:, :, -1], to_f64(full)[:, :, -1]) <= 2 * bar
+
+
+@pytest.mark.parametrize("dtype,d,N", [("bf16", 64, 300), ("f16", 32, 260), ("bf16", 16, 230),
+                                       ("f16", 64, 209), ("f32", 32, 300)])
+def test_causal_16bit_beyond_the_resident_limit(oracle, dtype, d, N):
+    """16-bit sequences of more than 208 rows do not fit the kernels that keep a slice in LDS
+    and run on the chunked scan, like every fp32 shape."""
+    B, H = 4, 2
+    print(f"[causal] long {dtype} d={d} N={N}", flush=True)
+    Q, K, V, dO, mask = _inputs(4500 + N + d, dtype, B, H, N, d)
+    mask[2] = 0                          # a sequence without any valid key
+    mask[3] = 0
+    mask[3, N - 37:] = 1                 # left-padded
+    tq, tk, tv, tg = (to_gpu(x, dtype) for x in (Q, K, V, dO))
+    tm = torch.from_numpy(mask).cuda()
+    O = binding.cotten_attn_fwd(tq, tk, tv, tm, scale=0.2, causal=True)
+    dQ, dK, dV = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, scale=0.2, causal=True)
+    O2 = binding.cotten_attn_fwd(tq, tk, tv, tm, scale=0.2, causal=True)
+    g2 = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, scale=0.2, causal=True)
+    torch.cuda.synchronize()
+    ref_o = oracle.causal_fwd(Q, K, V, mask, scale=0.2)
+    ref_g = oracle.causal_bwd(Q, K, V, dO, mask, scale=0.2)
+    bar = bar_for(dtype)
+    for n, g, r in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), (ref_o, *ref_g)):
+        e = check_tensor(n, to_f64(g), r, bar)
+        print(f"[causal]   {n}: whole {e['whole']:.2e} slice {e['slice']:.2e} row {e['row']:.2e}", flush=True)
+    assert np.all(to_f64(O)[2] == 0.0)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], ref_o.shape)
+    assert np.all(to_f64(dK)[dead] == 0.0) and np.all(to_f64(dV)[dead] == 0.0)
+    assert torch.equal(O, O2) and all(torch.equal(a, c) for a, c in zip((dQ, dK, dV), g2))
 
 
 def test_causal_layout_scales_and_errors(oracle):

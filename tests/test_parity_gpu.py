@@ -8,7 +8,7 @@ import torch
 from paper_2602_06935_amd import binding
 from paper_2602_06935_amd.inputs import WORKLOADS, make_batch, round_to_bf16, round_to_f16
 
-from gpu_util import FP32_BAR, bar_for, gpu_bwd, gpu_fwd, rel_l2, to_f64, to_gpu
+from gpu_util import FP32_BAR, bar_for, check_tensor, gpu_bwd, gpu_fwd, rel_l2, to_f64, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -21,22 +21,24 @@ def _check_batch(oracle, b, fwd=True, bwd=True, label=""):
     w = b.workload
     bar = bar_for(w.dtype)
     errs = {}
+    results = []
     if fwd:
         ref = oracle.fwd_linear(b.Q, b.K, b.V, b.mask, scale=b.scale, eps=b.eps)
         got = gpu_fwd(b.Q, b.K, b.V, b.mask, w.dtype, scale=b.scale, eps=b.eps)
-        errs["O"] = rel_l2(got, ref)
+        results.append(("O", got, ref))
     if bwd:
         refs = oracle.bwd(b.Q, b.K, b.V, b.dO, b.mask, scale=b.scale, eps=b.eps)
         gots = gpu_bwd(b.Q, b.K, b.V, b.dO, b.mask, w.dtype, scale=b.scale, eps=b.eps)
         for n, g, r in zip(("dQ", "dK", "dV"), gots, refs):
-            errs[n] = rel_l2(g, r)
+            results.append((n, g, r))
             if b.mask is not None and n in ("dK", "dV"):
                 dead = np.broadcast_to((b.mask == 0)[:, None, :, None], g.shape)
                 assert np.all(g[dead] == 0.0), f"{n}: masked rows must be exact zeros"
-    _say(f"[parity] {label or w.name} seed={b.seed} shape={b.Q.shape} {w.dtype} "
-         + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
-    for k, v in errs.items():
-        assert v <= bar, f"{k}: rel L2 {v:.3e} above {bar:.0e}"
+    _say(f"[parity] {label or w.name} seed={b.seed} shape={b.Q.shape} {w.dtype}")
+    for n, g, r in results:
+        errs[n] = check_tensor(n, g, r, bar)
+        _say(f"[parity]   {n}: whole {errs[n]['whole']:.2e}  worst slice {errs[n]['slice']:.2e}"
+             f"  worst row {errs[n]['row']:.2e}")
     return errs
 
 
@@ -109,10 +111,10 @@ def _check_case(oracle, Q, K, V, dO, mask, dtype, scale=None, eps=None, label=""
     ref_g = oracle.bwd(Q, K, V, dO, mask, scale=scale, eps=oe)
     got_o = gpu_fwd(Q, K, V, mask, dtype, scale=scale, eps=eps)
     got_g = gpu_bwd(Q, K, V, dO, mask, dtype, scale=scale, eps=eps)
-    errs = [rel_l2(got_o, ref_o)] + [rel_l2(g, r) for g, r in zip(got_g, ref_g)]
-    _say(f"[parity] {label} shape={Q.shape} {dtype} " + " ".join(f"{e:.2e}" for e in errs))
-    assert all(np.isfinite(x).all() for x in (got_o, *got_g))
-    assert max(errs) <= bar, errs
+    _say(f"[parity] {label} shape={Q.shape} {dtype}")
+    for n, g, r in zip(("O", "dQ", "dK", "dV"), (got_o, *got_g), (ref_o, *ref_g)):
+        e = check_tensor(n, g, r, bar)
+        _say(f"[parity]   {n}: whole {e['whole']:.2e}  worst slice {e['slice']:.2e}  worst row {e['row']:.2e}")
     return got_o, got_g
 
 
@@ -325,6 +327,50 @@ def test_long_sequences_with_many_slices(oracle):
     for b in range(B):
         mask[b, N - int(rng.integers(1, N + 1)):] = 1
     _check_case(oracle, Q, K, V, dO, mask, "f32", label="256 slices x 2100 rows")
+
+
+def _mixed_masks(B, N, seed):
+    """Left-padded, right-padded, scattered and island masks in turn; one sequence without any
+    valid key and one with a single valid key."""
+    rng = np.random.default_rng(seed)
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        kind = b % 4
+        if kind == 0:
+            mask[b, N - int(rng.integers(1, N + 1)):] = 1
+        elif kind == 1:
+            mask[b, :int(rng.integers(1, N + 1))] = 1
+        elif kind == 2:
+            mask[b] = rng.random(N) < 0.4
+        else:
+            mask[b, N // 5:N // 4] = 1
+            mask[b, N - 40:N - 3] = 1
+    mask[3] = 0
+    mask[4] = 0
+    mask[4, N // 2] = 1
+    return mask
+
+
+@pytest.mark.parametrize("dtype,B,H,N,d", [("f32", 128, 2, 520, 32), ("bf16", 64, 4, 700, 64),
+                                           ("f16", 64, 4, 700, 64), ("f32", 256, 2, 2100, 32),
+                                           ("bf16", 128, 4, 2100, 64)])
+def test_streaming_forward_with_many_slices(oracle, dtype, B, H, N, d):
+    """More than 256 rows with at least 256 slices (512 beyond 2048 rows): forward and backward
+    both run on the fused streaming kernels that re-read their tiles (one workgroup per slice,
+    tiles not kept in registers, no workspace)."""
+    code = {"f32": binding.COTTEN_F32, "bf16": binding.COTTEN_BF16, "f16": binding.COTTEN_F16}[dtype]
+    assert binding.cotten_attn_workspace_bytes(B, H, N, d, code, False) == 0
+    assert binding.cotten_attn_workspace_bytes(B, H, N, d, code, True) == 0
+    Q, K, V, dO = _case(9800 + N + d, B, H, N, d, dtype)
+    mask = _mixed_masks(B, N, N + d)
+    got_o, got_g = _check_case(oracle, Q, K, V, dO, mask, dtype, label=f"streaming fwd {dtype} {B}x{H}x{N}x{d}")
+    assert np.all(got_o[3] == 0.0)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], got_o.shape)
+    assert np.all(got_g[1][dead] == 0.0) and np.all(got_g[2][dead] == 0.0)
+    # run to run: bit for bit
+    assert np.array_equal(gpu_fwd(Q, K, V, mask, dtype), got_o)
+    for a, c in zip(gpu_bwd(Q, K, V, dO, mask, dtype), got_g):
+        assert np.array_equal(a, c)
 
 
 def test_binding_reports_library_errors():
