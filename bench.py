@@ -8,14 +8,23 @@ events on the launch stream, and the fp64 CPU oracle timed on the host cores.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu]
 
-Successive steps rotate over independent buffer sets whose total size exceeds the
-256 MB memory-side cache twice over, so every step streams from HBM.
+Protocol.  Steps rotate over independent buffer sets whose total size exceeds the 256 MB
+memory-side cache twice over, and the backward of a step works on the buffer set half a
+rotation away from its forward, so nothing a call reads was left in a cache by the call
+before it.  K steps are recorded into one HIP graph (kernel launches only).  After the W
+warm-up steps the graph is replayed untimed for a few tenths of a second (clocks and
+caches settle whatever W is), then replayed `--repeats` times, each replay timed with
+events on the launch stream; the line carries the median replay (ms_per_step = median / K)
+and the 10th / 90th percentiles.  Forward and backward calls are timed the same way on
+their own (K back-to-back launches of one direction).
 """
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -26,18 +35,21 @@ if ROOT not in sys.path:
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # dense, published
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 640 << 20       # rotate over at least this many bytes of tensors
+SETTLE_SECONDS = 0.3           # untimed replays before the timed ones
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=15, help="timed replays of the K-step graph")
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
-    ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every step from Python instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of 64 MiB (reference for HBM byte counters)")
     ap.add_argument("--warm-cache", action="store_true", help="one buffer set only (cache-resident)")
@@ -47,13 +59,15 @@ def parse_args():
 class DeviceBatch:
     """R independent copies of one batch on the GPU (same values, distinct addresses)."""
 
-    def __init__(self, batch, torch, rotate_bytes):
+    def __init__(self, batch, torch, binding, rotate_bytes):
         w = batch.workload
         self.batch = batch
         self.dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         self.esize = 2 if w.dtype == "bf16" else 4
         self.tensor_bytes = batch.Q.size * self.esize
         self.R = max(1, -(-rotate_bytes // (11 * self.tensor_bytes)))
+        if rotate_bytes and self.R % 2:
+            self.R += 1
         host = [torch.from_numpy(x).to(self.dt) for x in (batch.Q, batch.K, batch.V, batch.dO)]
         self.mask = None if batch.mask is None else torch.from_numpy(batch.mask).cuda()
         self.sets = []
@@ -61,36 +75,38 @@ class DeviceBatch:
             q, k, v, g = (h.cuda() for h in host)
             outs = [torch.empty_like(q) for _ in range(4)]     # O, dQ, dK, dV
             self.sets.append((q, k, v, g, *outs))
+        # the caller's workspace (long sequences are cut over several workgroups per slice)
+        code = binding.COTTEN_BF16 if w.dtype == "bf16" else binding.COTTEN_F32
+        N = batch.Q.shape[2]
+        need = max(binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, True),
+                   binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, False))
+        self.workspace = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
         # mask-aware algorithmic bytes (masked K/V rows need not be read)
         f = batch.valid_fraction
         self.bytes_fwd = (2 + 2 * f) * self.tensor_bytes
         self.bytes_bwd = (5 + 2 * f) * self.tensor_bytes
         self.bytes_fwd_dense = 4 * self.tensor_bytes
         self.bytes_bwd_dense = 7 * self.tensor_bytes
-        self.tokens = w.B * batch.Q.shape[2]
+        self.tokens = w.B * N
+        self.valid_tokens = int(batch.lengths.sum())
         # algorithmic flops of the backward call per token-head: S (2 d^2, valid keys only), dS
         # and g (2 d^2 each, every row), dV and h (4 d^2, valid keys only)
-        rows = w.B * w.H * batch.Q.shape[2]
+        rows = w.B * w.H * N
         self.flops_bwd = rows * w.d_h * w.d_h * (4 + 6 * f)
 
 
 def run_steps(db, binding, n, first=0, fwd=True, bwd=True):
     b = db.batch
+    far = db.R // 2
     for i in range(first, first + n):
-        q, k, v, g, O, dQ, dK, dV = db.sets[i % db.R]
         if fwd:
-            binding.cotten_attn_fwd(q, k, v, db.mask, O, scale=b.scale, eps=b.eps)
+            q, k, v, g, O, dQ, dK, dV = db.sets[i % db.R]
+            binding.cotten_attn_fwd(q, k, v, db.mask, O, scale=b.scale, eps=b.eps,
+                                    workspace=db.workspace)
         if bwd:
-            binding.cotten_attn_bwd(q, k, v, db.mask, g, dQ, dK, dV, scale=b.scale, eps=b.eps)
-
-
-def event_ms(torch, fn):
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    fn()
-    e1.record()
-    e1.synchronize()
-    return e0.elapsed_time(e1)
+            q, k, v, g, O, dQ, dK, dV = db.sets[(i + far) % db.R]
+            binding.cotten_attn_bwd(q, k, v, db.mask, g, dQ, dK, dV, scale=b.scale, eps=b.eps,
+                                    workspace=db.workspace)
 
 
 def capture(db, binding, torch, n, first=0, fwd=True, bwd=True):
@@ -101,69 +117,145 @@ def capture(db, binding, torch, n, first=0, fwd=True, bwd=True):
     return g
 
 
-def measure(db, binding, torch, steps, warmup, use_graph=True):
-    """W untimed steps, then exactly K timed steps between two device synchronisations.
-    With use_graph the K steps are replayed from one HIP graph, so the host only pays one
-    launch and the GPU sees the kernels back to back (how a launch-bound loop is deployed)."""
+def timed_replays(torch, fn, repeats, settle_s):
+    """Untimed calls of fn for settle_s seconds (at least two), then `repeats` calls timed one
+    by one with events on the current stream.  Sorted list of milliseconds."""
+    t0 = time.perf_counter()
+    n = 0
+    while n < 2 or time.perf_counter() - t0 < settle_s:
+        fn()
+        torch.cuda.synchronize()
+        n += 1
+    ms = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    return sorted(ms)
+
+
+def pct(sorted_ms, q):
+    return sorted_ms[min(len(sorted_ms) - 1, max(0, int(round(q * (len(sorted_ms) - 1)))))]
+
+
+def measure(db, binding, torch, steps, warmup, repeats, use_graph=True, clocks=False):
     run_steps(db, binding, warmup)
     torch.cuda.synchronize()
     if use_graph:
         g_step = capture(db, binding, torch, steps, first=warmup)
         g_fwd = capture(db, binding, torch, steps, bwd=False)
         g_bwd = capture(db, binding, torch, steps, fwd=False)
-        g_step.replay()                      # untimed: first replay uploads the graph
-        torch.cuda.synchronize()
         step_fn, fwd_fn, bwd_fn = g_step.replay, g_fwd.replay, g_bwd.replay
     else:
         step_fn = lambda: run_steps(db, binding, steps, first=warmup)
         fwd_fn = lambda: run_steps(db, binding, steps, bwd=False)
         bwd_fn = lambda: run_steps(db, binding, steps, fwd=False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    step_fn()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    # per-launch durations: K back-to-back launches of one direction between two events
-    fwd_fn(); bwd_fn()
-    torch.cuda.synchronize()
-    fwd_ms = event_ms(torch, fwd_fn) / steps
-    bwd_ms = event_ms(torch, bwd_fn) / steps
-    ms = wall_ms / steps
-    return {
+    step_ms = timed_replays(torch, step_fn, repeats, SETTLE_SECONDS)
+    fwd_ms = timed_replays(torch, fwd_fn, repeats, SETTLE_SECONDS / 3)
+    bwd_ms = timed_replays(torch, bwd_fn, repeats, SETTLE_SECONDS / 3)
+    ms = pct(step_ms, 0.5) / steps
+    fwd_us = pct(fwd_ms, 0.5) / steps * 1e3
+    bwd_us = pct(bwd_ms, 0.5) / steps * 1e3
+    res = {
         "ms_per_step": ms,
+        "ms_per_step_p10": pct(step_ms, 0.1) / steps,
+        "ms_per_step_p90": pct(step_ms, 0.9) / steps,
         "tokens_per_s": db.tokens / (ms * 1e-3),
-        "fwd_us": fwd_ms * 1e3,
-        "bwd_us": bwd_ms * 1e3,
-        "fwd_gbs": db.bytes_fwd / (fwd_ms * 1e-3) / 1e9,
-        "bwd_gbs": db.bytes_bwd / (bwd_ms * 1e-3) / 1e9,
+        "valid_tokens_per_s": db.valid_tokens / (ms * 1e-3),
+        "fwd_us": fwd_us, "bwd_us": bwd_us,
+        "fwd_us_p10_p90": [pct(fwd_ms, 0.1) / steps * 1e3, pct(fwd_ms, 0.9) / steps * 1e3],
+        "bwd_us_p10_p90": [pct(bwd_ms, 0.1) / steps * 1e3, pct(bwd_ms, 0.9) / steps * 1e3],
+        "fwd_gbs": db.bytes_fwd / (fwd_us * 1e-6) / 1e9,
+        "bwd_gbs": db.bytes_bwd / (bwd_us * 1e-6) / 1e9,
         "step_gbs": (db.bytes_fwd + db.bytes_bwd) / (ms * 1e-3) / 1e9,
         "step_gbs_dense": (db.bytes_fwd_dense + db.bytes_bwd_dense) / (ms * 1e-3) / 1e9,
+        "clocks": None,
     }
+    if clocks:
+        # read the clocks while the GPU is busy with about two seconds of replays
+        n = max(1, int(2000.0 / max(pct(step_ms, 0.5), 1e-3)))
+        for _ in range(n):
+            step_fn()
+        res["clocks"] = read_clocks()
+        torch.cuda.synchronize()
+    return res
 
 
-def measured_traffic(workload, kernel_tags):
-    """HBM bytes per backward call, from the committed rocprofv3 counter summary of this
-    workload: FETCH_SIZE + WRITE_SIZE (scaled by the copy kernel's reading) summed over the
-    kernels of the call, i.e. those whose name contains one of `kernel_tags`.  None when no
-    summary is there."""
-    import glob
-    paths = sorted(glob.glob(os.path.join(ROOT, "profiles", f"*_path_{workload}.txt")))
-    if not paths:
-        return None
-    total, seen = 0.0, 0
-    for line in open(paths[-1]):
-        parts = line.strip().split(",")      # kernel names may contain commas themselves
-        if len(parts) >= 3 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") \
-                and any(t in ",".join(parts[1:-1]) for t in kernel_tags) \
-                and parts[-1].endswith("MB per launch"):
-            total += float(parts[-1].split()[0]) * 1e6
-            seen += 1
-    return int(total) if seen else None
+def read_clocks():
+    """sclk / mclk as rocm-smi reports them at the moment of the call (None if unavailable)."""
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True,
+                             timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        pick = lambda key: next((v for k, v in card.items() if key in k.lower()), None)
+        return {"sclk": pick("sclk"), "mclk": pick("mclk"), "source": "rocm-smi --showclocks, under load"}
+    except Exception as e:                                      # noqa: BLE001
+        return {"sclk": None, "mclk": None, "source": f"rocm-smi unavailable: {type(e).__name__}"}
 
 
-# kernels one backward call launches (resident or fused: one; long sequences: three)
+# kernels one call launches (slice kept in LDS or one workgroup per slice: one kernel; long
+# sequences cut over several workgroups: two forward, three backward)
 BWD_KERNELS = ("resident_bwd_kernel", "fused_bwd_kernel", "split_state_kernel", "split_q_kernel",
                "split_kv_kernel")
+
+
+def profile_figures(workload, kernel_tags):
+    """Figures of the backward call taken from the committed rocprofv3 summary of this workload
+    (profiles/*_<workload>.txt): HBM bytes per call = FETCH_SIZE + WRITE_SIZE scaled by the copy
+    kernel's reading, summed over the call's kernels; matrix-core busy share = the
+    SQ_VALU_MFMA_BUSY_CYCLES-based percentage, time-weighted over the call's kernels."""
+    paths = sorted(glob.glob(os.path.join(ROOT, "profiles", f"*_path_{workload}.txt")))
+    if not paths:
+        return {"traffic": None, "mfma_busy_pct": None, "file": None}
+    total, seen, busy = 0.0, 0, None
+    for line in open(paths[-1]):
+        parts = line.strip().split(",")      # kernel names may contain commas themselves
+        if len(parts) < 3:
+            continue
+        mine = any(t in ",".join(parts[1:-1]) for t in kernel_tags)
+        if parts[0] in ("FETCH_SIZE", "WRITE_SIZE") and mine and parts[-1].endswith("MB per launch"):
+            total += float(parts[-1].split()[0]) * 1e6
+            seen += 1
+        if parts[0] == "MFMA_BUSY" and parts[1] == "backward call":
+            busy = float(parts[-1].split()[0])
+    return {"traffic": int(total) if seen else None, "mfma_busy_pct": busy,
+            "file": os.path.relpath(paths[-1], ROOT)}
+
+
+def roofline_block(w, db, res):
+    prof = profile_figures(w.name, BWD_KERNELS)
+    mfma_tflops = db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12
+    r4 = lambda x: round(x, 4)
+    return {
+        "bound": "hbm",
+        "kernel": "backward call (cotten_attn_bwd)",
+        "achieved": round(res["bwd_gbs"], 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": r4(res["bwd_gbs"] / HBM_PEAK_GBS),
+        "traffic": prof["traffic"],
+        "traffic_source": None if prof["file"] is None else
+            f"{prof['file']} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE; not measured in this run)",
+        "launch_us": round(res["bwd_us"], 2),
+        "launch_us_p10_p90": [round(x, 2) for x in res["bwd_us_p10_p90"]],
+        "algorithmic_bytes_per_launch": int(db.bytes_bwd),
+        "forward": {"achieved": round(res["fwd_gbs"], 1), "frac": r4(res["fwd_gbs"] / HBM_PEAK_GBS),
+                    "launch_us": round(res["fwd_us"], 2),
+                    "launch_us_p10_p90": [round(x, 2) for x in res["fwd_us_p10_p90"]],
+                    "algorithmic_bytes_per_launch": int(db.bytes_fwd)},
+        "step": {"achieved": round(res["step_gbs"], 1), "frac": r4(res["step_gbs"] / HBM_PEAK_GBS),
+                 "achieved_dense_bytes": round(res["step_gbs_dense"], 1),
+                 "separate_calls_frac": r4((db.bytes_fwd + db.bytes_bwd)
+                                           / ((res["fwd_us"] + res["bwd_us"]) * 1e-6) / 1e9 / HBM_PEAK_GBS)},
+        # the contractions run on the matrix cores: algorithmic flops / time against the dense
+        # peak, and the share of SIMD cycles the matrix cores were busy (hardware counter)
+        "matrix_cores": {"achieved": round(mfma_tflops, 2), "peak": MFMA_PEAK_TFLOPS[w.dtype],
+                         "unit": "TFLOP/s", "frac": r4(mfma_tflops / MFMA_PEAK_TFLOPS[w.dtype]),
+                         "busy_pct_counter": prof["mfma_busy_pct"]},
+    }
 
 
 def cpu_baseline(batch, budget_s=12.0):
@@ -210,12 +302,23 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     binding.load_library()
+    graph = not args.no_graph
 
     rot = 0 if args.warm_cache else ROTATE_BYTES
     w = WORKLOADS[args.workload]
     batch = make_batch(args.workload, args.seed)
-    db = DeviceBatch(batch, torch, rot)
-    res = measure(db, binding, torch, args.steps, args.warmup, not args.no_graph)
+    db = DeviceBatch(batch, torch, binding, rot)
+    res = measure(db, binding, torch, args.steps, args.warmup, args.repeats, graph, clocks=True)
+    warm = None
+    if not args.warm_cache and not args.no_others:
+        # the same steps over ONE buffer set: inputs of the 13 MB-per-tensor workloads are then
+        # served by the 256 MB memory-side cache.  Labelled, never the headline.
+        wdb = DeviceBatch(batch, torch, binding, 0)
+        wr = measure(wdb, binding, torch, args.steps, args.warmup, max(5, args.repeats // 3), graph)
+        warm = {"label": "WARM CACHE: one buffer set, repeats served by the memory-side cache",
+                "tokens_per_s": round(wr["tokens_per_s"], 1), "ms_per_step": round(wr["ms_per_step"], 5),
+                "fwd_us": round(wr["fwd_us"], 2), "bwd_us": round(wr["bwd_us"], 2)}
+        del wdb
 
     others = {}
     if not args.no_others:
@@ -223,15 +326,17 @@ def main():
             if name == args.workload:
                 continue
             ob = make_batch(name, args.seed)
-            odb = DeviceBatch(ob, torch, rot)
-            r = measure(odb, binding, torch, max(20, args.steps // 4), max(5, args.warmup // 4), not args.no_graph)
+            ow = WORKLOADS[name]
+            odb = DeviceBatch(ob, torch, binding, rot)
+            r = measure(odb, binding, torch, args.steps, args.warmup, args.repeats, graph)
             others[name] = {
-                "tokens_per_s": round(r["tokens_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 5),
-                "fwd_us": round(r["fwd_us"], 2), "bwd_us": round(r["bwd_us"], 2),
-                "bwd_frac_of_hbm_peak": round(r["bwd_gbs"] / HBM_PEAK_GBS, 4),
-                "fwd_frac_of_hbm_peak": round(r["fwd_gbs"] / HBM_PEAK_GBS, 4),
-                "step_frac_of_hbm_peak": round(r["step_gbs"] / HBM_PEAK_GBS, 4),
+                "workload": f"B={ow.B} H={ow.H} N={ow.N} d_h={ow.d_h} {ow.dtype}",
+                "tokens_per_s": round(r["tokens_per_s"], 1),
+                "valid_tokens_per_s": round(r["valid_tokens_per_s"], 1),
+                "ms_per_step": round(r["ms_per_step"], 5),
+                "ms_per_step_p10_p90": [round(r["ms_per_step_p10"], 5), round(r["ms_per_step_p90"], 5)],
                 "valid_fraction": round(ob.valid_fraction, 4), "buffer_sets": odb.R,
+                "roofline": roofline_block(ow, odb, r),
             }
             del odb, ob
             torch.cuda.empty_cache()
@@ -265,27 +370,14 @@ def main():
             "buffer_sets_rotated": db.R,
             "seed": args.seed,
             "launch": "python per step" if args.no_graph else "one HIP graph of K steps",
+            "timing": f"median of {args.repeats} replays of the K steps after {SETTLE_SECONDS} s of "
+                      "untimed replays; events on the launch stream",
         },
-        "roofline": {
-            "bound": "hbm",
-            "kernel": "backward call (cotten_attn_bwd)",
-            "achieved": round(res["bwd_gbs"], 1),
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": round(res["bwd_gbs"] / HBM_PEAK_GBS, 4),
-            "traffic": measured_traffic(w.name, BWD_KERNELS),
-            "launch_us": round(res["bwd_us"], 2),
-            "algorithmic_bytes_per_launch": int(db.bytes_bwd),
-            "forward": {"achieved": round(res["fwd_gbs"], 1), "frac": round(res["fwd_gbs"] / HBM_PEAK_GBS, 4),
-                        "launch_us": round(res["fwd_us"], 2), "algorithmic_bytes_per_launch": int(db.bytes_fwd)},
-            "step": {"achieved": round(res["step_gbs"], 1), "frac": round(res["step_gbs"] / HBM_PEAK_GBS, 4),
-                     "achieved_dense_bytes": round(res["step_gbs_dense"], 1)},
-            # the contractions run on the matrix cores: how much of their peak the call uses
-            "matrix_cores": {"achieved": round(db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12, 2),
-                             "peak": MFMA_PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
-                             "frac": round(db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12
-                                           / MFMA_PEAK_TFLOPS[w.dtype], 4)},
-        },
+        "ms_per_step_p10_p90": [round(res["ms_per_step_p10"], 5), round(res["ms_per_step_p90"], 5)],
+        "valid_tokens_per_s": round(res["valid_tokens_per_s"], 1),
+        "clocks": res["clocks"],
+        "roofline": roofline_block(w, db, res),
+        "warm_cache": warm,
         "cpu_baseline": cpu,
         "other_workloads": others,
     }

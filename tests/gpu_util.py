@@ -26,11 +26,14 @@ def bar_for(dtype: str) -> float:
 # Finer bounds behind the whole-tensor figure, so that a few bad rows or one bad slice cannot
 # hide in a large tensor: every slice (b,h) on its own stays within the bar, and every row
 # within ROW_FACTOR times the bar.  A row's error is taken relative to its own norm, but not
-# to less than ROW_FLOOR times the root-mean-square row norm of its slice: rows that come
-# out small by cancellation (a gradient nearly parallel to its unit row) carry the absolute
-# rounding error of ordinary rows.
+# to less than ROW_FLOOR times the root-mean-square row norm of its slice, and a slice's
+# relative to its own norm, but not to less than SLICE_FLOOR times the root-mean-square slice
+# norm of the tensor: results that come out small by cancellation (a gradient nearly parallel
+# to its unit row; a one-key slice whose only cosine is near zero) carry the absolute
+# rounding error of ordinary ones.
 ROW_FACTOR = 4.0
 ROW_FLOOR = 0.25
+SLICE_FLOOR = 0.25
 
 
 def check_tensor(name: str, got: np.ndarray, ref: np.ndarray, bar: float) -> dict:
@@ -45,7 +48,8 @@ def check_tensor(name: str, got: np.ndarray, ref: np.ndarray, bar: float) -> dic
     sl_num, sl_den = np.sqrt(diff2.sum(axis=-1)), np.sqrt(ref2.sum(axis=-1))     # [B,H]
     zero = sl_den == 0
     assert np.all(sl_num[zero] == 0), f"{name}: a slice that must be zero is not"
-    per_slice = np.where(zero, 0.0, sl_num / np.where(zero, 1.0, sl_den))
+    sl_floor = SLICE_FLOOR * float(np.sqrt((sl_den ** 2).mean()))
+    per_slice = np.where(zero, 0.0, sl_num / np.maximum(np.where(zero, 1.0, sl_den), sl_floor))
     rms_row = np.sqrt(ref2.mean(axis=-1, keepdims=True))                          # [B,H,1]
     den = np.maximum(np.sqrt(ref2), ROW_FLOOR * rms_row)
     per_row = np.where(den > 0, np.sqrt(diff2) / np.where(den > 0, den, 1.0), 0.0)
