@@ -31,9 +31,13 @@ def bar_for(dtype: str) -> float:
 # norm of the tensor: results that come out small by cancellation (a gradient nearly parallel
 # to its unit row; a one-key slice whose only cosine is near zero) carry the absolute
 # rounding error of ordinary ones.
+# Sequences of fewer than SHORT_ROWS rows consist of so few cosines that a whole slice can
+# cancel (N = 1: O is one cosine times v): their slices are held to the row bound and their
+# rows are floored by the root-mean-square row norm of the whole tensor.
 ROW_FACTOR = 4.0
 ROW_FLOOR = 0.25
 SLICE_FLOOR = 0.25
+SHORT_ROWS = 8
 
 
 def check_tensor(name: str, got: np.ndarray, ref: np.ndarray, bar: float) -> dict:
@@ -50,13 +54,18 @@ def check_tensor(name: str, got: np.ndarray, ref: np.ndarray, bar: float) -> dic
     assert np.all(sl_num[zero] == 0), f"{name}: a slice that must be zero is not"
     sl_floor = SLICE_FLOOR * float(np.sqrt((sl_den ** 2).mean()))
     per_slice = np.where(zero, 0.0, sl_num / np.maximum(np.where(zero, 1.0, sl_den), sl_floor))
-    rms_row = np.sqrt(ref2.mean(axis=-1, keepdims=True))                          # [B,H,1]
+    if got.shape[2] >= SHORT_ROWS:
+        rms_row = np.sqrt(ref2.mean(axis=-1, keepdims=True))                      # [B,H,1]
+    else:
+        rms_row = np.sqrt(ref2.mean())
     den = np.maximum(np.sqrt(ref2), ROW_FLOOR * rms_row)
     per_row = np.where(den > 0, np.sqrt(diff2) / np.where(den > 0, den, 1.0), 0.0)
     out = {"whole": whole, "slice": float(per_slice.max()), "row": float(per_row.max())}
     assert whole <= bar, f"{name}: rel L2 {whole:.3e} above {bar:.0e}"
     worst = np.unravel_index(np.argmax(per_slice), per_slice.shape)
-    assert out["slice"] <= bar, f"{name}: slice {worst} rel L2 {out['slice']:.3e} above {bar:.0e}"
+    slice_bar = bar if got.shape[2] >= SHORT_ROWS else ROW_FACTOR * bar
+    assert out["slice"] <= slice_bar, \
+        f"{name}: slice {worst} rel L2 {out['slice']:.3e} above {slice_bar:.0e}"
     worst = np.unravel_index(np.argmax(per_row), per_row.shape)
     assert out["row"] <= ROW_FACTOR * bar, \
         f"{name}: row {worst} error {out['row']:.3e} above {ROW_FACTOR * bar:.0e}"
