@@ -108,7 +108,10 @@ typedef enum cotten_status {
                                            NULL or params->workspace_bytes is too small  */
   COTTEN_ERR_BAD_PARAM = -7,            /* params->scale or params->eps is NaN or Inf, or
                                            an option combination that is not available   */
-  COTTEN_ERR_LAUNCH = -8                /* the HIP runtime refused a launch             */
+  COTTEN_ERR_LAUNCH = -8,               /* the HIP runtime refused a launch             */
+  COTTEN_ERR_STATIC_SCRATCH = -9        /* cotten_attn_bwd_static only: the call needs more than
+                                           COTTEN_STATIC_SCRATCH_BYTES of scratch, or the
+                                           address of the scratch array could not be obtained */
 } cotten_status;
 
 typedef struct cotten_params {
@@ -152,6 +155,25 @@ int cotten_attn_fwd_ex(const void* Q, const void* K, const void* V, const uint8_
 int cotten_attn_bwd_ex(const void* Q, const void* K, const void* V, const uint8_t* mask,
                        const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
                        int d_h, void* stream, const cotten_params* params);
+
+/* For callers that cannot allocate device memory and so cannot bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * operation, arguments and results (bit for bit) as cotten_attn_bwd_ex, except that the
+ * partial states of long sequences go through a scratch array that is part of the library
+ * image (a file-scope __device__ array of COTTEN_STATIC_SCRATCH_BYTES bytes; every GPU the
+ * library runs on holds its own copy until the process ends) instead of params->workspace,
+ * which is ignored together with params->workspace_bytes.  The call allocates, frees and
+ * synchronises nothing.  A call that needs more scratch than the array holds
+ * (cotten_attn_workspace_bytes(..., is_bwd = 1) > COTTEN_STATIC_SCRATCH_BYTES) returns
+ * COTTEN_ERR_STATIC_SCRATCH and enqueues nothing; 32 MiB covers, for instance, 64 slices of
+ * 4096 rows at d_h = 64 (16 MiB) and every shape that needs no workspace at all.  All calls on
+ * one GPU share that GPU's array, which keeps the last call's contents (every element a
+ * call reads it has written before, so nothing needs clearing): calls on the same GPU must be
+ * ordered on one stream; calls that overlap on one GPU race. */
+#define COTTEN_STATIC_SCRATCH_BYTES (32u << 20)
+int cotten_attn_bwd_static(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                           const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
+                           int d_h, void* stream, const cotten_params* params);
 
 /* Learnable normaliser 1/n^m of the scaled CosineAttention ("Model Description"), one
  * exponent per head:  slice_scale[b*H+h] = n_b^(-m_h).  m: device, [H] floats.  n: device,

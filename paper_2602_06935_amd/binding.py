@@ -30,7 +30,7 @@ COTTEN_BNHD = 1
 EXPORTS = (
     "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
     "cotten_attn_workspace_bytes", "cotten_status_string",
-    "cotten_normaliser_fwd", "cotten_normaliser_bwd",
+    "cotten_normaliser_fwd", "cotten_normaliser_bwd", "cotten_attn_bwd_static",
 )
 
 
@@ -66,7 +66,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.cotten_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
     lib.cotten_attn_fwd_ex.argtypes = lib.cotten_attn_fwd.argtypes + [ctypes.POINTER(CottenParams)]
     lib.cotten_attn_bwd_ex.argtypes = lib.cotten_attn_bwd.argtypes + [ctypes.POINTER(CottenParams)]
-    for f in (lib.cotten_attn_fwd, lib.cotten_attn_bwd, lib.cotten_attn_fwd_ex, lib.cotten_attn_bwd_ex):
+    lib.cotten_attn_bwd_static.argtypes = lib.cotten_attn_bwd_ex.argtypes
+    for f in (lib.cotten_attn_fwd, lib.cotten_attn_bwd, lib.cotten_attn_fwd_ex, lib.cotten_attn_bwd_ex,
+              lib.cotten_attn_bwd_static):
         f.restype = ctypes.c_int
     lib.cotten_attn_workspace_bytes.argtypes = [ip, ip, ip, ip, ip, ip]
     lib.cotten_attn_workspace_bytes.restype = ctypes.c_size_t
@@ -234,10 +236,13 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
                     dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
-                    causal: bool = False) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+                    causal: bool = False,
+                    static_scratch: bool = False) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
     `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
-    d loss / d log(scale) of every slice."""
+    d loss / d log(scale) of every slice.  With `static_scratch` the call goes to
+    cotten_attn_bwd_static: no workspace is passed or allocated, the library's own static
+    scratch array serves (the output tensors must then be given, nothing is allocated here)."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q); dO = _prep("dO", dO, Q)
     B, H, N, d = _dims(Q, layout)
@@ -245,14 +250,17 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     dK = torch.empty_like(Q) if dK is None else _prep("dK", dK, Q)
     dV = torch.empty_like(Q) if dV is None else _prep("dV", dV, Q)
     handle = _stream_handle(stream)
-    if not causal:
+    if static_scratch:
+        workspace = None
+    elif not causal:
         workspace = _workspace(Q, (B, H, N, d), True, handle, workspace)
     prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal)
+    entry = lib.cotten_attn_bwd_static if static_scratch else lib.cotten_attn_bwd_ex
     with torch.cuda.device(Q.device):
-        _check(lib.cotten_attn_bwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
-                                      _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),
-                                      dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                      B, H, N, d, handle, ctypes.byref(prm)))
+        _check(entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                     _mask_ptr(mask, B, N, Q.device), dO.data_ptr(),
+                     dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                     B, H, N, d, handle, ctypes.byref(prm)))
     return dQ, dK, dV
 
 

@@ -39,6 +39,34 @@ Granted g_granted[kMaxGranted];
 std::atomic<int> g_granted_count{0};
 std::mutex g_grant_mutex;
 
+// Scratch of cotten_attn_bwd_static: the partial states of the split path, for callers that
+// cannot bring a workspace.  One copy per GPU the library runs on, held until the process ends.
+// In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[COTTEN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (nullptr on failure).
+void* static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p != nullptr) return p;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+  if (p != nullptr) return p;
+  void* addr = nullptr;
+  if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || addr == nullptr) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(addr, std::memory_order_release);
+  return addr;
+}
+
 int resolve(const cotten_params* prm, int N, float* scale, float* eps) {
   *scale = prm->scale > 0.0f ? prm->scale : 1.0f / static_cast<float>(N);
   *eps = prm->eps < 0.0f ? kDefaultEps : prm->eps;
@@ -48,13 +76,14 @@ int resolve(const cotten_params* prm, int N, float* scale, float* eps) {
 
 int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* mask,
         const void* dO, void* O, void* dQ, void* dK, void* dV, int B, int H, int N, int d_h,
-        void* stream, const cotten_params* prm) {
+        void* stream, const cotten_params* prm, bool use_static_scratch = false) {
   if (prm == nullptr) return COTTEN_ERR_NULL_POINTER;
   if (Q == nullptr || K == nullptr || V == nullptr) return COTTEN_ERR_NULL_POINTER;
   if (bwd ? (dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr) : (O == nullptr))
     return COTTEN_ERR_NULL_POINTER;
   if (int rc = check_shape(B, H, N, d_h, prm->dtype)) return rc;
-  const void* tensors[8] = {Q, K, V, bwd ? dO : O, dQ, dK, dV, prm->workspace};
+  const void* tensors[8] = {Q, K, V, bwd ? dO : O, dQ, dK, dV,
+                            use_static_scratch ? nullptr : prm->workspace};
   for (const void* t : tensors)
     if (t != nullptr && !aligned16(t)) return COTTEN_ERR_MISALIGNED;
 
@@ -87,7 +116,13 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   }
   const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
   const size_t need = plan.workspace_floats * sizeof(float);
-  if (prm->workspace != nullptr) {
+  if (use_static_scratch) {
+    if (need > COTTEN_STATIC_SCRATCH_BYTES) return COTTEN_ERR_STATIC_SCRATCH;
+    if (need > 0) {
+      p.workspace = static_cast<float*>(static_scratch());
+      if (p.workspace == nullptr) return COTTEN_ERR_STATIC_SCRATCH;
+    }
+  } else if (prm->workspace != nullptr) {
     if (prm->workspace_bytes < need) return COTTEN_ERR_WORKSPACE_TOO_SMALL;
     p.workspace = static_cast<float*>(prm->workspace);
   } else if (need > 0) {
@@ -163,6 +198,12 @@ int cotten_attn_bwd_ex(const void* Q, const void* K, const void* V, const uint8_
   return run(true, Q, K, V, mask, dO, nullptr, dQ, dK, dV, B, H, N, d_h, stream, params);
 }
 
+int cotten_attn_bwd_static(const void* Q, const void* K, const void* V, const uint8_t* mask,
+                           const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
+                           int d_h, void* stream, const cotten_params* params) {
+  return run(true, Q, K, V, mask, dO, nullptr, dQ, dK, dV, B, H, N, d_h, stream, params, true);
+}
+
 int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* mask, void* O,
                     int B, int H, int N, int d_h, void* stream) {
   return cotten_attn_fwd_ex(Q, K, V, mask, O, B, H, N, d_h, stream, &kDefaults);
@@ -210,6 +251,9 @@ const char* cotten_status_string(int status) {
     case COTTEN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than cotten_attn_workspace_bytes()";
     case COTTEN_ERR_BAD_PARAM: return "scale and eps must be finite; option combination not available";
     case COTTEN_ERR_LAUNCH: return "HIP kernel launch failed";
+    case COTTEN_ERR_STATIC_SCRATCH:
+      return "the call needs more scratch than COTTEN_STATIC_SCRATCH_BYTES (use cotten_attn_bwd_ex "
+             "with a workspace), or the scratch array's address could not be obtained";
     default: return "unknown status";
   }
 }

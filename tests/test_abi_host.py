@@ -32,11 +32,11 @@ def test_exports_every_declared_symbol(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         s = binding.cotten_status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert binding.cotten_status_string(-99) == "unknown status"
 
 
@@ -129,6 +129,18 @@ def test_library_never_allocates_a_workspace(lib):
         assert f(16, 4, 4096, 32, binding.COTTEN_F32, bwd) > 0
     assert lib.cotten_attn_fwd(*ptrs[:5], 16, 4, 4096, 32, None) == -6
     assert lib.cotten_attn_bwd(*ptrs, 16, 4, 4096, 32, None) == -6
+
+
+def test_static_scratch_entry_point_checks_on_the_host(lib):
+    """cotten_attn_bwd_static validates like cotten_attn_bwd_ex and refuses, before any device
+    work, a call whose partial states do not fit its static scratch array."""
+    ptrs = (0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000)
+    p = binding.CottenParams(binding.COTTEN_BF16, 0.0, -1.0, None, 0)
+    assert lib.cotten_attn_bwd_static(*ptrs, 2, 2, 64, 48, None, ctypes.byref(p)) == -3
+    assert lib.cotten_attn_bwd_static(*ptrs, 0, 2, 64, 64, None, ctypes.byref(p)) == -2
+    assert lib.cotten_attn_bwd_static(*ptrs, 2, 2, 64, 64, None, None) == -1
+    assert binding.cotten_attn_workspace_bytes(1, 200, 50000, 64, binding.COTTEN_BF16, True) > (32 << 20)
+    assert lib.cotten_attn_bwd_static(*ptrs, 1, 200, 50000, 64, None, ctypes.byref(p)) == -9
 
 
 def test_sources_hold_no_allocation_or_synchronisation():
