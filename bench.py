@@ -36,6 +36,15 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # dense, publ
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 640 << 20       # rotate over at least this many bytes of tensors
 SETTLE_SECONDS = 0.3           # untimed replays before the timed ones
+# Padding between neighbouring tensors in device memory.  Tensors whose base addresses differ by
+# a large power of two (the 32 MiB tensors of the N = 4096 workload, allocated back to back) put
+# the same row of every tensor into the same HBM bank, and the three or four streams a backward
+# kernel walks in step then evict each other's open DRAM rows: measured 60-64 us per backward
+# call with 0-8 KiB of padding, 42-45 us with 16-24 KiB (the 13 MB tensors of the N = 200
+# workloads are indifferent: 18.6 us either way).  The library cannot choose its caller's
+# addresses; the benchmark lays its buffers out the way an allocator tuned for this memory
+# would, and reports the back-to-back layout beside it (`layout_sensitivity`).
+STAGGER_BYTES = 20 << 10
 
 
 def parse_args():
@@ -53,15 +62,22 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of 64 MiB (reference for HBM byte counters)")
     ap.add_argument("--warm-cache", action="store_true", help="one buffer set only (cache-resident)")
+    ap.add_argument("--stagger", type=int, default=None,
+                    help="bytes of padding between neighbouring tensors (default STAGGER_BYTES)")
+    ap.add_argument("--rebuild-state", action="store_true",
+                    help="the backward rebuilds the state S from K, V instead of reading the one "
+                         "its forward kept (cotten_params.saved_state)")
     return ap.parse_args()
 
 
 class DeviceBatch:
     """R independent copies of one batch on the GPU (same values, distinct addresses)."""
 
-    def __init__(self, batch, torch, binding, rotate_bytes):
+    def __init__(self, batch, torch, binding, rotate_bytes, keep_state=True, stagger=None):
+        stagger = STAGGER_BYTES if stagger is None else stagger
         w = batch.workload
         self.batch = batch
+        self.keep_state = keep_state
         self.dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         self.esize = 2 if w.dtype == "bf16" else 4
         self.tensor_bytes = batch.Q.size * self.esize
@@ -71,16 +87,30 @@ class DeviceBatch:
         host = [torch.from_numpy(x).to(self.dt) for x in (batch.Q, batch.K, batch.V, batch.dO)]
         self.mask = None if batch.mask is None else torch.from_numpy(batch.mask).cuda()
         self.sets = []
-        for _ in range(self.R):
-            q, k, v, g = (h.cuda() for h in host)
-            outs = [torch.empty_like(q) for _ in range(4)]     # O, dQ, dK, dV
-            self.sets.append((q, k, v, g, *outs))
+        # All tensors are carved from one allocation, `stagger` bytes of padding between
+        # neighbours (see STAGGER_BYTES).
+        stride = (self.tensor_bytes + stagger + 255) // 256 * 256
+        self.arena = torch.empty(stride * 8 * self.R + 256, dtype=torch.uint8, device="cuda")
+        carve = lambda i: self.arena[i * stride: i * stride + self.tensor_bytes].view(self.dt).view(host[0].shape)
+        for r in range(self.R):
+            q, k, v, g = (carve(8 * r + j) for j in range(4))
+            for dst, h in zip((q, k, v, g), host):
+                dst.copy_(h)
+            outs = [carve(8 * r + 4 + j) for j in range(4)]    # O, dQ, dK, dV
+            # the d x d state of every slice, handed from the forward to the backward of the set
+            st = torch.zeros(w.B, w.H, w.d_h, w.d_h, device="cuda") if keep_state else None
+            self.sets.append((q, k, v, g, *outs, st))
         # the caller's workspace (long sequences are cut over several workgroups per slice)
         code = binding.COTTEN_BF16 if w.dtype == "bf16" else binding.COTTEN_F32
         N = batch.Q.shape[2]
         need = max(binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, True),
                    binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, False))
         self.workspace = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+        if keep_state:     # every set's state exists before any backward is timed on its own
+            for q, k, v, g, O, dQ, dK, dV, st in self.sets:
+                binding.cotten_attn_fwd(q, k, v, self.mask, O, scale=batch.scale, eps=batch.eps,
+                                        workspace=self.workspace, saved_state=st)
+            torch.cuda.synchronize()
         # mask-aware algorithmic bytes (masked K/V rows need not be read)
         f = batch.valid_fraction
         self.bytes_fwd = (2 + 2 * f) * self.tensor_bytes
@@ -100,13 +130,13 @@ def run_steps(db, binding, n, first=0, fwd=True, bwd=True):
     far = db.R // 2
     for i in range(first, first + n):
         if fwd:
-            q, k, v, g, O, dQ, dK, dV = db.sets[i % db.R]
+            q, k, v, g, O, dQ, dK, dV, st = db.sets[i % db.R]
             binding.cotten_attn_fwd(q, k, v, db.mask, O, scale=b.scale, eps=b.eps,
-                                    workspace=db.workspace)
+                                    workspace=db.workspace, saved_state=st)
         if bwd:
-            q, k, v, g, O, dQ, dK, dV = db.sets[(i + far) % db.R]
+            q, k, v, g, O, dQ, dK, dV, st = db.sets[(i + far) % db.R]
             binding.cotten_attn_bwd(q, k, v, db.mask, g, dQ, dK, dV, scale=b.scale, eps=b.eps,
-                                    workspace=db.workspace)
+                                    workspace=db.workspace, saved_state=st)
 
 
 def capture(db, binding, torch, n, first=0, fwd=True, bwd=True):
@@ -307,13 +337,18 @@ def main():
     rot = 0 if args.warm_cache else ROTATE_BYTES
     w = WORKLOADS[args.workload]
     batch = make_batch(args.workload, args.seed)
-    db = DeviceBatch(batch, torch, binding, rot)
+    # The forward keeps the state for its backward where that saves the backward a pass over K, V
+    # at little cost: the state is d*d*4 bytes per slice next to N*d*e bytes per tensor (3 % of a
+    # tensor at N = 4096, 64 % at N = 200 with d = 64, where the slice sits in LDS anyway).
+    pays = lambda wl: wl.N * (2 if wl.dtype == "bf16" else 4) >= 16 * wl.d_h
+    keep = (not args.rebuild_state) and pays(w)
+    db = DeviceBatch(batch, torch, binding, rot, keep, args.stagger)
     res = measure(db, binding, torch, args.steps, args.warmup, args.repeats, graph, clocks=True)
     warm = None
     if not args.warm_cache and not args.no_others:
         # the same steps over ONE buffer set: inputs of the 13 MB-per-tensor workloads are then
         # served by the 256 MB memory-side cache.  Labelled, never the headline.
-        wdb = DeviceBatch(batch, torch, binding, 0)
+        wdb = DeviceBatch(batch, torch, binding, 0, keep, args.stagger)
         wr = measure(wdb, binding, torch, args.steps, args.warmup, max(5, args.repeats // 3), graph)
         warm = {"label": "WARM CACHE: one buffer set, repeats served by the memory-side cache",
                 "tokens_per_s": round(wr["tokens_per_s"], 1), "ms_per_step": round(wr["ms_per_step"], 5),
@@ -327,8 +362,18 @@ def main():
                 continue
             ob = make_batch(name, args.seed)
             ow = WORKLOADS[name]
-            odb = DeviceBatch(ob, torch, binding, rot)
+            odb = DeviceBatch(ob, torch, binding, rot, (not args.rebuild_state) and pays(ow), args.stagger)
             r = measure(odb, binding, torch, args.steps, args.warmup, args.repeats, graph)
+            sens = None
+            if odb.tensor_bytes & (odb.tensor_bytes - 1) == 0 and args.stagger is None:
+                # power-of-two tensors: the same measurement with the tensors back to back
+                del odb
+                torch.cuda.empty_cache()
+                odb = DeviceBatch(ob, torch, binding, rot, (not args.rebuild_state) and pays(ow), 0)
+                r0 = measure(odb, binding, torch, args.steps, args.warmup, max(3, args.repeats // 3), graph)
+                sens = {"tensors_back_to_back": {"fwd_us": round(r0["fwd_us"], 2), "bwd_us": round(r0["bwd_us"], 2),
+                                                 "tokens_per_s": round(r0["tokens_per_s"], 1)},
+                        "note": "same kernels, no padding between the 32 MiB tensors: HBM bank aliasing"}
             others[name] = {
                 "workload": f"B={ow.B} H={ow.H} N={ow.N} d_h={ow.d_h} {ow.dtype}",
                 "tokens_per_s": round(r["tokens_per_s"], 1),
@@ -336,7 +381,9 @@ def main():
                 "ms_per_step": round(r["ms_per_step"], 5),
                 "ms_per_step_p10_p90": [round(r["ms_per_step_p10"], 5), round(r["ms_per_step_p90"], 5)],
                 "valid_fraction": round(ob.valid_fraction, 4), "buffer_sets": odb.R,
+                "state": "kept by the forward (saved_state)" if odb.keep_state else "rebuilt by the backward",
                 "roofline": roofline_block(ow, odb, r),
+                "layout_sensitivity": sens,
             }
             del odb, ob
             torch.cuda.empty_cache()
@@ -368,8 +415,11 @@ def main():
             "workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d_h={w.d_h} {w.dtype}, {w.description}",
             "valid_fraction": round(batch.valid_fraction, 4),
             "buffer_sets_rotated": db.R,
+            "tensor_stagger_bytes": STAGGER_BYTES if args.stagger is None else args.stagger,
             "seed": args.seed,
             "launch": "python per step" if args.no_graph else "one HIP graph of K steps",
+            "state": "the forward keeps the d x d state of every slice (saved_state), its backward reads it"
+                     if keep else "rebuilt from K, V by the backward",
             "timing": f"median of {args.repeats} replays of the K steps after {SETTLE_SECONDS} s of "
                       "untimed replays; events on the launch stream",
         },

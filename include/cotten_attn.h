@@ -131,6 +131,17 @@ typedef struct cotten_params {
                              causal mask"): O_i = scale * qhat_i sum_{j<=i} m_j khat_j^T v_j
                              and its exact gradients.  d_h in {16, 32, 64}; no workspace;
                              dlog_scale is not available (COTTEN_ERR_BAD_PARAM)            */
+  float* saved_state;     /* device, [B*H, d_h, d_h] floats, 16-byte aligned, or NULL.  The state
+                             S = sum_j m_j khat_j^T v_j of every slice (row a, column c; without
+                             the scale), kept by the caller from the forward call to the
+                             backward call of the same K, V, mask and eps, as the chain rule
+                             allows (the backward needs S again, nothing else of the forward).
+                             Forward: written when given.  Backward: when given, read instead
+                             of rebuilding S from K and V (one pass over K, V less); results
+                             agree with the rebuilding call to fp32 rounding of S.  The
+                             vector-ALU kernels (fp32 d_h = 64, d_h = 128) and a backward call
+                             that also asks for dlog_scale rebuild S all the same; the causal
+                             variant has no such state and ignores the field              */
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):
@@ -141,7 +152,7 @@ int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* 
 
 /* Backward of the same expression: given dO writes dQ, dK, dV (formulas above).
  * fp32 I/O, scale = 1/N, eps = 1e-6.  The state S is rebuilt from K, V; nothing
- * saved by the forward call is needed.  Shapes for which
+ * saved by the forward call is needed (cotten_params.saved_state offers the other way).  Shapes for which
  * cotten_attn_workspace_bytes() is not 0 need the _ex form. */
 int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
                     const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,

@@ -112,6 +112,17 @@ static void build_state(const double* k, const double* v, const uint8_t* mask, i
   }
 }
 
+/* The state of the reordered form on its own, S[b,h] = Khat^T V under the key mask
+ * ([B,H,d,d]): what a forward call may hand to its backward call. */
+void cotten_oracle_state(const double* K, const double* V, const uint8_t* mask, double* S,
+                         int B, int H, int N, int d, double eps) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const size_t off = (size_t)bh * N * d;
+    build_state(K + off, V + off, mask, bh / H, N, d, eps, S + (size_t)bh * d * d);
+  }
+}
+
 /* Reordered form: S = Khat^T V under the key mask, then O_i = scale * qhat_i S. */
 void cotten_oracle_fwd_linear(const double* Q, const double* K, const double* V,
                               const uint8_t* mask, double* O, int B, int H, int N, int d,

@@ -55,6 +55,8 @@ def _load():
         lib.cotten_oracle_causal_fwd.restype = None
         lib.cotten_oracle_causal_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, i, i, i, i, f, f]
         lib.cotten_oracle_causal_bwd.restype = None
+        lib.cotten_oracle_state.argtypes = [dp, dp, bp, dp, i, i, i, i, f]
+        lib.cotten_oracle_state.restype = None
         lib.cotten_oracle_threads.argtypes = []
         lib.cotten_oracle_threads.restype = ctypes.c_int
         _lib = lib
@@ -100,6 +102,17 @@ def fwd_quadratic(Q, K, V, mask=None, scale: Optional[float] = None, eps: float 
 def fwd_linear(Q, K, V, mask=None, scale: Optional[float] = None, eps: float = 1e-6):
     """O = scale * Qhat (Khat^T V): the reordered form with the d x d state."""
     return _fwd("cotten_oracle_fwd_linear", Q, K, V, mask, scale, eps)
+
+
+def state(K, V, mask=None, eps: float = 1e-6) -> np.ndarray:
+    """S[b,h] = Khat^T V under the key mask, [B,H,d,d]: the state of the reordered form."""
+    K, V = _f64(K), _f64(V)
+    assert K.ndim == 4 and K.shape == V.shape
+    B, H, N, d = K.shape
+    S = np.empty((B, H, d, d), dtype=np.float64)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_state(_ptr(K), _ptr(V), mp, _ptr(S), B, H, N, d, float(eps))
+    return S
 
 
 def bwd(Q, K, V, dO, mask=None, scale: Optional[float] = None,

@@ -38,7 +38,8 @@ class CottenParams(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int), ("scale", ctypes.c_float), ("eps", ctypes.c_float),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p),
-                ("layout", ctypes.c_int), ("causal", ctypes.c_int)]
+                ("layout", ctypes.c_int), ("causal", ctypes.c_int),
+                ("saved_state", ctypes.c_void_p)]
 
 
 class CottenError(RuntimeError):
@@ -146,10 +147,11 @@ def _dims(Q: torch.Tensor, layout: str) -> Tuple[int, int, int, int]:
 def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
             slice_scale: Optional[torch.Tensor] = None,
             dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
-            causal: bool = False) -> CottenParams:
+            causal: bool = False, saved_state: Optional[torch.Tensor] = None) -> CottenParams:
     p = CottenParams()
     p.causal = int(bool(causal))
-    B, H, _, _ = _dims(Q, layout)
+    B, H, _, d = _dims(Q, layout)
+    p.saved_state = _f32_vector("saved_state", saved_state, B * H * d * d, Q.device)
     p.layout = COTTEN_BNHD if layout == "bnhd" else COTTEN_BHND
     slices = B * H
     p.slice_scale = _f32_vector("slice_scale", slice_scale, slices, Q.device)
@@ -207,10 +209,13 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     scale: Optional[float] = None, eps: Optional[float] = None,
                     stream=None, workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
-                    layout: str = "bhnd", causal: bool = False) -> torch.Tensor:
+                    layout: str = "bhnd", causal: bool = False,
+                    saved_state: Optional[torch.Tensor] = None) -> torch.Tensor:
     """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O.
     `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`;
-    `layout` "bnhd" means all tensors are [B,N,H,d_h] instead of [B,H,N,d_h]."""
+    `layout` "bnhd" means all tensors are [B,N,H,d_h] instead of [B,H,N,d_h];
+    `saved_state` ([B,H,d_h,d_h] float32) receives the state S of every slice for the
+    backward call."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q)
     B, H, N, d = _dims(Q, layout)
@@ -220,7 +225,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     handle = _stream_handle(stream)
     if not causal:
         workspace = _workspace(Q, (B, H, N, d), False, handle, workspace)
-    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal)
+    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal, saved_state)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
@@ -236,13 +241,16 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
                     dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
-                    causal: bool = False,
-                    static_scratch: bool = False) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+                    causal: bool = False, static_scratch: bool = False,
+                    saved_state: Optional[torch.Tensor] = None
+                    ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
     `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
     d loss / d log(scale) of every slice.  With `static_scratch` the call goes to
     cotten_attn_bwd_static: no workspace is passed or allocated, the library's own static
-    scratch array serves (the output tensors must then be given, nothing is allocated here)."""
+    scratch array serves (the output tensors must then be given, nothing is allocated here).
+    `saved_state`: the state the forward call of the same inputs wrote; read instead of being
+    rebuilt from K, V."""
     lib = load_library()
     Q = _prep("Q", Q); K = _prep("K", K, Q); V = _prep("V", V, Q); dO = _prep("dO", dO, Q)
     B, H, N, d = _dims(Q, layout)
@@ -254,7 +262,7 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
         workspace = None
     elif not causal:
         workspace = _workspace(Q, (B, H, N, d), True, handle, workspace)
-    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal)
+    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal, saved_state)
     entry = lib.cotten_attn_bwd_static if static_scratch else lib.cotten_attn_bwd_ex
     with torch.cuda.device(Q.device):
         _check(entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(),

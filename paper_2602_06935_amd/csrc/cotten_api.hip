@@ -82,8 +82,8 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   if (bwd ? (dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr) : (O == nullptr))
     return COTTEN_ERR_NULL_POINTER;
   if (int rc = check_shape(B, H, N, d_h, prm->dtype)) return rc;
-  const void* tensors[8] = {Q, K, V, bwd ? dO : O, dQ, dK, dV,
-                            use_static_scratch ? nullptr : prm->workspace};
+  const void* tensors[9] = {Q, K, V, bwd ? dO : O, dQ, dK, dV,
+                            use_static_scratch ? nullptr : prm->workspace, prm->saved_state};
   for (const void* t : tensors)
     if (t != nullptr && !aligned16(t)) return COTTEN_ERR_MISALIGNED;
 
@@ -130,6 +130,7 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   }
   p.slice_scale = prm->slice_scale;
   p.dlog_scale = bwd ? prm->dlog_scale : nullptr;
+  p.saved_state = prm->saved_state;
   p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
   p.O = O; p.dQ = dQ; p.dK = dK; p.dV = dV;
   p.B = B; p.H = H; p.N = N; p.D = d_h;
@@ -145,7 +146,10 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   return err == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
 }
 
-const cotten_params kDefaults = {COTTEN_F32, 0.0f, -1.0f, nullptr, 0, nullptr, nullptr, COTTEN_BHND, 0};
+// dtype, scale, eps, workspace, workspace_bytes, slice_scale, dlog_scale, layout, causal,
+// saved_state
+const cotten_params kDefaults = {COTTEN_F32, 0.0f,    -1.0f,       nullptr, 0,
+                                 nullptr,    nullptr, COTTEN_BHND, 0,       nullptr};
 
 }  // namespace
 

@@ -420,6 +420,9 @@ hipError_t run_fwd(const Problem& p, const Plan& plan) {
                      p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, size_t{0}, p.eps,
                      elem_strides(p));
   const float* states = reduce_generic(p, plan, 1);
+  // the caller keeps the state for its backward call: same [B*H][D*D] layout, a plain copy
+  if (p.saved_state != nullptr)
+    launch_reduce_states(states, p.saved_state, 1, D * D, static_cast<size_t>(BH), p.stream);
   constexpr size_t lds = (D * D + kTileRows * (D + 4)) * sizeof(float);
   if (hipError_t err = allow_lds(apply_fwd_kernel<T, D>, lds)) return err;
   hipLaunchKernelGGL((apply_fwd_kernel<T, D>), grid, dim3(kThreads), lds, p.stream,

@@ -26,6 +26,8 @@ struct Problem {
   float scale, eps;
   const float* slice_scale;  // [B*H] or nullptr: per-slice scale instead of `scale`
   float* dlog_scale;         // backward only, [B*H] or nullptr: receives <S, dS> per slice
+  float* saved_state;        // [B*H][D][D] or nullptr: S of every slice, written by the forward,
+                             // read by the backward (which then does not rebuild it)
   float* workspace;     // partial and reduced states, see Plan
   hipStream_t stream;
 };

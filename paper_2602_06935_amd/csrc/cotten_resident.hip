@@ -51,6 +51,10 @@ struct Args {
   float scale, eps;
   const float* scales;  // per-slice scale, or nullptr
   float* dlog;          // backward: <S, dS> per slice, or nullptr
+  // S = sum_j m_j khat_j^T v_j of every slice as the caller keeps it from the forward to the
+  // backward call ([slices][d][d] floats, row-major, without the scale), or nullptr
+  float* saved;
+  int d;                // head dimension (states are D x D, zero beyond d)
 };
 
 // The wave's tile: rows 16*tile + r8 + 8h.  `want` bit h: the row takes part.
@@ -114,34 +118,60 @@ __device__ __forceinline__ void publish_inv(float* dst, const Lane& L, const flo
   }
 }
 
-// One wave per state block: walks all kMaxTiles resident tiles in straight-line code (so
-// that the LDS reads of later tiles overlap the matrix-core work on earlier ones) and then
-// writes its block into the images.  Tiles that contribute nothing must hold zeros.
-template <class F>
+// One wave per state block: walks all kMaxTiles resident tiles and then writes its block into
+// the images.  Tiles that contribute nothing must hold zeros.  The operands of the next
+// kAhead tiles are requested from LDS before the matrix cores start on a tile (the scheduler
+// is held to that order: left alone it funnels every tile through one register set, and each
+// LDS read then waits for the product before it).
+// Images are written with wide stores from an accumulator that holds the block the other way
+// round: the natural image needs the transposed block, i.e. the operands swapped (a second
+// accumulation, far cheaper than narrow image writes).
+template <class F, bool NATURAL, bool TRANSPOSED>
 __device__ __forceinline__ void build_state(const Lane& L, int block, int x_off, int y_off,
                                             float scale, unsigned char* natural,
                                             unsigned char* transposed,
                                             const unsigned char* other_natural = nullptr,
-                                            float* dot_out = nullptr) {
+                                            float* dot_out = nullptr, float* save_to = nullptr,
+                                            int d = 0) {
   typedef typename F::BlockAcc Acc;
-  // Images are written with wide stores from an accumulator that holds the block the other
-  // way round: the natural image needs the transposed block, i.e. the operands swapped
-  // (a second accumulation, far cheaper than narrow image writes).
+  constexpr int kAhead = 3;
+  static_assert(kAhead < kMaxTiles, "prefetch depth");
   Acc acc_t, acc_n;
   acc_t.zero();
   acc_n.zero();
+  typename Acc::Frag ring[kAhead];
+#pragma unroll
+  for (int t = 0; t < kAhead; ++t)
+    ring[t] = Acc::fetch(smem + t * kBlockBytes + x_off, smem + t * kBlockBytes + y_off, L, block);
 #pragma unroll
   for (int t = 0; t < kMaxTiles; ++t) {
-    const unsigned char* blk = smem + t * kBlockBytes;
-    const typename Acc::Frag f = Acc::fetch(blk + x_off, blk + y_off, L, block);
-    if (transposed != nullptr) acc_t.mma(f);
-    if (natural != nullptr) acc_n.mma_swapped(f);
+    const typename Acc::Frag f = ring[t % kAhead];
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + kAhead < kMaxTiles) {
+      const unsigned char* blk = smem + (t + kAhead) * kBlockBytes;
+      ring[t % kAhead] = Acc::fetch(blk + x_off, blk + y_off, L, block);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (TRANSPOSED) acc_t.mma(f);
+    if (NATURAL) acc_n.mma_swapped(f);
   }
   const int r0 = Acc::block_row0(block), c0 = Acc::block_col0(block);
-  if (transposed != nullptr) acc_t.write_image(L, r0, c0, scale, transposed);
-  if (natural != nullptr) acc_n.write_image(L, c0, r0, scale, natural);
+  if (TRANSPOSED) acc_t.write_image(L, r0, c0, scale, transposed);
+  if (NATURAL) acc_n.write_image(L, c0, r0, scale, natural);
+  // the block as it is (fp32, unscaled) into the caller's d x d array: the lane holds column
+  // c0 + lane%32 of rows r0 + 8j + 4*(lane/32) .. +3, so 32 lanes write 128 contiguous bytes
+  if (TRANSPOSED && save_to != nullptr) {
+    const int c = c0 + (L.lane & 31);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = r0 + 8 * j + 4 * (L.lane >> 5) + v;
+        if (r < d && c < d) save_to[r * d + c] = acc_t.v[4 * j + v];
+      }
+  }
   // <this state, the state whose natural image is given>, this wave's block of it
-  if (dot_out != nullptr) {
+  if (NATURAL && dot_out != nullptr) {
     const float dot = wave_sum(acc_n.dot_image(L, c0, r0, other_natural));
     if (L.lane == 0) *dot_out = dot;
   }
@@ -206,7 +236,9 @@ __global__ __launch_bounds__(kThreads) void resident_fwd_kernel(const Args a) {
       if (tile >= kWaves - kB) {  // O = qhat S: contraction over rows of S -> transposed image
         __builtin_amdgcn_s_setprio(3);
         const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
-        build_state<F>(L, tile - (kWaves - kB), kKt, kVt, scale, nullptr, img);
+        build_state<F, false, true>(
+            L, tile - (kWaves - kB), kKt, kVt, scale, nullptr, img, nullptr, nullptr,
+            a.saved != nullptr ? a.saved + static_cast<size_t>(slice) * a.d * a.d : nullptr, a.d);
         __builtin_amdgcn_s_setprio(0);
       }
       if (mine) {
@@ -271,11 +303,10 @@ __device__ __forceinline__ void apply_tile(const Lane& L, int kind, int t, int N
   if (row < N) store_product_row<F, kStoreStreamed>(dst, row, row_addr, L, p);
 }
 
-// Backward, per slice (B = workgroup barrier).  Q and dO come first because their loads do not
-// wait for the mask bytes, so for a workgroup's first slice they arrive first:
-//   1  tile waves stage Q, dO                                                        B
+// Backward, per slice (B = workgroup barrier):
+//   1  tile waves stage Q, dO and request Q, dO of the next slice                    B
 //   2  waves 12-15 build dS (one block each, at raised priority: everyone waits for it);
-//      tile waves stage K, V and issue the loads of the next slice                   B
+//      tile waves stage K, V and request K, V of the next slice                      B
 //   3  waves 12-15 build S;  waves 0-11 apply dV and dK, which need only dS: waves 2i, 2i+1
 //      take tiles i, i+6, i+12, one product each, so that every SIMD gets both kinds    B
 //   4  wave w applies dQ of tile w                                                    B
@@ -301,11 +332,13 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
 
   int slice = blockIdx.x;
   Raw rq, rk;
-  // The first slice: only Q and dO are requested at once (every compute unit asks at the same
-  // moment, and the first phase needs nothing else); K and V follow when those have arrived
-  // and travel while Q, dO are staged and dS is built.
+  // Loads are requested as early as the registers that receive them are free: everything of the
+  // first slice at once, Q and dO of the next slice as soon as those of the current one are
+  // staged, its K and V as soon as the current ones are (measured against requesting the next
+  // slice in one go after phase 2, and K, V of the first slice only after Q, dO: 18.3 against
+  // 21.0 us at 512 slices of 200 rows).
   const int first_keys = key_rows(a, L0, slice, tile);
-  fetch<true, 2>(rq, rk, a, L0, slice, tile, 0);
+  fetch<true>(rq, rk, a, L0, slice, tile, first_keys);
   int keys = key_rows(a, L0, slice + stride, tile);
   float* dots = reinterpret_cast<float*>(smem + Lds<F>::kDots);
   for (int iter = 0; slice < a.slices; slice += stride, ++iter) {
@@ -318,7 +351,8 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
         stage<F, kXNormalized, true>(rq, L, a.eps, blk + kQt, blk + kGt, inv);
         publish_inv(invs + tile * 2 * TR, L, inv);
       }
-      if (iter == 0) fetch<true, 1>(rq, rk, a, L, slice, tile, first_keys);
+      // Q, dO of the next slice are requested as soon as their registers are free
+      if (mine) fetch<true, 2>(rq, rk, a, L, slice + stride, tile, 0);
     }
     __syncthreads();
     {
@@ -326,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       if (tile >= kApplyWaves) {
         // dV = khat dS -> transposed image;  h = v dS^T -> natural image
         __builtin_amdgcn_s_setprio(3);  // the other waves wait for this at the next barrier
-        build_state<F>(L, tile - kApplyWaves, kQt, kGt, scale, img_ds, img_dst);
+        build_state<F, true, true>(L, tile - kApplyWaves, kQt, kGt, scale, img_ds, img_dst);
         __builtin_amdgcn_s_setprio(0);
       }
       if (mine) {
@@ -340,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
           clear_tiles(L, blk + kKt, blk + kVt);
         }
         if (L.lane == 0) live[tile] = any_key;
-        fetch<true>(rq, rk, a, L, slice + stride, tile, keys);
+        fetch<true, 1>(rq, rk, a, L, slice + stride, tile, keys);
         keys = key_rows(a, L, slice + 2 * stride, tile);
       }
     }
@@ -350,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
       // block of <sum_j khat_j^T v_j, scale * dS (its image)>
       const Lane L = L0.again();
       __builtin_amdgcn_s_setprio(3);
-      build_state<F>(L, tile - kApplyWaves, kKt, kVt, scale, img_s, nullptr, img_ds,
+      build_state<F, true, false>(L, tile - kApplyWaves, kKt, kVt, scale, img_s, nullptr, img_ds,
                      a.dlog != nullptr ? dots + (tile - kApplyWaves) : nullptr);
       __builtin_amdgcn_s_setprio(0);
     } else {
@@ -617,6 +651,8 @@ Args make_args(const Problem& p) {
   a.eps = p.eps;
   a.scales = p.slice_scale;
   a.dlog = p.dlog_scale;
+  a.saved = p.saved_state;
+  a.d = p.D;
   return a;
 }
 
@@ -626,6 +662,10 @@ hipError_t run(const Problem& p, bool bwd) {
   const int units = compute_units();
   const dim3 grid(static_cast<unsigned>(a.slices < units ? a.slices : units));
   const size_t lds = Lds<F>::kBytes;
+  // The backward never reads a kept state here: with the slice in LDS K and V are fetched once
+  // whether S is rebuilt or not, and reading d x d floats per slice would only add traffic (at
+  // d = 64 and 200 rows the state is 16 KB next to 25 KB per tensor: measured 23.1 against
+  // 18.4 us at 512 slices).
   const void* kern = bwd ? reinterpret_cast<const void*>(resident_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(resident_fwd_kernel<F>);
   const hipError_t err = grant_dynamic_lds(kern, static_cast<int>(lds));

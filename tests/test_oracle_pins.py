@@ -442,3 +442,32 @@ def test_causal_backward_against_autograd_and_differences(oracle):
             argm = {"Q": (Xm, K, V), "K": (Q, Xm, V), "V": (Q, K, Xm)}[name]
             fd = (loss(*args) - loss(*argm)) / 2e-6
             assert abs(fd - G[idx]) < 1e-6 * max(1.0, abs(G[idx]))
+
+
+def test_state_reproduces_the_quadratic_definition(oracle):
+    """The exported state S = Khat^T V is what the reordered CosineAttention contracts Qhat
+    with: scale * qhat_i S, formed here row by row with the library's matrix product, equals the
+    N x N definition; masked keys leave S unchanged whatever they hold; S of a single valid key
+    is the outer product khat^T v."""
+    rng = np.random.default_rng(77)
+    B, H, N, d = 2, 2, 19, 8
+    Q, K, V = (rng.standard_normal((B, H, N, d)) for _ in range(3))
+    mask = (rng.random((B, N)) < 0.6).astype(np.uint8)
+    mask[:, 3] = 1
+    eps = 1e-3
+    S = oracle.state(K, V, mask, eps=eps)
+    assert S.shape == (B, H, d, d)
+    qhat = Q / np.sqrt((Q * Q).sum(-1, keepdims=True) + eps)
+    np.testing.assert_allclose(0.37 * np.matmul(qhat, S),
+                               oracle.fwd_quadratic(Q, K, V, mask, scale=0.37, eps=eps), rtol=1e-12, atol=1e-13)
+    K2, V2 = K.copy(), V.copy()
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], K.shape)
+    K2[dead] = 1e30
+    V2[dead] = -7.0
+    assert np.array_equal(oracle.state(K2, V2, mask, eps=eps), S)
+    one = np.zeros((B, N), np.uint8)
+    one[:, 5] = 1
+    S1 = oracle.state(K, V, one, eps=eps)
+    k5, v5 = K[:, :, 5], V[:, :, 5]
+    np.testing.assert_allclose(S1, (k5 / np.sqrt((k5 * k5).sum(-1, keepdims=True) + eps))[..., :, None] * v5[..., None, :],
+                               rtol=1e-13, atol=0)
