@@ -33,6 +33,13 @@
  * cotten_oracle_causal_fwd / _bwd, so that the prefix-state kernels can be checked against
  * something that has no prefix state in it.
  *
+ * The ELU + 1 feature map (section "Linear Attention Models": the linear-attention comparison
+ * model applies ELU(x) + 1 element-wise to queries and keys, collapses keys and values into a
+ * d x d product and multiplies the transformed queries with it).  Stated here from the N x N
+ * scores A_ij = phi(q_i) . phi(k_j), O_i = scale * sum_j m_j A_ij v_j, phi(x) = x + 1 for x > 0
+ * and exp(x) otherwise (ELU with alpha = 1), cotten_oracle_elu_fwd / _bwd.  Reading: the
+ * section names no normalising denominator, so none is applied beyond the scalar `scale`.
+ *
  * Pins (tests/test_oracle_pins.py): linear == quadratic on small inputs;
  * closed forms; unit norms; masked-key invariance; permutation equivariance;
  * fp64 autograd of the library expression; central finite differences and an
@@ -369,5 +376,89 @@ void cotten_oracle_causal_bwd(const double* Q, const double* K, const double* V,
       for (int a = 0; a < d; ++a) dK[off + (size_t)j * d + a] = (gh[a] - xh[a] * proj) / rk[j];
     }
     free(P); free(G); free(rq); free(rk); free(xh); free(gh);
+  }
+}
+
+/* ---- ELU + 1 feature map ("Linear Attention Models") ---------------------------------- */
+
+/* phi(x) = ELU(x) + 1 with alpha = 1: x + 1 for x > 0, exp(x) otherwise; always positive. */
+static double elu1(double x) { return x > 0.0 ? x + 1.0 : exp(x); }
+/* its derivative: 1 for x > 0, exp(x) otherwise */
+static double elu1_prime(double x) { return x > 0.0 ? 1.0 : exp(x); }
+
+/* A[i][j] = m_j * phi(q_i) . phi(k_j) */
+static void elu_scores(const double* q, const double* k, const uint8_t* mask, int b, int N,
+                       int d, double* A) {
+  for (int i = 0; i < N; ++i)
+    for (int j = 0; j < N; ++j) {
+      double a = 0.0;
+      if (key_valid(mask, b, N, j))
+        for (int c = 0; c < d; ++c) a += elu1(q[(size_t)i * d + c]) * elu1(k[(size_t)j * d + c]);
+      A[(size_t)i * N + j] = a;
+    }
+}
+
+/* O_i = scale * sum_j m_j (phi(q_i) . phi(k_j)) v_j */
+void cotten_oracle_elu_fwd(const double* Q, const double* K, const double* V,
+                           const uint8_t* mask, double* O, int B, int H, int N, int d,
+                           double scale) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const size_t off = (size_t)bh * N * d;
+    double* A = (double*)malloc(sizeof(double) * (size_t)N * N);
+    elu_scores(Q + off, K + off, mask, bh / H, N, d, A);
+    for (int i = 0; i < N; ++i)
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int j = 0; j < N; ++j) acc += A[(size_t)i * N + j] * V[off + (size_t)j * d + c];
+        O[off + (size_t)i * d + c] = scale * acc;
+      }
+    free(A);
+  }
+}
+
+/* Backward through the N x N scores: with G[i][j] = scale * m_j * (dO_i . v_j),
+ *   dV_j = scale * sum_i A[i][j] dO_i,
+ *   dq_i = phi'(q_i) * sum_j G[i][j] phi(k_j),   dk_j = phi'(k_j) * sum_i G[i][j] phi(q_i)
+ * (element-wise products with phi').  Masked keys get exact zeros. */
+void cotten_oracle_elu_bwd(const double* Q, const double* K, const double* V,
+                           const uint8_t* mask, const double* dO, double* dQ, double* dK,
+                           double* dV, int B, int H, int N, int d, double scale) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    const int b = bh / H;
+    const size_t off = (size_t)bh * N * d;
+    const double *q = Q + off, *k = K + off, *v = V + off, *go = dO + off;
+    double* A = (double*)malloc(sizeof(double) * (size_t)N * N);
+    double* G = (double*)malloc(sizeof(double) * (size_t)N * N);
+    elu_scores(q, k, mask, b, N, d, A);
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j < N; ++j) {
+        double g = 0.0;
+        if (key_valid(mask, b, N, j)) {
+          for (int c = 0; c < d; ++c) g += go[(size_t)i * d + c] * v[(size_t)j * d + c];
+          g *= scale;
+        }
+        G[(size_t)i * N + j] = g;
+      }
+    for (int j = 0; j < N; ++j)
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int i = 0; i < N; ++i) acc += A[(size_t)i * N + j] * go[(size_t)i * d + c];
+        dV[off + (size_t)j * d + c] = scale * acc;
+      }
+    for (int i = 0; i < N; ++i)
+      for (int a = 0; a < d; ++a) {
+        double acc = 0.0;
+        for (int j = 0; j < N; ++j) acc += G[(size_t)i * N + j] * elu1(k[(size_t)j * d + a]);
+        dQ[off + (size_t)i * d + a] = elu1_prime(q[(size_t)i * d + a]) * acc;
+      }
+    for (int j = 0; j < N; ++j)
+      for (int a = 0; a < d; ++a) {
+        double acc = 0.0;
+        for (int i = 0; i < N; ++i) acc += G[(size_t)i * N + j] * elu1(q[(size_t)i * d + a]);
+        dK[off + (size_t)j * d + a] = elu1_prime(k[(size_t)j * d + a]) * acc;
+      }
+    free(A); free(G);
   }
 }

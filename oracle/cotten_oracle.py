@@ -55,6 +55,10 @@ def _load():
         lib.cotten_oracle_causal_fwd.restype = None
         lib.cotten_oracle_causal_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, i, i, i, i, f, f]
         lib.cotten_oracle_causal_bwd.restype = None
+        lib.cotten_oracle_elu_fwd.argtypes = [dp, dp, dp, bp, dp, i, i, i, i, f]
+        lib.cotten_oracle_elu_fwd.restype = None
+        lib.cotten_oracle_elu_bwd.argtypes = [dp, dp, dp, bp, dp, dp, dp, dp, i, i, i, i, f]
+        lib.cotten_oracle_elu_bwd.restype = None
         lib.cotten_oracle_state.argtypes = [dp, dp, bp, dp, i, i, i, i, f]
         lib.cotten_oracle_state.restype = None
         lib.cotten_oracle_threads.argtypes = []
@@ -187,4 +191,28 @@ def causal_bwd(Q, K, V, dO, mask=None, scale: Optional[float] = None, eps: float
     m, mp = _mask_arg(mask, B, N)
     _load().cotten_oracle_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(dO), _ptr(dQ), _ptr(dK),
                                      _ptr(dV), B, H, N, d, s, float(eps))
+    return dQ, dK, dV
+
+
+def elu_fwd(Q, K, V, mask=None, scale: Optional[float] = None) -> np.ndarray:
+    """O_i = scale * sum_j m_j (phi(q_i) . phi(k_j)) v_j with phi = ELU + 1, all N x N scores formed."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    assert Q.ndim == 4 and Q.shape == K.shape == V.shape
+    B, H, N, d = Q.shape
+    s = 1.0 / N if scale is None else float(scale)
+    O = np.empty_like(Q)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_elu_fwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(O), B, H, N, d, s)
+    return O
+
+
+def elu_bwd(Q, K, V, dO, mask=None, scale: Optional[float] = None):
+    """(dQ, dK, dV) of elu_fwd for upstream gradient dO, through the N x N scores."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    B, H, N, d = Q.shape
+    s = 1.0 / N if scale is None else float(scale)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    m, mp = _mask_arg(mask, B, N)
+    _load().cotten_oracle_elu_bwd(_ptr(Q), _ptr(K), _ptr(V), mp, _ptr(dO), _ptr(dQ), _ptr(dK),
+                                  _ptr(dV), B, H, N, d, s)
     return dQ, dK, dV

@@ -471,3 +471,77 @@ def test_state_reproduces_the_quadratic_definition(oracle):
     k5, v5 = K[:, :, 5], V[:, :, 5]
     np.testing.assert_allclose(S1, (k5 / np.sqrt((k5 * k5).sum(-1, keepdims=True) + eps))[..., :, None] * v5[..., None, :],
                                rtol=1e-13, atol=0)
+
+
+# ------------------------------------------------------------- ELU + 1 feature map
+
+def test_elu_feature_map_closed_forms(oracle):
+    """phi(0) = 1, so with Q = K = 0 every score is d and O_i = scale * d * sum_j m_j v_j; a
+    single large positive entry adds exactly its value to the score; large negative entries
+    contribute nothing (phi -> 0); the result is positive-homogeneous of degree 1 in V."""
+    rng = np.random.default_rng(5)
+    B, H, N, d = 2, 1, 6, 4
+    V = rng.standard_normal((B, H, N, d))
+    mask = np.array([[1, 1, 0, 1, 1, 1], [0, 1, 1, 0, 0, 1]], np.uint8)
+    Z = np.zeros((B, H, N, d))
+    O = oracle.elu_fwd(Z, Z, V, mask, scale=0.5)
+    want = 0.5 * d * (V * mask[:, None, :, None]).sum(axis=2, keepdims=True)
+    np.testing.assert_allclose(O, np.broadcast_to(want, O.shape), rtol=1e-14, atol=1e-14)
+    Q1 = Z.copy()
+    Q1[0, 0, 2, 1] = 3.0          # phi = 4 instead of 1: the scores of row 2 grow by 3 * phi(k_j1) = 3
+    O1 = oracle.elu_fwd(Q1, Z, V, mask, scale=0.5)
+    np.testing.assert_allclose(O1[0, 0, 2], want[0, 0, 0] * (d + 3) / d, rtol=1e-14)
+    np.testing.assert_allclose(np.delete(O1[0, 0], 2, axis=0), np.delete(O[0, 0], 2, axis=0), rtol=0, atol=0)
+    Kneg = np.full((B, H, N, d), -800.0)   # phi(k) = exp(-800) = 0 in double
+    assert np.all(oracle.elu_fwd(Q1, Kneg, V, mask, scale=0.5) == 0.0)
+    np.testing.assert_allclose(oracle.elu_fwd(Q1, Z, 3.0 * V, mask, scale=0.5), 3.0 * O1, rtol=1e-14)
+
+
+def test_elu_feature_map_against_the_two_product_form_and_autograd(oracle):
+    """The N x N statement equals the two-product (d x d state) form by associativity, and
+    forward and backward equal fp64 autograd of the library expression elu(x) + 1."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(8)
+    B, H, N, d = 2, 2, 13, 5
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) * 1.5 for _ in range(4))
+    mask = (rng.random((B, N)) < 0.7).astype(np.uint8)
+    mask[:, 0] = 1
+    s = 0.21
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    tm = torch.tensor(mask, dtype=torch.float64)[:, None, :, None]
+    fq, fk = torch.nn.functional.elu(tq) + 1, torch.nn.functional.elu(tk) + 1
+    state = torch.matmul((fk * tm).transpose(-1, -2), tv)          # d x d, keys collapsed first
+    out = s * torch.matmul(fq, state)
+    (out * torch.tensor(dO)).sum().backward()
+    np.testing.assert_allclose(oracle.elu_fwd(Q, K, V, mask, scale=s), out.detach().numpy(), rtol=1e-12, atol=1e-13)
+    got = oracle.elu_bwd(Q, K, V, dO, mask, scale=s)
+    for g, t in zip(got, (tq, tk, tv)):
+        np.testing.assert_allclose(g, t.grad.numpy(), rtol=1e-11, atol=1e-12)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], Q.shape)
+    assert np.all(got[1][dead] == 0.0) and np.all(got[2][dead] == 0.0)
+    # garbage in masked K, V rows changes nothing
+    K2, V2 = K.copy(), V.copy()
+    K2[dead] = 50.0
+    V2[dead] = -1e6
+    assert np.array_equal(oracle.elu_fwd(Q, K2, V2, mask, scale=s), oracle.elu_fwd(Q, K, V, mask, scale=s))
+
+
+def test_elu_backward_central_differences(oracle):
+    rng = np.random.default_rng(9)
+    B, H, N, d = 1, 2, 7, 3
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) for _ in range(4))
+    Q[0, 0, 0, 0], K[0, 1, 2, 1] = 0.3, -0.4       # both branches of the map, away from the kink
+    mask = np.array([[1, 0, 1, 1, 1, 0, 1]], np.uint8)
+    s = 0.4
+    loss = lambda q, k, v: float((oracle.elu_fwd(q, k, v, mask, scale=s) * dO).sum())
+    grads = oracle.elu_bwd(Q, K, V, dO, mask, scale=s)
+    h = 1e-6
+    for which, (X, g) in enumerate(zip((Q, K, V), grads)):
+        for idx in [(0, 0, 0, 0), (0, 1, 2, 1), (0, 1, 6, 2), (0, 0, 3, 1)]:
+            xp, xm = X.copy(), X.copy()
+            xp[idx] += h
+            xm[idx] -= h
+            args_p = [Q, K, V]; args_m = [Q, K, V]
+            args_p[which], args_m[which] = xp, xm
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
+            assert abs(fd - g[idx]) <= 1e-7 * max(1.0, abs(fd)), (which, idx, fd, g[idx])
