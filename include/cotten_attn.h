@@ -96,6 +96,19 @@ typedef enum cotten_layout {
                       row stay contiguous, the rows of a slice are H*d_h elements apart   */
 } cotten_layout;
 
+typedef enum cotten_feature_map {
+  COTTEN_MAP_COSINE = 0, /* rows of Q and K divided by sqrt(sum_c x_c^2 + eps): the cosine
+                            attention of the paper (default)                                */
+  COTTEN_MAP_ELU1 = 1    /* ELU(x) + 1 element-wise on Q and K (x + 1 above zero, exp(x) below):
+                            the linear-attention comparison model of the paper's section
+                            "Linear Attention Models", on the same two products
+                            O = scale * phi(Q) (phi(K)^T V) and their exact gradients.  No
+                            normalising denominator (the section names none), eps unused.
+                            Served by the matrix-core kernels: fp32 with d_h in {16, 32}, 16-bit
+                            with d_h in {16, 32, 64} (COTTEN_ERR_UNSUPPORTED_HEAD_DIM
+                            otherwise); not with causal (COTTEN_ERR_BAD_PARAM)              */
+} cotten_feature_map;
+
 typedef enum cotten_status {
   COTTEN_OK = 0,
   COTTEN_ERR_NULL_POINTER = -1,         /* a required tensor pointer is NULL            */
@@ -142,6 +155,7 @@ typedef struct cotten_params {
                              vector-ALU kernels (fp32 d_h = 64, d_h = 128) and a backward call
                              that also asks for dlog_scale rebuild S all the same; the causal
                              variant has no such state and ignores the field              */
+  int feature_map;        /* a cotten_feature_map: what is done to the rows of Q and K    */
 } cotten_params;
 
 /* Forward (reordered CosineAttention with scalar normaliser, "Model Description"):

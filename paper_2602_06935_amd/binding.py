@@ -26,6 +26,8 @@ COTTEN_BF16 = 1
 COTTEN_F16 = 2
 COTTEN_BHND = 0
 COTTEN_BNHD = 1
+COTTEN_MAP_COSINE = 0
+COTTEN_MAP_ELU1 = 1
 
 EXPORTS = (
     "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
@@ -39,7 +41,7 @@ class CottenParams(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("slice_scale", ctypes.c_void_p), ("dlog_scale", ctypes.c_void_p),
                 ("layout", ctypes.c_int), ("causal", ctypes.c_int),
-                ("saved_state", ctypes.c_void_p)]
+                ("saved_state", ctypes.c_void_p), ("feature_map", ctypes.c_int)]
 
 
 class CottenError(RuntimeError):
@@ -147,9 +149,13 @@ def _dims(Q: torch.Tensor, layout: str) -> Tuple[int, int, int, int]:
 def _params(Q: torch.Tensor, scale, eps, workspace: Optional[torch.Tensor],
             slice_scale: Optional[torch.Tensor] = None,
             dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
-            causal: bool = False, saved_state: Optional[torch.Tensor] = None) -> CottenParams:
+            causal: bool = False, saved_state: Optional[torch.Tensor] = None,
+            feature_map: str = "cosine") -> CottenParams:
     p = CottenParams()
     p.causal = int(bool(causal))
+    if feature_map not in ("cosine", "elu1"):
+        raise ValueError("feature_map must be 'cosine' or 'elu1'")
+    p.feature_map = COTTEN_MAP_ELU1 if feature_map == "elu1" else COTTEN_MAP_COSINE
     B, H, _, d = _dims(Q, layout)
     p.saved_state = _f32_vector("saved_state", saved_state, B * H * d * d, Q.device)
     p.layout = COTTEN_BNHD if layout == "bnhd" else COTTEN_BHND
@@ -210,7 +216,8 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     stream=None, workspace: Optional[torch.Tensor] = None,
                     slice_scale: Optional[torch.Tensor] = None,
                     layout: str = "bhnd", causal: bool = False,
-                    saved_state: Optional[torch.Tensor] = None) -> torch.Tensor:
+                    saved_state: Optional[torch.Tensor] = None,
+                    feature_map: str = "cosine") -> torch.Tensor:
     """O = scale * Qhat (Khat^T V) under the key mask; enqueues on the stream and returns O.
     `slice_scale` ([B,H] float32) gives every slice its own scale instead of `scale`;
     `layout` "bnhd" means all tensors are [B,N,H,d_h] instead of [B,H,N,d_h];
@@ -225,7 +232,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     handle = _stream_handle(stream)
     if not causal:
         workspace = _workspace(Q, (B, H, N, d), False, handle, workspace)
-    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal, saved_state)
+    prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal, saved_state, feature_map)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       _mask_ptr(mask, B, N, Q.device), O.data_ptr(),
@@ -242,7 +249,7 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
                     slice_scale: Optional[torch.Tensor] = None,
                     dlog_scale: Optional[torch.Tensor] = None, layout: str = "bhnd",
                     causal: bool = False, static_scratch: bool = False,
-                    saved_state: Optional[torch.Tensor] = None
+                    saved_state: Optional[torch.Tensor] = None, feature_map: str = "cosine"
                     ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """(dQ, dK, dV) for upstream gradient dO; enqueues on the stream and returns the tensors.
     `slice_scale` as in the forward; `dlog_scale` ([B,H] float32), when given, receives
@@ -262,7 +269,8 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
         workspace = None
     elif not causal:
         workspace = _workspace(Q, (B, H, N, d), True, handle, workspace)
-    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal, saved_state)
+    prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal, saved_state,
+                  feature_map)
     entry = lib.cotten_attn_bwd_static if static_scratch else lib.cotten_attn_bwd_ex
     with torch.cuda.device(Q.device):
         _check(entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(),

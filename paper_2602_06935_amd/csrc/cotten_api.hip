@@ -103,6 +103,13 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   if ((static_cast<long long>(N - 1) * p.stride_row + d_h) * (prm->dtype == COTTEN_F32 ? 4 : 2) >=
       (1ll << 31))
     return COTTEN_ERR_BAD_SHAPE;
+  if (prm->feature_map != COTTEN_MAP_COSINE && prm->feature_map != COTTEN_MAP_ELU1)
+    return COTTEN_ERR_BAD_PARAM;
+  if (prm->feature_map == COTTEN_MAP_ELU1) {
+    if (prm->causal != 0) return COTTEN_ERR_BAD_PARAM;
+    if (!cotten::mfma_supports(prm->dtype, d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
+  }
+  p.feature_map = prm->feature_map;
   if (prm->causal != 0) {
     if (prm->causal != 1 || (bwd && prm->dlog_scale != nullptr)) return COTTEN_ERR_BAD_PARAM;
     if (!cotten::causal_supports(d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
@@ -114,7 +121,8 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
     p.stream = static_cast<hipStream_t>(stream);
     return cotten::launch_causal(p, bwd) == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
   }
-  const cotten::Plan plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd);
+  const cotten::Plan plan =
+      cotten::make_plan(B, H, N, d_h, prm->dtype, bwd, prm->feature_map == COTTEN_MAP_COSINE);
   const size_t need = plan.workspace_floats * sizeof(float);
   if (use_static_scratch) {
     if (need > COTTEN_STATIC_SCRATCH_BYTES) return COTTEN_ERR_STATIC_SCRATCH;
@@ -147,9 +155,9 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
 }
 
 // dtype, scale, eps, workspace, workspace_bytes, slice_scale, dlog_scale, layout, causal,
-// saved_state
-const cotten_params kDefaults = {COTTEN_F32, 0.0f,    -1.0f,       nullptr, 0,
-                                 nullptr,    nullptr, COTTEN_BHND, 0,       nullptr};
+// saved_state, feature_map
+const cotten_params kDefaults = {COTTEN_F32, 0.0f,    -1.0f,       nullptr, 0,      nullptr,
+                                 nullptr,    COTTEN_BHND, 0,       nullptr, COTTEN_MAP_COSINE};
 
 }  // namespace
 

@@ -481,7 +481,7 @@ void launch_reduce_states(const float* partial, float* reduced, int splits, int 
                      splits, dd, total);
 }
 
-Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
+Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_resident) {
   const long BH = static_cast<long>(B) * H;
   const size_t nstates = is_bwd ? 2 : 1;
   Plan plan;
@@ -498,7 +498,7 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd) {
     // registers is faster (N = 208, 512 slices: 9.6 against 10.2 us; the resident kernel wins
     // at N = 100, 7.1 against 7.6 us, and with 64 slices, 5.7 against 7.2 us).
     const bool fused_fwd_instead = !is_bwd && N > 160 && BH >= 256;
-    if (resident_supports(dtype, D, N) && !fused_fwd_instead) {
+    if (allow_resident && resident_supports(dtype, D, N) && !fused_fwd_instead) {
       plan.path = Plan::kResident;
       plan.splits = 1;
       plan.rows_per_split = N;

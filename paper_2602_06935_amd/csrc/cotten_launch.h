@@ -26,6 +26,7 @@ struct Problem {
   float scale, eps;
   const float* slice_scale;  // [B*H] or nullptr: per-slice scale instead of `scale`
   float* dlog_scale;         // backward only, [B*H] or nullptr: receives <S, dS> per slice
+  int feature_map;           // 0: row-wise L2 normalisation of Q and K, 1: ELU(x) + 1 element-wise
   float* saved_state;        // [B*H][D][D] or nullptr: S of every slice, written by the forward,
                              // read by the backward (which then does not rebuild it)
   float* workspace;     // partial and reduced states, see Plan
@@ -51,7 +52,9 @@ struct Plan {
   size_t workspace_floats;
 };
 
-Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd);
+// allow_resident = false keeps short 16-bit sequences off the kernels that hold a slice in LDS
+// (they implement the cosine map only); the workspace requirement is the same either way.
+Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_resident = true);
 
 // Grants `kernel` `bytes` of dynamic LDS (kernels that use more than 64 KB must be granted it
 // before their first launch).  The attribute is set once per kernel and device: later calls

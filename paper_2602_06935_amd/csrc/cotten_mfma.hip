@@ -49,12 +49,20 @@ bool mfma_supports(int dtype, int D) {
 int mfma_state_dim(int dtype) { return dtype == 0 ? F32x32::D : Bf16x64::D; }
 
 hipError_t launch_mfma_fwd(const Problem& p, const Plan& plan) {
+  if (p.feature_map == kMapElu1)
+    return p.dtype == 1   ? stream4::run_fwd<WithElu1<Bf16x64>>(p, plan)
+           : p.dtype == 2 ? stream4::run_fwd<WithElu1<F16x64>>(p, plan)
+                          : stream4::run_fwd<WithElu1<F32x32>>(p, plan);
   return p.dtype == 1   ? stream4::run_fwd<Bf16x64>(p, plan)
          : p.dtype == 2 ? stream4::run_fwd<F16x64>(p, plan)
                         : stream4::run_fwd<F32x32>(p, plan);
 }
 
 hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan) {
+  if (p.feature_map == kMapElu1)
+    return p.dtype == 1   ? stream4::run_bwd<WithElu1<Bf16x64>>(p, plan)
+           : p.dtype == 2 ? stream4::run_bwd<WithElu1<F16x64>>(p, plan)
+                          : stream4::run_bwd<WithElu1<F32x32>>(p, plan);
   return p.dtype == 1   ? stream4::run_bwd<Bf16x64>(p, plan)
          : p.dtype == 2 ? stream4::run_bwd<F16x64>(p, plan)
                         : stream4::run_bwd<F32x32>(p, plan);

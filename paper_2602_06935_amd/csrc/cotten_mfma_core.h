@@ -162,6 +162,7 @@ struct F16Elem {
 template <class E>
 struct Half64 {
   typedef E Elem;
+  static constexpr int kMap = 0;  // what is done to the rows of Q and K: see FeatureMap
   typedef typename E::v8 v8_t;
   typedef typename E::v4 v4_t;
   static constexpr int D = 64, EPL = 8, NT = 4;
@@ -387,6 +388,7 @@ typedef Half64<F16Elem> F16x64;
 
 struct F32x32 {
   typedef float io_t;
+  static constexpr int kMap = 0;
   static constexpr int D = 32, EPL = 4, NT = 2;
   static constexpr int kDepthState = 3, kDepthFwd = 3, kDepthQ = 3, kDepthKV = 2, kDepthQAccum = 2;
   static constexpr bool kShortFwd = true, kShortBwd = true;
@@ -501,6 +503,24 @@ struct F32x32 {
   }
 };
 
+// What a format does to the rows of Q and K before they enter the products:
+//   kMapCosine  x / sqrt(|x|^2 + eps)   row-wise L2 normalisation (the paper's model)
+//   kMapElu1    ELU(x) + 1              element-wise (the linear-attention comparison model of
+//                                       "Linear Attention Models"); eps plays no part
+// A format with the second map is the same format with kMap overridden: every pass picks the
+// staging mode and the row epilogue from F::kMap.
+enum FeatureMap { kMapCosine = 0, kMapElu1 = 1 };
+template <class Base>
+struct WithElu1 : Base {
+  static constexpr int kMap = kMapElu1;
+};
+
+// phi(x) = ELU(x) + 1 with alpha = 1: x + 1 above zero, exp(x) below (hardware exp2, about
+// 1 ulp).  Its derivative is 1 above zero and exp(x) below, i.e. min(phi(x), 1).
+__device__ __forceinline__ float elu1(float x) {
+  return x > 0.0f ? x + 1.0f : __builtin_amdgcn_exp2f(x * 1.44269504088896340736f);
+}
+
 // ---- tiles --------------------------------------------------------------------------------
 
 // The tiles one workgroup walks: local tile lt = 0 .. n_tiles-1 is tile (tile0 + lt * stride)
@@ -587,17 +607,35 @@ __device__ __forceinline__ void load_raw(Raw& r, const Lane& L, const Src& src, 
 }
 
 // What becomes of the x rows on their way to the LDS tile.
-enum XMode { kXNone = 0, kXRaw = 1, kXNormalized = 2 };
+enum XMode { kXNone = 0, kXRaw = 1, kXNormalized = 2, kXFeature = 3 };
+
+// The staging mode of rows that enter a product through the feature map of the format.
+template <class F>
+constexpr int mapped_mode() {
+  return F::kMap == kMapElu1 ? kXFeature : kXNormalized;
+}
 
 // inv[h] = 1/r of row h (0 for rows that do not take part; their registers are zero).
-// Xt receives nothing, the raw rows, or xhat; Yt the raw y rows.
+// Xt receives nothing, the raw rows, xhat, or phi(x) (kXFeature: then inv[h] is 1 for a row
+// that takes part, and `cols` says whether the lane's columns exist - phi(0) is not 0, so
+// padding columns and absent rows are written as zeros explicitly); Yt the raw y rows.
 template <class F, int XMODE, bool USE_Y>
 __device__ __forceinline__ void stage(const Raw& r, const Lane& L, float eps, unsigned char* Xt,
-                                      unsigned char* Yt, float (&inv)[2]) {
+                                      unsigned char* Yt, float (&inv)[2], bool cols = true) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     float f[F::EPL];
     F::unpack(r.x[h], f);
+    if (XMODE == kXFeature) {
+      const bool live = ((r.live >> h) & 1) != 0;
+      inv[h] = live ? 1.0f : 0.0f;
+#pragma unroll
+      for (int i = 0; i < F::EPL; ++i) f[i] = (live && cols) ? elu1(f[i]) : 0.0f;
+      const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+      *reinterpret_cast<u32x4_t*>(Xt + off) = F::pack(f);
+      if (USE_Y) *reinterpret_cast<u32x4_t*>(Yt + off) = r.y[h];
+      continue;
+    }
     float ss = 0.0f;
 #pragma unroll
     for (int i = 0; i < F::EPL; ++i) ss += f[i] * f[i];
@@ -660,6 +698,17 @@ __device__ __forceinline__ void project_rows(float (&p)[2 * F::EPL], typename F:
   }
 #pragma unroll
   for (int c = 0; c < 2 * F::EPL; ++c) p[c] = (p[c] - u[c] * proj) * inv_r;
+}
+
+// p <- p * phi'(x) element-wise, with phi(x) of the lane's row held in `e`: the chain rule
+// through the ELU + 1 map (phi' = min(phi, 1)).
+template <class F>
+__device__ __forceinline__ void feature_grad_rows(float (&p)[2 * F::EPL],
+                                                  const typename F::TileRows& e) {
+  float u[2 * F::EPL];
+  e.unpack(u);
+#pragma unroll
+  for (int c = 0; c < 2 * F::EPL; ++c) p[c] *= fminf(u[c], 1.0f);
 }
 
 // The same with the raw row x = r * u in `e`:  (p - u (u.p)) / r = p/r - x (x.p) / r^3.

@@ -1,0 +1,100 @@
+"""GPU parity of the ELU + 1 feature map (params->feature_map = COTTEN_MAP_ELU1, the
+linear-attention comparison model of the paper's section "Linear Attention Models") against the
+oracle's N x N statement of it, on the fused and split matrix-core kernels."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_06935_amd import binding
+from paper_2602_06935_amd.inputs import round_to_bf16, round_to_f16
+
+from gpu_util import bar_for, check_tensor, rel_l2, to_f64, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    ("f32", 6, 2, 200, 32),      # one workgroup per slice, tiles kept in registers
+    ("f32", 3, 2, 77, 16),       # narrower rows: the padding columns must stay zero (phi(0) = 1)
+    ("bf16", 9, 4, 200, 64),     # 16-bit: forward with kept tiles, backward streaming
+    ("bf16", 5, 2, 100, 32),
+    ("f16", 4, 2, 61, 16),
+    ("f32", 130, 2, 300, 32),    # streaming, one workgroup per slice
+    ("bf16", 66, 4, 520, 64),
+    ("f32", 2, 2, 1030, 32),     # sequence cut over several workgroups
+    ("bf16", 2, 2, 1500, 64),
+    ("f32", 1, 1, 1, 32),
+]
+
+
+def _inputs(seed, dtype, B, H, N, d):
+    rng = np.random.default_rng(seed)
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)).astype(np.float32) for _ in range(4))
+    if dtype == "bf16":
+        Q, K, V, dO = (round_to_bf16(x) for x in (Q, K, V, dO))
+    if dtype == "f16":
+        Q, K, V, dO = (round_to_f16(x) for x in (Q, K, V, dO))
+    mask = np.zeros((B, N), np.uint8)
+    for b in range(B):
+        if b % 3 == 0:
+            mask[b, N - int(rng.integers(1, N + 1)):] = 1
+        elif b % 3 == 1:
+            mask[b] = rng.random(N) < 0.5
+            mask[b, -1] = 1
+        else:
+            mask[b, : int(rng.integers(1, N + 1))] = 1
+    if B > 2:
+        mask[2] = 0                      # no valid key at all
+    return Q, K, V, dO, mask
+
+
+@pytest.mark.parametrize("dtype,B,H,N,d", CASES)
+def test_elu_feature_map(oracle, dtype, B, H, N, d):
+    print(f"[elu1] {dtype} B={B} H={H} N={N} d={d}", flush=True)
+    Q, K, V, dO, mask = _inputs(777 + N + d, dtype, B, H, N, d)
+    tq, tk, tv, tg = (to_gpu(x, dtype) for x in (Q, K, V, dO))
+    tm = torch.from_numpy(mask).cuda()
+    scale = 0.7 / N
+    S = torch.empty(B, H, d, d, device="cuda")
+    O = binding.cotten_attn_fwd(tq, tk, tv, tm, scale=scale, feature_map="elu1", saved_state=S)
+    grads = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, scale=scale, feature_map="elu1")
+    with_state = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, scale=scale, feature_map="elu1", saved_state=S)
+    again = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, scale=scale, feature_map="elu1")
+    torch.cuda.synchronize()
+    ref_o = oracle.elu_fwd(Q, K, V, mask, scale=scale)
+    ref_g = oracle.elu_bwd(Q, K, V, dO, mask, scale=scale)
+    bar = bar_for(dtype)
+    for n, g, r in zip(("O", "dQ", "dK", "dV"), (O, *grads), (ref_o, *ref_g)):
+        e = check_tensor(n, to_f64(g), r, bar)
+        print(f"[elu1]   {n}: whole {e['whole']:.2e} slice {e['slice']:.2e} row {e['row']:.2e}", flush=True)
+    for n, g, r in zip(("dQ", "dK", "dV"), with_state, ref_g):
+        check_tensor(n + " (kept state)", to_f64(g), r, bar)
+    dead = np.broadcast_to((mask == 0)[:, None, :, None], Q.shape)
+    assert np.all(to_f64(grads[1])[dead] == 0.0) and np.all(to_f64(grads[2])[dead] == 0.0)
+    if B > 2:
+        assert np.all(to_f64(O)[2] == 0.0)
+    assert all(torch.equal(a, b) for a, b in zip(grads, again))
+    # a different map gives a different answer: the flag is not ignored
+    O_cos = binding.cotten_attn_fwd(tq, tk, tv, tm, scale=scale)
+    torch.cuda.synchronize()
+    assert rel_l2(to_f64(O_cos), ref_o) > 0.1
+
+
+def test_elu_feature_map_layout_and_refusals(oracle):
+    B, H, N, d = 4, 2, 90, 32
+    Q, K, V, dO, mask = _inputs(31, "f32", B, H, N, d)
+    tq, tk, tv, tg = (to_gpu(x, "f32") for x in (Q, K, V, dO))
+    tm = torch.from_numpy(mask).cuda()
+    sw = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    O = binding.cotten_attn_fwd(tq, tk, tv, tm, feature_map="elu1")
+    O2 = binding.cotten_attn_fwd(sw(tq), sw(tk), sw(tv), tm, feature_map="elu1", layout="bnhd")
+    g = binding.cotten_attn_bwd(tq, tk, tv, tm, tg, feature_map="elu1")
+    g2 = binding.cotten_attn_bwd(sw(tq), sw(tk), sw(tv), tm, sw(tg), feature_map="elu1", layout="bnhd")
+    torch.cuda.synchronize()
+    assert torch.equal(sw(O), O2) and all(torch.equal(sw(a), b) for a, b in zip(g, g2))
+    with pytest.raises(binding.CottenError) as e:
+        binding.cotten_attn_fwd(tq, tk, tv, tm, feature_map="elu1", causal=True)
+    assert e.value.status == -7
+    big = torch.zeros(1, 1, 8, 64, device="cuda")     # fp32 d_h = 64: vector-ALU kernels only
+    with pytest.raises(binding.CottenError) as e:
+        binding.cotten_attn_fwd(big, big, big, None, feature_map="elu1")
+    assert e.value.status == -3
