@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--repeats", type=int, default=15, help="timed replays of the K-step graph")
+    ap.add_argument("--settle", type=float, default=SETTLE_SECONDS,
+                    help="seconds of untimed replays before the timed ones (short for profiler runs)")
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -171,7 +173,7 @@ def pct(sorted_ms, q):
     return sorted_ms[min(len(sorted_ms) - 1, max(0, int(round(q * (len(sorted_ms) - 1)))))]
 
 
-def measure(db, binding, torch, steps, warmup, repeats, use_graph=True, clocks=False):
+def measure(db, binding, torch, steps, warmup, repeats, use_graph=True, clocks=False, settle=SETTLE_SECONDS):
     run_steps(db, binding, warmup)
     torch.cuda.synchronize()
     if use_graph:
@@ -183,9 +185,9 @@ def measure(db, binding, torch, steps, warmup, repeats, use_graph=True, clocks=F
         step_fn = lambda: run_steps(db, binding, steps, first=warmup)
         fwd_fn = lambda: run_steps(db, binding, steps, bwd=False)
         bwd_fn = lambda: run_steps(db, binding, steps, fwd=False)
-    step_ms = timed_replays(torch, step_fn, repeats, SETTLE_SECONDS)
-    fwd_ms = timed_replays(torch, fwd_fn, repeats, SETTLE_SECONDS / 3)
-    bwd_ms = timed_replays(torch, bwd_fn, repeats, SETTLE_SECONDS / 3)
+    step_ms = timed_replays(torch, step_fn, repeats, settle)
+    fwd_ms = timed_replays(torch, fwd_fn, repeats, settle / 3)
+    bwd_ms = timed_replays(torch, bwd_fn, repeats, settle / 3)
     ms = pct(step_ms, 0.5) / steps
     fwd_us = pct(fwd_ms, 0.5) / steps * 1e3
     bwd_us = pct(bwd_ms, 0.5) / steps * 1e3
@@ -256,7 +258,9 @@ def profile_figures(workload, kernel_tags):
 
 
 def roofline_block(w, db, res):
-    prof = profile_figures(w.name, BWD_KERNELS)
+    # with the state kept by the forward the backward of a long sequence launches no state kernel
+    tags = tuple(t for t in BWD_KERNELS if not (db.keep_state and t == "split_state_kernel"))
+    prof = profile_figures(w.name, tags)
     mfma_tflops = db.flops_bwd / (res["bwd_us"] * 1e-6) / 1e12
     r4 = lambda x: round(x, 4)
     return {
@@ -343,7 +347,8 @@ def main():
     pays = lambda wl: wl.N * (2 if wl.dtype == "bf16" else 4) >= 16 * wl.d_h
     keep = (not args.rebuild_state) and pays(w)
     db = DeviceBatch(batch, torch, binding, rot, keep, args.stagger)
-    res = measure(db, binding, torch, args.steps, args.warmup, args.repeats, graph, clocks=True)
+    res = measure(db, binding, torch, args.steps, args.warmup, args.repeats, graph, clocks=not args.no_others,
+                  settle=args.settle)
     warm = None
     if not args.warm_cache and not args.no_others:
         # the same steps over ONE buffer set: inputs of the 13 MB-per-tensor workloads are then
@@ -420,7 +425,7 @@ def main():
             "launch": "python per step" if args.no_graph else "one HIP graph of K steps",
             "state": "the forward keeps the d x d state of every slice (saved_state), its backward reads it"
                      if keep else "rebuilt from K, V by the backward",
-            "timing": f"median of {args.repeats} replays of the K steps after {SETTLE_SECONDS} s of "
+            "timing": f"median of {args.repeats} replays of the K steps after {args.settle} s of "
                       "untimed replays; events on the launch stream",
         },
         "ms_per_step_p10_p90": [round(res["ms_per_step_p10"], 5), round(res["ms_per_step_p90"], 5)],
