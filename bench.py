@@ -13,9 +13,10 @@ memory-side cache twice over, and the backward of a step works on the buffer set
 rotation away from its forward, so nothing a call reads was left in a cache by the call
 before it.  K steps are recorded into one HIP graph (kernel launches only).  After the W
 warm-up steps the graph is replayed untimed for a few tenths of a second (clocks and
-caches settle whatever W is), then replayed `--repeats` times, each replay timed with
-events on the launch stream; the line carries the median replay (ms_per_step = median / K)
-and the 10th / 90th percentiles.  Forward and backward calls are timed the same way on
+caches settle whatever W is), then `--repeats` samples are timed with events on the launch
+stream, a sample being as many back-to-back replays of the K steps as last a few
+milliseconds (one for large K); the line carries the median sample (ms_per_step = median /
+steps in the sample) and the 10th / 90th percentiles.  Forward and backward calls are timed the same way on
 their own (K back-to-back launches of one direction).
 """
 from __future__ import annotations
@@ -36,6 +37,7 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # dense, publ
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 640 << 20       # rotate over at least this many bytes of tensors
 SETTLE_SECONDS = 0.3           # untimed replays before the timed ones
+MIN_SAMPLE_MS = 4.0            # a timed sample lasts at least about this long
 # Padding between neighbouring tensors in device memory.  Tensors whose base addresses differ by
 # a large power of two (the 32 MiB tensors of the N = 4096 workload, allocated back to back) put
 # the same row of every tensor into the same HBM bank, and the three or four streams a backward
@@ -91,23 +93,31 @@ class DeviceBatch:
         self.sets = []
         # All tensors are carved from one allocation, `stagger` bytes of padding between
         # neighbours (see STAGGER_BYTES).
-        stride = (self.tensor_bytes + stagger + 255) // 256 * 256
-        self.arena = torch.empty(stride * 8 * self.R + 256, dtype=torch.uint8, device="cuda")
+        code = binding.COTTEN_BF16 if w.dtype == "bf16" else binding.COTTEN_F32
+        N = batch.Q.shape[2]
+        # the caller's workspace (long sequences are cut over several workgroups per slice) and
+        # the d x d states handed from the forward to the backward of a set live in the same
+        # allocation, so that the whole layout is fixed relative to one base address
+        need = max(binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, True),
+                   binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, False))
+        state_bytes = w.B * w.H * w.d_h * w.d_h * 4 if keep_state else 0
+        pad = lambda n: (n + stagger + 255) // 256 * 256
+        stride = pad(self.tensor_bytes)
+        off_ws = stride * 8 * self.R
+        off_st = off_ws + pad(need)
+        self.arena = torch.empty(off_st + pad(state_bytes) * self.R + 256, dtype=torch.uint8, device="cuda")
         carve = lambda i: self.arena[i * stride: i * stride + self.tensor_bytes].view(self.dt).view(host[0].shape)
+        self.workspace = self.arena[off_ws: off_ws + need] if need else None
         for r in range(self.R):
             q, k, v, g = (carve(8 * r + j) for j in range(4))
             for dst, h in zip((q, k, v, g), host):
                 dst.copy_(h)
             outs = [carve(8 * r + 4 + j) for j in range(4)]    # O, dQ, dK, dV
-            # the d x d state of every slice, handed from the forward to the backward of the set
-            st = torch.zeros(w.B, w.H, w.d_h, w.d_h, device="cuda") if keep_state else None
+            st = None
+            if keep_state:
+                o = off_st + r * pad(state_bytes)
+                st = self.arena[o: o + state_bytes].view(torch.float32).view(w.B, w.H, w.d_h, w.d_h)
             self.sets.append((q, k, v, g, *outs, st))
-        # the caller's workspace (long sequences are cut over several workgroups per slice)
-        code = binding.COTTEN_BF16 if w.dtype == "bf16" else binding.COTTEN_F32
-        N = batch.Q.shape[2]
-        need = max(binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, True),
-                   binding.cotten_attn_workspace_bytes(w.B, w.H, N, w.d_h, code, False))
-        self.workspace = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
         if keep_state:     # every set's state exists before any backward is timed on its own
             for q, k, v, g, O, dQ, dK, dV, st in self.sets:
                 binding.cotten_attn_fwd(q, k, v, self.mask, O, scale=batch.scale, eps=batch.eps,
@@ -158,14 +168,23 @@ def timed_replays(torch, fn, repeats, settle_s):
         fn()
         torch.cuda.synchronize()
         n += 1
+    # a sample is `inner` back-to-back calls, enough of them to last a few milliseconds: the cost
+    # of starting a graph (tens of microseconds) would otherwise weigh on short ones
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    e1.record()
+    e1.synchronize()
+    inner = max(1, min(64, int(round(MIN_SAMPLE_MS / max(e0.elapsed_time(e1), 1e-3)))))
     ms = []
     for _ in range(repeats):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        fn()
+        for _ in range(inner):
+            fn()
         e1.record()
         e1.synchronize()
-        ms.append(e0.elapsed_time(e1))
+        ms.append(e0.elapsed_time(e1) / inner)
     return sorted(ms)
 
 
@@ -425,8 +444,8 @@ def main():
             "launch": "python per step" if args.no_graph else "one HIP graph of K steps",
             "state": "the forward keeps the d x d state of every slice (saved_state), its backward reads it"
                      if keep else "rebuilt from K, V by the backward",
-            "timing": f"median of {args.repeats} replays of the K steps after {args.settle} s of "
-                      "untimed replays; events on the launch stream",
+            "timing": f"median of {args.repeats} samples (back-to-back replays of the K steps lasting "
+                      f">= {MIN_SAMPLE_MS} ms) after {args.settle} s of untimed replays; events on the launch stream",
         },
         "ms_per_step_p10_p90": [round(res["ms_per_step_p10"], 5), round(res["ms_per_step_p90"], 5)],
         "valid_tokens_per_s": round(res["valid_tokens_per_s"], 1),

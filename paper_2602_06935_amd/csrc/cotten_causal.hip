@@ -338,8 +338,8 @@ hipError_t dispatch(const Problem& p, bool bwd) {
 bool causal_supports(int D) { return D == 16 || D == 32 || D == 64; }
 
 hipError_t launch_causal(const Problem& p, bool bwd) {
-  // short 16-bit sequences: tile pairs on the matrix cores, the slice resident in LDS
-  if (resident_supports(p.dtype, p.D, p.N)) return launch_resident_causal(p, bwd);
+  // short sequences: tile pairs on the matrix cores, the slice resident in LDS
+  if (causal_resident_supports(p.dtype, p.D, p.N)) return launch_resident_causal(p, bwd);
   return p.dtype == 0 ? dispatch<float>(p, bwd) : p.dtype == 1 ? dispatch<bf16>(p, bwd) : dispatch<f16>(p, bwd);
 }
 

@@ -84,7 +84,9 @@ hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 bool resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_fwd(const Problem& p);
 hipError_t launch_resident_bwd(const Problem& p);
-// The causal variant on the matrix cores, for the shapes resident_supports() accepts.
+// The causal variant on the matrix cores, tile pair by tile pair with the slice in LDS: every
+// element type, 128-byte rows or narrower, at most 208 rows.
+bool causal_resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_causal(const Problem& p, bool bwd);
 
 // Learnable normaliser: slice_scale[b*H+h] = n_b^(-m_h), and dm[h] = -sum_b ln(n_b) dlog[b*H+h].

@@ -308,6 +308,30 @@ struct Half64 {
     apply(X, W, out);
   }
 
+  // Products of two 16-row tiles, for the kernels that work tile pair by tile pair:
+  // dots(a, b) = X_a X_b^T: lane (j, g) gets rows 4g .. 4g+3 (rows of a) of column j (row of b).
+  static __device__ __forceinline__ f32x4_t dots(const TileRows& a, const TileRows& b) {
+    f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) d = E::mfma16(a.a[ks], b.a[ks], d);
+    return d;
+  }
+  // out += X^T P for the tile X at `T` and a 16 x 16 matrix P as dots() leaves it (rounded to
+  // the element type): a 16x16 result leaves a lane with exactly the k it holds of a 16x16x16 B
+  // operand, so P goes in without moving between lanes; X^T comes from the transposing LDS
+  // read (lane i of a 16-lane group gets rows 4g .. 4g+3 of column out_col(nt, i/4) + i%4), so
+  // the result lands in the product layout.
+  static __device__ __forceinline__ void add_transposed_product(const unsigned char* T,
+                                                                const Lane& L, f32x4_t p,
+                                                                f32x4_t (&out)[4]) {
+    const v4_t pb = E::pack4(p);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+      out[nt] = E::mfma_k16(E::read_tr(T + (4 * L.g16 + (L.i16 >> 2)) * kTileStride +
+                                       out_col(nt, L.i16 & 3) * 2),
+                            pb, out[nt]);
+  }
+
   // One 32x32 block of a state, accumulated by one wave over LDS-resident tiles
   // (block = 0..3: rows 32*(block/2).., columns 32*(block%2)..), and its way into operand images.
   struct BlockAcc {
@@ -490,6 +514,29 @@ struct F32x32 {
     TileRows X;
     X.load(T, L);
     apply(X, W, out);
+  }
+
+  // Products of two 16-row tiles (see Half64): dots(a, b) = X_a X_b^T, lane (j, g) gets rows
+  // 4g .. 4g+3 of column j; eight 16x16x4 steps, each lane feeding the column it holds.
+  static __device__ __forceinline__ f32x4_t dots(const TileRows& a, const TileRows& b) {
+    f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.a[s], b.a[s], d, 0, 0, 0);
+    return d;
+  }
+  // out += X^T P: step v contracts over the rows 4g + v (g = 0..3), which is the row of P a lane
+  // of group g holds in p[v]; the matching element of X is read from the LDS tile directly.
+  static __device__ __forceinline__ void add_transposed_product(const unsigned char* T,
+                                                                const Lane& L, f32x4_t p,
+                                                                f32x4_t (&out)[2]) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float x = *reinterpret_cast<const float*>(T + (4 * L.g16 + v) * kTileStride +
+                                                        (16 * nt + L.i16) * 4);
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x, p[v], out[nt], 0, 0, 0);
+      }
   }
 
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,

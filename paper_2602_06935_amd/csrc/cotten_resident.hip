@@ -428,26 +428,6 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
 //     dV_u^T    += dO_t^T P,    H_u^T += Qhat_t^T G     (as key tile u, over t >= u)
 // and the row-norm Jacobians as everywhere else.
 
-// The operand X^T for 16 output columns (group nt of the product layout) of the 16-row tile
-// at `T`: lane i of a 16-lane group gets rows 4g .. 4g+3 of column out_col(nt, i/4) + i%4.
-template <class F>
-__device__ __forceinline__ typename F::v4_t transposed_rows(const unsigned char* T, const Lane& L,
-                                                            int nt) {
-  return F::Elem::read_tr(T + (4 * L.g16 + (L.i16 >> 2)) * kTileStride +
-                          F::out_col(nt, L.i16 & 3) * 2);
-}
-
-// X_a X_b^T for two tiles held as TileRows: lane (j, g) gets rows 4g .. 4g+3 (rows of a) of
-// column j (row of b).
-template <class F>
-__device__ __forceinline__ f32x4_t tile_dots(const typename F::TileRows& a,
-                                             const typename F::TileRows& b) {
-  f32x4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) d = F::Elem::mfma16(a.a[ks], b.a[ks], d);
-  return d;
-}
-
 template <class F>
 __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
   const Lane L0;
@@ -480,16 +460,13 @@ __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
     const unsigned char* ub = smem + u * kBlockBytes;
     typename F::TileRows xk;
     xk.load(ub + kKt, L);
-    f32x4_t pt = tile_dots<F>(xk, xq);  // [key 4g+v][query i16]
+    f32x4_t pt = F::dots(xk, xq);  // [key 4g+v][query i16]
     if (u == tile) {
 #pragma unroll
       for (int v = 0; v < 4; ++v)
         if (4 * L.g16 + v > L.i16) pt[v] = 0.0f;
     }
-    const typename F::v4_t pb = F::Elem::pack4(pt);
-#pragma unroll
-    for (int nt = 0; nt < F::NT; ++nt)
-      out[nt] = F::Elem::mfma_k16(transposed_rows<F>(ub + kVt, L, nt), pb, out[nt]);
+    F::add_transposed_product(ub + kVt, L, pt, out);
   }
   float o[2 * F::EPL];
   product_rows<F>(out, o);
@@ -541,16 +518,13 @@ __global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
       const unsigned char* ub = smem + u * kBlockBytes;
       typename F::TileRows xv;
       xv.load(ub + kVt, L);
-      f32x4_t gt = tile_dots<F>(xv, xg);  // [key 4g+v][query i16] = v_key . dO_query
+      f32x4_t gt = F::dots(xv, xg);  // [key 4g+v][query i16] = v_key . dO_query
       if (u == tile) {
 #pragma unroll
         for (int v = 0; v < 4; ++v)
           if (4 * L.g16 + v > L.i16) gt[v] = 0.0f;
       }
-      const typename F::v4_t gb = F::Elem::pack4(gt);
-#pragma unroll
-      for (int nt = 0; nt < F::NT; ++nt)
-        acc[nt] = F::Elem::mfma_k16(transposed_rows<F>(ub + kKt, L, nt), gb, acc[nt]);
+      F::add_transposed_product(ub + kKt, L, gt, acc);
     }
     float g[2 * F::EPL];
     product_rows<F>(acc, g);
@@ -579,19 +553,15 @@ __global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
         typename F::TileRows xq, xg;
         xq.load(tb + kQt, L);
         xg.load(tb + kGt, L);
-        f32x4_t p = tile_dots<F>(xq, xk);   // [query 4g+v][key i16] = qhat_query . khat_key
-        f32x4_t gg = tile_dots<F>(xg, xv);  // [query 4g+v][key i16] = dO_query . v_key
+        f32x4_t p = F::dots(xq, xk);   // [query 4g+v][key i16] = qhat_query . khat_key
+        f32x4_t gg = F::dots(xg, xv);  // [query 4g+v][key i16] = dO_query . v_key
         if (t == tile) {
 #pragma unroll
           for (int v = 0; v < 4; ++v)
             if (L.i16 > 4 * L.g16 + v) p[v] = gg[v] = 0.0f;
         }
-        const typename F::v4_t pb = F::Elem::pack4(p), gb = F::Elem::pack4(gg);
-#pragma unroll
-        for (int nt = 0; nt < F::NT; ++nt) {
-          av[nt] = F::Elem::mfma_k16(transposed_rows<F>(tb + kGt, L, nt), pb, av[nt]);
-          ah[nt] = F::Elem::mfma_k16(transposed_rows<F>(tb + kQt, L, nt), gb, ah[nt]);
-        }
+        F::add_transposed_product(tb + kGt, L, p, av);
+        F::add_transposed_product(tb + kQt, L, gg, ah);
       }
       product_rows<F>(av, dv);
       product_rows<F>(ah, dk);
@@ -699,8 +669,15 @@ bool resident_supports(int dtype, int D, int N) {
   return (dtype == 1 || dtype == 2) && (D == 64 || D == 32 || D == 16) && N <= kMaxTiles * mfma::TR;
 }
 
+bool causal_resident_supports(int dtype, int D, int N) {
+  if (N > kMaxTiles * mfma::TR) return false;
+  return dtype == 0 ? (D == 32 || D == 16) : (D == 64 || D == 32 || D == 16);
+}
+
 hipError_t launch_resident_causal(const Problem& p, bool bwd) {
-  return p.dtype == 1 ? run_causal<Bf16x64>(p, bwd) : run_causal<F16x64>(p, bwd);
+  return p.dtype == 0   ? run_causal<F32x32>(p, bwd)
+         : p.dtype == 1 ? run_causal<Bf16x64>(p, bwd)
+                        : run_causal<F16x64>(p, bwd);
 }
 
 hipError_t launch_resident_fwd(const Problem& p) {
