@@ -152,9 +152,11 @@ typedef struct cotten_params {
                              Forward: written when given.  Backward: when given, read instead
                              of rebuilding S from K and V (one pass over K, V less); results
                              agree with the rebuilding call to fp32 rounding of S.  The
-                             vector-ALU kernels (fp32 d_h = 64, d_h = 128) and a backward call
-                             that also asks for dlog_scale rebuild S all the same; the causal
-                             variant has no such state and ignores the field              */
+                             vector-ALU kernels (fp32 d_h = 64, d_h = 128), the 16-bit backward
+                             for N <= 208 (its slice sits in LDS, rebuilding costs no memory
+                             traffic) and a backward call that also asks for dlog_scale rebuild
+                             S all the same; the causal variant has no such state and ignores
+                             the field                                                     */
   int feature_map;        /* a cotten_feature_map: what is done to the rows of Q and K    */
 } cotten_params;
 
@@ -166,8 +168,8 @@ int cotten_attn_fwd(const void* Q, const void* K, const void* V, const uint8_t* 
 
 /* Backward of the same expression: given dO writes dQ, dK, dV (formulas above).
  * fp32 I/O, scale = 1/N, eps = 1e-6.  The state S is rebuilt from K, V; nothing
- * saved by the forward call is needed (cotten_params.saved_state offers the other way).  Shapes for which
- * cotten_attn_workspace_bytes() is not 0 need the _ex form. */
+ * saved by the forward call is needed (cotten_params.saved_state offers the other way).
+ * Shapes for which cotten_attn_workspace_bytes() is not 0 need the _ex form. */
 int cotten_attn_bwd(const void* Q, const void* K, const void* V, const uint8_t* mask,
                     const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N,
                     int d_h, void* stream);
