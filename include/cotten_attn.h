@@ -142,8 +142,10 @@ typedef struct cotten_params {
   int causal;             /* 0: bidirectional (the paper's model).  1: row i attends only the
                              valid keys j <= i (the variant the paper's model leaves out, "no
                              causal mask"): O_i = scale * qhat_i sum_{j<=i} m_j khat_j^T v_j
-                             and its exact gradients.  d_h in {16, 32, 64}; no workspace;
-                             dlog_scale is not available (COTTEN_ERR_BAD_PARAM)            */
+                             and its exact gradients.  d_h in {16, 32, 64}; sequences of more
+                             than 208 rows need the workspace that
+                             cotten_attn_workspace_bytes_ex() reports; dlog_scale is not
+                             available (COTTEN_ERR_BAD_PARAM)                              */
   float* saved_state;     /* device, [B*H, d_h, d_h] floats, 16-byte aligned, or NULL.  The state
                              S = sum_j m_j khat_j^T v_j of every slice (row a, column c; without
                              the scale), kept by the caller from the forward call to the
@@ -220,6 +222,14 @@ int cotten_normaliser_bwd(const float* dlog_scale, const int32_t* n, float* dm, 
  * never like N*d_h or N^2: the method keeps only the d_h x d_h state ("Memory and
  * Compute Complexity"). */
 size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd);
+
+/* The same for a call with these params (dtype, causal and feature_map are looked at): what
+ * params->workspace must hold.  Differs from the function above for the causal variant, whose
+ * sequences of more than 208 rows pass one d x d state per 208-row chunk and slice through the
+ * workspace (two in the backward call).  0 for invalid arguments or params == NULL.  Host
+ * only, no device work. */
+size_t cotten_attn_workspace_bytes_ex(int B, int H, int N, int d_h, int is_bwd,
+                                      const cotten_params* params);
 
 /* Static, NUL-terminated description of a status code. */
 const char* cotten_status_string(int status);

@@ -33,6 +33,7 @@ EXPORTS = (
     "cotten_attn_fwd", "cotten_attn_bwd", "cotten_attn_fwd_ex", "cotten_attn_bwd_ex",
     "cotten_attn_workspace_bytes", "cotten_status_string",
     "cotten_normaliser_fwd", "cotten_normaliser_bwd", "cotten_attn_bwd_static",
+    "cotten_attn_workspace_bytes_ex",
 )
 
 
@@ -75,6 +76,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
         f.restype = ctypes.c_int
     lib.cotten_attn_workspace_bytes.argtypes = [ip, ip, ip, ip, ip, ip]
     lib.cotten_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.cotten_attn_workspace_bytes_ex.argtypes = [ip, ip, ip, ip, ip, ctypes.POINTER(CottenParams)]
+    lib.cotten_attn_workspace_bytes_ex.restype = ctypes.c_size_t
     lib.cotten_normaliser_fwd.argtypes = [vp, vp, vp, ip, ip, ip, vp]
     lib.cotten_normaliser_bwd.argtypes = [vp, vp, vp, ip, ip, ip, vp]
     lib.cotten_normaliser_fwd.restype = lib.cotten_normaliser_bwd.restype = ctypes.c_int
@@ -90,6 +93,16 @@ def cotten_status_string(status: int) -> str:
 
 def cotten_attn_workspace_bytes(B: int, H: int, N: int, d_h: int, dtype: int, is_bwd: bool) -> int:
     return int(load_library().cotten_attn_workspace_bytes(B, H, N, d_h, dtype, int(bool(is_bwd))))
+
+
+def cotten_attn_workspace_bytes_ex(B: int, H: int, N: int, d_h: int, is_bwd: bool, *, dtype: int,
+                                   causal: bool = False) -> int:
+    """Workspace bytes of a call with these options (the causal variant has needs of its own)."""
+    prm = CottenParams()
+    prm.dtype = dtype
+    prm.causal = 1 if causal else 0
+    return int(load_library().cotten_attn_workspace_bytes_ex(B, H, N, d_h, int(bool(is_bwd)),
+                                                             ctypes.byref(prm)))
 
 
 def _check(status: int) -> None:
@@ -181,12 +194,12 @@ _retired = []       # outgrown buffers: work already enqueued may still use them
 
 
 def _workspace(Q: torch.Tensor, dims, is_bwd: bool, stream_handle: int,
-               given: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+               given: Optional[torch.Tensor], causal: bool = False) -> Optional[torch.Tensor]:
     """The workspace tensor of a call: the caller's, or one of this module's."""
     if given is not None:
         return given
     B, H, N, d = dims
-    need = cotten_attn_workspace_bytes(B, H, N, d, _dtype_code(Q), is_bwd)
+    need = cotten_attn_workspace_bytes_ex(B, H, N, d, is_bwd, dtype=_dtype_code(Q), causal=causal)
     if need == 0:
         return None
     with torch.cuda.device(Q.device):
@@ -230,8 +243,7 @@ def cotten_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
         O = torch.empty_like(Q)
     _prep("O", O, Q)
     handle = _stream_handle(stream)
-    if not causal:
-        workspace = _workspace(Q, (B, H, N, d), False, handle, workspace)
+    workspace = _workspace(Q, (B, H, N, d), False, handle, workspace, causal)
     prm = _params(Q, scale, eps, workspace, slice_scale, None, layout, causal, saved_state, feature_map)
     with torch.cuda.device(Q.device):
         _check(lib.cotten_attn_fwd_ex(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
@@ -267,8 +279,8 @@ def cotten_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
     handle = _stream_handle(stream)
     if static_scratch:
         workspace = None
-    elif not causal:
-        workspace = _workspace(Q, (B, H, N, d), True, handle, workspace)
+    else:
+        workspace = _workspace(Q, (B, H, N, d), True, handle, workspace, causal)
     prm = _params(Q, scale, eps, workspace, slice_scale, dlog_scale, layout, causal, saved_state,
                   feature_map)
     entry = lib.cotten_attn_bwd_static if static_scratch else lib.cotten_attn_bwd_ex

@@ -110,20 +110,16 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
     if (!cotten::mfma_supports(prm->dtype, d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
   }
   p.feature_map = prm->feature_map;
-  if (prm->causal != 0) {
+  const bool causal = prm->causal != 0;
+  if (causal) {
     if (prm->causal != 1 || (bwd && prm->dlog_scale != nullptr)) return COTTEN_ERR_BAD_PARAM;
     if (!cotten::causal_supports(d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
-    p.slice_scale = prm->slice_scale;
-    p.Q = Q; p.K = K; p.V = V; p.mask = mask; p.dO = dO;
-    p.O = O; p.dQ = dQ; p.dK = dK; p.dV = dV;
-    p.B = B; p.H = H; p.N = N; p.D = d_h;
-    p.dtype = prm->dtype;
-    p.stream = static_cast<hipStream_t>(stream);
-    return cotten::launch_causal(p, bwd) == hipSuccess ? COTTEN_OK : COTTEN_ERR_LAUNCH;
   }
-  const cotten::Plan plan =
-      cotten::make_plan(B, H, N, d_h, prm->dtype, bwd, prm->feature_map == COTTEN_MAP_COSINE);
-  const size_t need = plan.workspace_floats * sizeof(float);
+  cotten::Plan plan{};
+  if (!causal)
+    plan = cotten::make_plan(B, H, N, d_h, prm->dtype, bwd, prm->feature_map == COTTEN_MAP_COSINE);
+  const size_t need = sizeof(float) * (causal ? cotten::causal_workspace_floats(B, H, N, d_h, prm->dtype, bwd)
+                                              : plan.workspace_floats);
   if (use_static_scratch) {
     if (need > COTTEN_STATIC_SCRATCH_BYTES) return COTTEN_ERR_STATIC_SCRATCH;
     if (need > 0) {
@@ -145,7 +141,9 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
   p.dtype = prm->dtype;
   p.stream = static_cast<hipStream_t>(stream);
   hipError_t err;
-  if (plan.path == cotten::Plan::kGeneric)
+  if (causal)  // no kept state, no dlog_scale (refused above)
+    err = cotten::launch_causal(p, bwd);
+  else if (plan.path == cotten::Plan::kGeneric)
     err = bwd ? cotten::launch_generic_bwd(p, plan) : cotten::launch_generic_fwd(p, plan);
   else if (plan.path == cotten::Plan::kResident)
     err = bwd ? cotten::launch_resident_bwd(p) : cotten::launch_resident_fwd(p);
@@ -250,6 +248,16 @@ int cotten_normaliser_bwd(const float* dlog_scale, const int32_t* n, float* dm, 
 size_t cotten_attn_workspace_bytes(int B, int H, int N, int d_h, int dtype, int is_bwd) {
   if (check_shape(B, H, N, d_h, dtype) != COTTEN_OK) return 0;
   return cotten::make_plan(B, H, N, d_h, dtype, is_bwd != 0).workspace_floats * sizeof(float);
+}
+
+size_t cotten_attn_workspace_bytes_ex(int B, int H, int N, int d_h, int is_bwd,
+                                      const cotten_params* params) {
+  if (params == nullptr || check_shape(B, H, N, d_h, params->dtype) != COTTEN_OK) return 0;
+  if (params->causal != 0)
+    return cotten::causal_supports(d_h)
+               ? cotten::causal_workspace_floats(B, H, N, d_h, params->dtype, is_bwd != 0) * sizeof(float)
+               : 0;
+  return cotten_attn_workspace_bytes(B, H, N, d_h, params->dtype, is_bwd);
 }
 
 const char* cotten_status_string(int status) {

@@ -17,7 +17,10 @@
 //     h_c  = V_c T_after^T  + scale * G^T Qhat_c               -> dK
 //
 // Vector-ALU kernels, one workgroup of 256 threads per slice, any supported element type,
-// d_h in {16, 32, 64}.  Not tuned: the bidirectional kernels are the benchmarked path.
+// d_h in {16, 32, 64}.  Not tuned: the bidirectional kernels are the benchmarked path.  They
+// serve the shapes the matrix-core kernels do not take (fp32 d_h = 64); every other call is
+// routed to those by launch_causal() below, which for sequences of more than one chunk also
+// launches the scan over the chunk states defined at the end of this file.
 #include "cotten_device.h"
 #include "cotten_launch.h"
 
@@ -323,24 +326,80 @@ hipError_t run(const Problem& p, bool bwd) {
   return hipGetLastError();
 }
 
-template <typename T>
-hipError_t dispatch(const Problem& p, bool bwd) {
-  switch (p.D) {
-    case 16: return run<T, 16>(p, bwd);
-    case 32: return run<T, 32>(p, bwd);
-    case 64: return run<T, 64>(p, bwd);
-    default: return hipErrorInvalidValue;
+// Chunked matrix-core path: the states of the chunks, [slice][chunk][dd] floats, become in
+// place the sums a chunk needs.  Block row 0: every S_c is replaced by the sum of the S before
+// chunk c, added in chunk order; block row 1 (backward): every T_c, stored behind all the S,
+// by the sum of the T after chunk c, added from the last chunk down.  One thread per four
+// consecutive floats of a state; the values of up to kAhead chunks are requested together.
+// The last S and the first T were never written and are not read.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kThreads) void chunk_scan_kernel(float* states, int slices, int chunks,
+                                                              int quads) {
+  constexpr int kAhead = 8;
+  const int id = blockIdx.x * kThreads + threadIdx.x;
+  if (id >= slices * quads) return;
+  const bool downwards = blockIdx.y == 1;
+  f32x4_t* base = reinterpret_cast<f32x4_t*>(states) +
+                  (static_cast<size_t>(blockIdx.y) * slices + id / quads) * chunks * quads + id % quads;
+  f32x4_t run = {0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < chunks; s0 += kAhead) {
+    f32x4_t own[kAhead];
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      const int step = s0 + j;  // chunk `step` counted from the end the sum starts at
+      own[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (step < chunks - 1)
+        own[j] = base[static_cast<size_t>(downwards ? chunks - 1 - step : step) * quads];
+    }
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      const int step = s0 + j;
+      if (step < chunks) {
+        base[static_cast<size_t>(downwards ? chunks - 1 - step : step) * quads] = run;
+        run += own[j];
+      }
+    }
   }
 }
 
 }  // namespace
 
+hipError_t launch_chunk_scan(float* states, int slices, int chunks, int dd, bool with_queries,
+                             hipStream_t stream) {
+  const int quads = dd / 4;
+  const dim3 grid((static_cast<unsigned>(slices) * quads + kThreads - 1) / kThreads,
+                  with_queries ? 2 : 1);
+  hipLaunchKernelGGL(chunk_scan_kernel, grid, dim3(kThreads), 0, stream, states, slices, chunks, quads);
+  return hipGetLastError();
+}
+
 bool causal_supports(int D) { return D == 16 || D == 32 || D == 64; }
 
+size_t causal_workspace_floats(int B, int H, int N, int D, int dtype, bool is_bwd) {
+  const int chunks = causal_chunks(N);
+  if (chunks < 2 || !causal_resident_supports(dtype, D)) return 0;
+  const size_t side = static_cast<size_t>(mfma_state_dim(dtype));
+  return static_cast<size_t>(B) * H * chunks * side * side * (is_bwd ? 2 : 1);
+}
+
 hipError_t launch_causal(const Problem& p, bool bwd) {
-  // short sequences: tile pairs on the matrix cores, the slice resident in LDS
-  if (causal_resident_supports(p.dtype, p.D, p.N)) return launch_resident_causal(p, bwd);
-  return p.dtype == 0 ? dispatch<float>(p, bwd) : p.dtype == 1 ? dispatch<bf16>(p, bwd) : dispatch<f16>(p, bwd);
+  if (!causal_resident_supports(p.dtype, p.D)) {
+    // the one shape left to the scan; its other instances would be reached by no call
+    if (p.dtype != 0 || p.D != 64) return hipErrorInvalidValue;
+    return run<float, 64>(p, bwd);
+  }
+  // tile pairs on the matrix cores, up to 208 rows resident in LDS per workgroup
+  const int chunks = causal_chunks(p.N);
+  if (chunks > 1) {
+    if (p.workspace == nullptr) return hipErrorInvalidValue;
+    const int side = mfma_state_dim(p.dtype);
+    hipError_t err = launch_chunk_states(p, kCausalChunkRows / 16, chunks, bwd);
+    if (err != hipSuccess) return err;
+    err = launch_chunk_scan(p.workspace, p.B * p.H, chunks, side * side, bwd, p.stream);
+    if (err != hipSuccess) return err;
+  }
+  return launch_resident_causal(p, bwd, chunks);
 }
 
 }  // namespace cotten

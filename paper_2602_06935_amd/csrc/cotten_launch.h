@@ -84,10 +84,22 @@ hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan);
 bool resident_supports(int dtype, int D, int N);
 hipError_t launch_resident_fwd(const Problem& p);
 hipError_t launch_resident_bwd(const Problem& p);
-// The causal variant on the matrix cores, tile pair by tile pair with the slice in LDS: every
-// element type, 128-byte rows or narrower, at most 208 rows.
-bool causal_resident_supports(int dtype, int D, int N);
-hipError_t launch_resident_causal(const Problem& p, bool bwd);
+// The causal variant on the matrix cores, tile pair by tile pair with up to 208 rows in LDS: every
+// element type, 128-byte rows or narrower.  Longer sequences are cut into chunks of 208 rows,
+// one workgroup each; what a chunk gets from the chunks before it (and, in the backward, gives
+// to the chunks after it) travels as d x d states through the workspace:
+//   launch_chunk_states    state of every chunk on its own, [S_c of all slices][T_c of all slices]
+//                          (T_c = sum of qhat^T dO over the chunk, backward only), each
+//                          [slice][chunk][D*D] floats with D = mfma_state_dim(dtype)
+//   launch_chunk_scan      in place: S_c <- sum of the S before chunk c, T_c <- sum of the T after it
+//   launch_resident_causal the chunk kernels, reading those sums (chunks == 1: no workspace)
+bool causal_resident_supports(int dtype, int D);
+constexpr int kCausalChunkRows = 208;
+inline int causal_chunks(int N) { return (N + kCausalChunkRows - 1) / kCausalChunkRows; }
+hipError_t launch_chunk_states(const Problem& p, int chunk_tiles, int chunks, bool with_queries);
+hipError_t launch_chunk_scan(float* states, int slices, int chunks, int dd, bool with_queries,
+                             hipStream_t stream);
+hipError_t launch_resident_causal(const Problem& p, bool bwd, int chunks);
 
 // Learnable normaliser: slice_scale[b*H+h] = n_b^(-m_h), and dm[h] = -sum_b ln(n_b) dlog[b*H+h].
 // n may be nullptr (n_b = N).
@@ -96,8 +108,11 @@ hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_
 hipError_t launch_normaliser_bwd(const float* dlog, const int32_t* n, float* dm, int B, int H,
                                  int N, hipStream_t stream);
 
-// Causal variant (row i attends keys j <= i): vector-ALU scan kernels, d_h in {16, 32, 64}.
+// Causal variant (row i attends keys j <= i), d_h in {16, 32, 64}: the matrix-core kernels above
+// where the rows are 128 bytes or narrower, vector-ALU scan kernels otherwise (fp32 d_h = 64).
+// causal_workspace_floats: what p.workspace must hold for the call (0: none needed).
 bool causal_supports(int D);
+size_t causal_workspace_floats(int B, int H, int N, int D, int dtype, bool is_bwd);
 hipError_t launch_causal(const Problem& p, bool bwd);
 
 }  // namespace cotten

@@ -68,4 +68,10 @@ hipError_t launch_mfma_bwd(const Problem& p, const Plan& plan) {
                         : stream4::run_bwd<F32x32>(p, plan);
 }
 
+hipError_t launch_chunk_states(const Problem& p, int chunk_tiles, int chunks, bool with_queries) {
+  return p.dtype == 1   ? stream4::run_chunk_states<Bf16x64>(p, chunk_tiles, chunks, with_queries)
+         : p.dtype == 2 ? stream4::run_chunk_states<F16x64>(p, chunk_tiles, chunks, with_queries)
+                        : stream4::run_chunk_states<F32x32>(p, chunk_tiles, chunks, with_queries);
+}
+
 }  // namespace cotten

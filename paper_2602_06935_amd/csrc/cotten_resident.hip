@@ -55,6 +55,11 @@ struct Args {
   // backward call ([slices][d][d] floats, row-major, without the scale), or nullptr
   float* saved;
   int d;                // head dimension (states are D x D, zero beyond d)
+  // causal variant on sequences cut into chunks of kMaxTiles tiles: workgroup = (slice, chunk);
+  // [slice][chunk][D*D] floats each, row-major, without the scale
+  int chunks;
+  const float* before;  // sum over the chunks before this one of khat^T v   (chunks > 1)
+  const float* after;   // sum over the chunks after this one of qhat^T dO   (chunks > 1, backward)
 };
 
 // The wave's tile: rows 16*tile + r8 + 8h.  `want` bit h: the row takes part.
@@ -427,18 +432,73 @@ __global__ __launch_bounds__(kThreads) void resident_bwd_kernel(const Args a) {
 //     dQhat_t^T += Khat_u^T G^T                         (as query tile t, over u <= t)
 //     dV_u^T    += dO_t^T P,    H_u^T += Qhat_t^T G     (as key tile u, over t >= u)
 // and the row-norm Jacobians as everywhere else.
+//
+// Longer sequences are cut into chunks of kMaxTiles tiles, one workgroup per chunk, wave w on
+// tile w of the chunk.  The pairs inside the chunk are done as above; everything before the
+// chunk reaches its queries through one state, S_before = sum of khat^T v over the earlier
+// chunks (O_t += Q_t S_before, dQhat_t += dO_t S_before^T), and its keys are reached by everything
+// after the chunk through T_after = sum of qhat^T dO over the later chunks (dV_u += Khat_u T_after,
+// H_u += V_u T_after^T): apply products against operand images, as in the bidirectional kernels.
+
+// The 2 x 2 block of a row-major D x D state in global memory that a thread carries into the
+// operand images (threads beyond D*D/4 carry nothing).
+template <class F>
+struct StateBlock {
+  float v[2][2];
+  __device__ __forceinline__ void fetch(const float* __restrict__ M) {
+    const int e = threadIdx.x;
+    if (e >= F::D * F::D / 4) return;
+    const int m = 2 * (e / (F::D / 2)), n = 2 * (e % (F::D / 2));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float2 r = *reinterpret_cast<const float2*>(M + (m + i) * F::D + n);
+      v[i][0] = r.x;
+      v[i][1] = r.y;
+    }
+  }
+  // natural: op[m][n] = M[m][n] (products contracting over n); transposed: op[n][m] = M[m][n]
+  __device__ __forceinline__ void write(unsigned char* natural, unsigned char* transposed) const {
+    const int e = threadIdx.x;
+    if (e >= F::D * F::D / 4) return;
+    const int m = 2 * (e / (F::D / 2)), n = 2 * (e % (F::D / 2));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if (natural != nullptr) F::write_image_pair(natural, m + i, n, v[i][0], v[i][1]);
+      if (transposed != nullptr) F::write_image_pair(transposed, n + i, m, v[0][i], v[1][i]);
+    }
+  }
+};
+
+// Which slice and chunk a workgroup of the causal kernels works on, and the wave's tile.
+struct ChunkId {
+  int slice, chunk, tile;  // tile: of the slice
+  size_t state;            // offset of the chunk's states in Args::before / Args::after
+  __device__ __forceinline__ ChunkId(const Args& a, int wave, int dd) {
+    slice = blockIdx.x / a.chunks;
+    chunk = blockIdx.x % a.chunks;
+    tile = chunk * kMaxTiles + wave;
+    state = static_cast<size_t>(blockIdx.x) * dd;
+  }
+};
 
 template <class F>
 __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
   const Lane L0;
-  const int N = a.N, tile = L0.wave, slice = blockIdx.x;
+  const ChunkId id(a, L0.wave, F::D * F::D);
+  const int N = a.N, tile = L0.wave, slice = id.slice;
   const int n_tiles = (N + TR - 1) / TR;
   unsigned char* blk = smem + tile * kBlockBytes;
+  unsigned char* image = smem + Lds<F>::kImages;
   int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
   float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv) + tile * 2 * TR;
-  const bool mine = tile < n_tiles;
+  const bool mine = tile < kMaxTiles && id.tile < n_tiles;  // the other waves only help with the image
+  const bool carried = id.chunk > 0;  // uniform over the workgroup
+  StateBlock<F> before;
+  if (carried) before.fetch(a.before + id.state);
   Raw rq, rk;
-  fetch<false>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  const int from = mine ? slice : a.slices;  // a slice that does not exist: nothing is loaded
+  fetch<false>(rq, rk, a, L0, from, id.tile, key_rows(a, L0, from, id.tile));
+  if (carried) before.write(nullptr, image);  // O = q S: contraction over the rows of S
   if (mine) {
     float inv[2];
     const bool any_key = __ballot(rk.live != 0) != 0;
@@ -453,8 +513,14 @@ __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
   typename F::TileRows xq;
   xq.load(blk + kQt, L);
   f32x4_t out[F::NT];
+  if (carried) {
+    typename F::Operand S;
+    S.load(image, L);
+    F::apply(xq, S, out);
+  } else {
 #pragma unroll
-  for (int nt = 0; nt < F::NT; ++nt) out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < F::NT; ++nt) out[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
   for (int u = 0; u <= tile; ++u) {
     if (live[u] == 0) continue;  // no valid key in the tile (uniform)
     const unsigned char* ub = smem + u * kBlockBytes;
@@ -473,7 +539,7 @@ __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
   const float factor = invs[L.i16] * (a.scales != nullptr ? a.scales[slice] : a.scale);
 #pragma unroll
   for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= factor;
-  const int row = tile * TR + L.i16;
+  const int row = id.tile * TR + L.i16;
   if (row < N)
     store_product_row<F, kStoreStreamed>(a.O + a.st.slice_base(slice, a.H), row, a.st.row, L, o);
 }
@@ -481,14 +547,28 @@ __global__ __launch_bounds__(kThreads) void causal_fwd_kernel(const Args a) {
 template <class F>
 __global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
   const Lane L0;
-  const int N = a.N, tile = L0.wave, slice = blockIdx.x;
+  const ChunkId id(a, L0.wave, F::D * F::D);
+  const int N = a.N, tile = L0.wave, slice = id.slice;
   const int n_tiles = (N + TR - 1) / TR;
+  // the tiles of the chunk that exist: the partners of a key tile end there
+  const int chunk_tiles = n_tiles - id.chunk * kMaxTiles < kMaxTiles ? n_tiles - id.chunk * kMaxTiles
+                                                                      : kMaxTiles;
   unsigned char* blk = smem + tile * kBlockBytes;
+  unsigned char* image_s = smem + Lds<F>::kImages;         // S_before, natural
+  unsigned char* image_tv = image_s + F::kImageBytes;      // T_after, transposed
+  unsigned char* image_th = image_tv + F::kImageBytes;     // T_after, natural
   int* live = reinterpret_cast<int*>(smem + Lds<F>::kLive);
   float* invs = reinterpret_cast<float*>(smem + Lds<F>::kInv) + tile * 2 * TR;
-  const bool mine = tile < n_tiles;
+  const bool mine = tile < chunk_tiles;  // the other waves only help with the images
+  const bool carried = id.chunk > 0, followed = id.chunk < a.chunks - 1;  // uniform
+  StateBlock<F> before, after;
+  if (carried) before.fetch(a.before + id.state);
+  if (followed) after.fetch(a.after + id.state);
   Raw rq, rk;
-  fetch<true>(rq, rk, a, L0, slice, tile, key_rows(a, L0, slice, tile));
+  const int from = mine ? slice : a.slices;  // a slice that does not exist: nothing is loaded
+  fetch<true>(rq, rk, a, L0, from, id.tile, key_rows(a, L0, from, id.tile));
+  if (carried) before.write(image_s, nullptr);    // dO S^T: contraction over the columns of S
+  if (followed) after.write(image_th, image_tv);  // v T^T over columns, khat T over rows
   if (mine) {
     float inv[2];
     stage<F, kXNormalized, true>(rq, L0, a.eps, blk + kQt, blk + kGt, inv);
@@ -505,14 +585,20 @@ __global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
   const Lane L = L0.again();
   const size_t base = a.st.slice_base(slice, a.H);
   const float scale = a.scales != nullptr ? a.scales[slice] : a.scale;
-  const int row = tile * TR + L.i16;
+  const int row = id.tile * TR + L.i16;
 
   {  // as query tile: dQ
     typename F::TileRows xg;
     xg.load(blk + kGt, L);
     f32x4_t acc[F::NT];
+    if (carried) {
+      typename F::Operand S;
+      S.load(image_s, L);
+      F::apply(xg, S, acc);
+    } else {
 #pragma unroll
-    for (int nt = 0; nt < F::NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      for (int nt = 0; nt < F::NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
     for (int u = 0; u <= tile; ++u) {
       if (live[u] == 0) continue;
       const unsigned char* ub = smem + u * kBlockBytes;
@@ -546,9 +632,17 @@ __global__ __launch_bounds__(kThreads) void causal_bwd_kernel(const Args a) {
       xk.load(blk + kKt, L);
       xv.load(blk + kVt, L);
       f32x4_t av[F::NT], ah[F::NT];
+      if (followed) {
+        typename F::Operand T;
+        T.load(image_tv, L);
+        F::apply(xk, T, av);
+        T.load(image_th, L);
+        F::apply(xv, T, ah);
+      } else {
 #pragma unroll
-      for (int nt = 0; nt < F::NT; ++nt) av[nt] = ah[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      for (int t = tile; t < n_tiles; ++t) {
+        for (int nt = 0; nt < F::NT; ++nt) av[nt] = ah[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      }
+      for (int t = tile; t < chunk_tiles; ++t) {
         const unsigned char* tb = smem + t * kBlockBytes;
         typename F::TileRows xq, xg;
         xq.load(tb + kQt, L);
@@ -650,9 +744,15 @@ hipError_t run(const Problem& p, bool bwd) {
 }  // namespace
 
 template <class F>
-hipError_t run_causal(const Problem& p, bool bwd) {
-  const Args a = make_args(p);
-  const dim3 grid(static_cast<unsigned>(a.slices));
+hipError_t run_causal(const Problem& p, bool bwd, int chunks) {
+  Args a = make_args(p);
+  a.chunks = chunks;
+  if (chunks > 1) {
+    if (p.workspace == nullptr) return hipErrorInvalidValue;
+    a.before = p.workspace;
+    a.after = p.workspace + static_cast<size_t>(a.slices) * chunks * F::D * F::D;
+  }
+  const dim3 grid(static_cast<unsigned>(a.slices) * chunks);
   const size_t lds = Lds<F>::kBytes;
   const void* kern = bwd ? reinterpret_cast<const void*>(causal_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(causal_fwd_kernel<F>);
@@ -669,15 +769,17 @@ bool resident_supports(int dtype, int D, int N) {
   return (dtype == 1 || dtype == 2) && (D == 64 || D == 32 || D == 16) && N <= kMaxTiles * mfma::TR;
 }
 
-bool causal_resident_supports(int dtype, int D, int N) {
-  if (N > kMaxTiles * mfma::TR) return false;
+static_assert(kCausalChunkRows == kMaxTiles * mfma::TR, "chunk = what the LDS holds");
+
+bool causal_resident_supports(int dtype, int D) {
   return dtype == 0 ? (D == 32 || D == 16) : (D == 64 || D == 32 || D == 16);
 }
 
-hipError_t launch_resident_causal(const Problem& p, bool bwd) {
-  return p.dtype == 0   ? run_causal<F32x32>(p, bwd)
-         : p.dtype == 1 ? run_causal<Bf16x64>(p, bwd)
-                        : run_causal<F16x64>(p, bwd);
+hipError_t launch_resident_causal(const Problem& p, bool bwd, int chunks) {
+  if (chunks != causal_chunks(p.N)) return hipErrorInvalidValue;
+  return p.dtype == 0   ? run_causal<F32x32>(p, bwd, chunks)
+         : p.dtype == 1 ? run_causal<Bf16x64>(p, bwd, chunks)
+                        : run_causal<F16x64>(p, bwd, chunks);
 }
 
 hipError_t launch_resident_fwd(const Problem& p) {

@@ -125,6 +125,34 @@ def test_workspace_rules(lib):
                                       16, 4, 4096, 64, None, ctypes.byref(p)) == -5
 
 
+def test_causal_workspace_rules(lib):
+    """The causal variant passes one d x d state per 208-row chunk and slice through the
+    workspace (two in the backward call) once a sequence has more than one chunk; the sizing
+    function that looks at the params says so, and a call without it is refused on the host."""
+    f = binding.cotten_attn_workspace_bytes_ex
+    BF, F32 = binding.COTTEN_BF16, binding.COTTEN_F32
+    assert f(4, 2, 208, 64, True, dtype=BF, causal=True) == 0
+    assert f(4, 2, 209, 64, False, dtype=BF, causal=True) == 4 * 2 * 2 * 64 * 64 * 4
+    assert f(4, 2, 209, 64, True, dtype=BF, causal=True) == 2 * 4 * 2 * 2 * 64 * 64 * 4
+    assert f(4, 2, 1000, 16, True, dtype=BF, causal=True) == 2 * 4 * 2 * 5 * 64 * 64 * 4   # padded states
+    assert f(3, 2, 4096, 32, False, dtype=F32, causal=True) == 3 * 2 * 20 * 32 * 32 * 4
+    assert f(3, 2, 4096, 64, True, dtype=F32, causal=True) == 0          # vector-ALU scan: none
+    assert f(3, 2, 4096, 128, True, dtype=F32, causal=True) == 0         # not available at all
+    # without the causal flag it is the plain function
+    for args in [(16, 4, 4096, 64, BF), (256, 2, 200, 32, F32)]:
+        for bwd in (False, True):
+            assert f(*args[:4], bwd, dtype=args[4]) == binding.cotten_attn_workspace_bytes(*args, bwd)
+    assert lib.cotten_attn_workspace_bytes_ex(4, 2, 300, 64, 1, None) == 0
+    ptrs = (0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000, 0x7000)
+    need = f(4, 2, 300, 64, True, dtype=BF, causal=True)
+    p = binding.CottenParams(BF, 0.0, -1.0, None, 0)
+    p.causal = 1
+    assert lib.cotten_attn_bwd_ex(*ptrs, 4, 2, 300, 64, None, ctypes.byref(p)) == -6
+    assert lib.cotten_attn_fwd_ex(*ptrs[:5], 4, 2, 300, 64, None, ctypes.byref(p)) == -6
+    p.workspace, p.workspace_bytes = 0x10000, need - 4
+    assert lib.cotten_attn_bwd_ex(*ptrs, 4, 2, 300, 64, None, ctypes.byref(p)) == -6
+
+
 def test_library_never_allocates_a_workspace(lib):
     """A shape that needs a workspace and comes without one is refused on the host, before any
     device work: with params->workspace NULL, and through the plain entry points, which have
