@@ -154,7 +154,8 @@ typedef struct cotten_params {
                              Forward: written when given.  Backward: when given, read instead
                              of rebuilding S from K and V (one pass over K, V less); results
                              agree with the rebuilding call to fp32 rounding of S.  The
-                             vector-ALU kernels (fp32 d_h = 64, d_h = 128), the 16-bit backward
+                             kernels for rows of 256 bytes and more (fp32 d_h = 64, d_h = 128),
+                             the 16-bit backward
                              for N <= 208 (its slice sits in LDS, rebuilding costs no memory
                              traffic) and a backward call that also asks for dlog_scale rebuild
                              S all the same; the causal variant has no such state and ignores

@@ -460,6 +460,26 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
   return hipGetLastError();
 }
 
+// The same launch structure with the matrix-core kernels for 256-byte rows (cotten_wide.hip) in
+// place of the vector-ALU state and apply kernels; reduction, kept state and <S, dS> as above.
+hipError_t run_wide(const Problem& p, const Plan& plan, bool bwd) {
+  const int BH = p.B * p.H;
+  const int dd = p.D * p.D;
+  if (hipError_t err = launch_wide_states(p, plan, bwd)) return err;
+  const float* states = reduce_generic(p, plan, bwd ? 2 : 1);
+  const size_t second = static_cast<size_t>(BH) * plan.splits * dd;
+  const float* dstates =
+      bwd ? states + (plan.splits == 1 ? second : static_cast<size_t>(BH) * dd) : nullptr;
+  if (!bwd && p.saved_state != nullptr)
+    launch_reduce_states(states, p.saved_state, 1, dd, static_cast<size_t>(BH), p.stream);
+  if (hipError_t err = launch_wide_apply(p, plan, states, dstates, bwd)) return err;
+  if (bwd && p.dlog_scale != nullptr)
+    hipLaunchKernelGGL(state_inner_product_kernel, dim3(static_cast<unsigned>(BH)),
+                       dim3(kThreads), 0, p.stream, states, dstates, dd, p.scale, p.slice_scale,
+                       p.dlog_scale);
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
   switch (p.D) {
@@ -528,12 +548,19 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_re
     // Enough workgroups to fill 256 compute units a few times over, at least one
     // 32-row tile each.
     plan.path = Plan::kGeneric;
-    splits = (2048 + BH - 1) / BH;
-    const long max_splits = (N + kTileRows - 1) / kTileRows;
+    // The matrix-core kernels for 256-byte rows build operand images per workgroup and stage
+    // 64 rows per round: about two workgroups per compute unit, in blocks of 64 rows.
+    // A d x d state is as large as 64 (16-bit: 256) rows of a tensor there, and every split
+    // writes one and has the sum read back: no fewer than 256 rows per workgroup, and a
+    // sequence is not cut at all once there is a workgroup per compute unit without it.
+    const bool wide = wide_supports(dtype, D);
+    const long target = wide ? 512 : 2048, block = wide ? 64 : kTileRows;
+    splits = wide && BH >= 256 ? 1 : (target + BH - 1) / BH;
+    const long max_splits = wide ? (N + 255) / 256 : (N + block - 1) / block;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     rows = (N + splits - 1) / splits;
-    rows = (rows + kTileRows - 1) / kTileRows * kTileRows;
+    rows = (rows + block - 1) / block * block;
   }
   splits = (N + rows - 1) / rows;
   plan.splits = static_cast<int>(splits);
@@ -550,12 +577,14 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_re
 }
 
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan) {
+  if (wide_supports(p.dtype, p.D)) return run_wide(p, plan, false);
   return p.dtype == 0   ? dispatch_d<float>(p, plan, false)
          : p.dtype == 1 ? dispatch_d<bf16>(p, plan, false)
                         : dispatch_d<f16>(p, plan, false);
 }
 
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan) {
+  if (wide_supports(p.dtype, p.D)) return run_wide(p, plan, true);
   return p.dtype == 0   ? dispatch_d<float>(p, plan, true)
          : p.dtype == 1 ? dispatch_d<bf16>(p, plan, true)
                         : dispatch_d<f16>(p, plan, true);

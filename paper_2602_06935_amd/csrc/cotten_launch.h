@@ -71,6 +71,14 @@ void launch_reduce_states(const float* partial, float* reduced, int splits, int 
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 
+// Matrix-core kernels for 256-byte rows (fp32 d_h = 64, 16-bit d_h = 128) inside the launch
+// structure of the vector-ALU path: partial states into p.workspace in its layout, then, from
+// the reduced states ([B*H][D*D] floats each), O or dQ, dK, dV.
+bool wide_supports(int dtype, int D);
+hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd);
+hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
+                             const float* dstates, bool bwd);
+
 // MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows), and
 // the half-width shapes (16-bit d_h = 32, fp32 d_h = 16) zero-padded onto the same kernels.
 bool mfma_supports(int dtype, int D);
