@@ -381,7 +381,7 @@ def main():
 
     others = {}
     if not args.no_others:
-        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5", "emb256"):
             if name == args.workload:
                 continue
             ob = make_batch(name, args.seed)

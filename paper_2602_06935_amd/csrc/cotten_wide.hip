@@ -11,9 +11,10 @@
 // with the row norm taken over both halves.  The launch structure is that of the vector-ALU
 // path whose place these kernels take for the shapes above (same plan, same workspace):
 //
-//   wide_state_kernel   a workgroup of four waves reduces a block of rows of one slice to a
-//                       partial state: per round every wave stages one 16-row tile in LDS, then
-//                       wave (p, q) adds the round's four tiles to its quadrant
+//   wide_state_kernel   a workgroup of four (or eight) waves reduces a block of rows of one slice
+//                       to a partial state: per round every wave stages one 16-row tile in LDS,
+//                       then wave (p, q) adds four tiles of the round to its quadrant (with eight
+//                       waves two waves share a quadrant and their sums meet at the end)
 //   (the partial states of a slice are summed in split order by the reduction kernel of the
 //    vector-ALU path)
 //   wide_fwd_kernel / wide_bwd_kernel
@@ -31,9 +32,8 @@ namespace wide {
 
 using namespace mfma;
 
-constexpr int kWaves = 4;
-constexpr int kThreads = 64 * kWaves;
-constexpr int kRoundRows = kWaves * TR;  // rows a workgroup stages per round of the state kernel
+// Every kernel exists for workgroups of 4 and of 8 waves (template parameter WAVES): 4 when there
+// are workgroups enough to put two on every compute unit, 8 when there are not.
 constexpr int kHalfBytes = kRowBytes;    // one half of a 256-byte row
 
 // A 16-row tile of a tensor pair in the load layout: piece [h][c] is bytes 128 c + 16 ch .. + 15 of
@@ -128,19 +128,22 @@ __device__ __forceinline__ float inv_by_row(float* slot, const Lane& L, const fl
   return slot[L.i16];
 }
 
+extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
 // ---- state kernel -------------------------------------------------------------------------------
 
 // grid (slices * splits, 1 or 2): blockIdx.y == 1 reduces (Q, dO) to sum_i qhat_i^T dO_i instead
 // of (K, V) under the key mask.  Partial states: row-major D x D floats per workgroup, the second
 // kind `second_offset` floats behind the first (the layout of the vector-ALU path).
-template <class F>
-__global__ __launch_bounds__(kThreads) void wide_state_kernel(
+template <class F, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void wide_state_kernel(
     const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
     const unsigned char* __restrict__ V, const unsigned char* __restrict__ dO,
     const uint8_t* __restrict__ mask, float* __restrict__ ws, int H, int N, int splits,
     int rows_per_split, size_t second_offset, float eps, Strides st) {
-  constexpr int Dh = F::D, D = 2 * Dh;
-  __shared__ __attribute__((aligned(16))) unsigned char round[kWaves * 4 * kTileBytes];
+  constexpr int Dh = F::D, D = 2 * Dh, kRoundRows = WAVES * TR;
+  static_assert(WAVES == 4 || WAVES == 8, "one or two waves per quadrant");
+  unsigned char* round = smem;  // WAVES x [x half 0 | x half 1 | y half 0 | y half 1]
   const Lane L;
   const int split = blockIdx.x % splits, bh = blockIdx.x / splits;
   const bool second = blockIdx.y == 1;
@@ -150,7 +153,8 @@ __global__ __launch_bounds__(kThreads) void wide_state_kernel(
       (second || mask == nullptr) ? nullptr : mask + static_cast<size_t>(bh / H) * N;
   const int r_begin = split * rows_per_split;
   const int r_end = N < r_begin + rows_per_split ? N : r_begin + rows_per_split;
-  const int p = L.wave >> 1, q = L.wave & 1;  // this wave's quadrant of the state
+  // this wave's quadrant of the state, and (8 waves) which four tiles of a round it adds up
+  const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, part = L.wave >> 2;
   unsigned char* mine = round + L.wave * 4 * kTileBytes;
 
   typename F::Acc acc;
@@ -166,17 +170,29 @@ __global__ __launch_bounds__(kThreads) void wide_state_kernel(
     next_bits = row_bits(m, r0 + 2 * kRoundRows + L.wave * TR, r_end, L);
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < kWaves; ++t) {
-      const unsigned char* tile = round + t * 4 * kTileBytes;
+    for (int t = 0; t < 4; ++t) {
+      const unsigned char* tile = round + (4 * part + t) * 4 * kTileBytes;
       acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
     }
     __syncthreads();  // the round's tiles are overwritten next
+  }
+  // 8 waves: the two sums of a quadrant meet in LDS (the round buffer is free), in a fixed order
+  f32x4_t* meet = reinterpret_cast<f32x4_t*>(round) + quadrant * F::Acc::kGroups * 64 + L.lane;
+  static_assert(4 * F::Acc::kGroups * 64 * 16 <= 8 * 4 * kTileBytes, "the sums fit the round buffer");
+  if (WAVES == 8) {
+    if (part == 1) {
+#pragma unroll
+      for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+    }
+    __syncthreads();
+    if (part == 1) return;
   }
   float* __restrict__ out =
       ws + (second ? second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
 #pragma unroll
   for (int g = 0; g < F::Acc::kGroups; ++g) {
-    const f32x4_t v = acc.group(g);
+    f32x4_t v = acc.group(g);
+    if (WAVES == 8) v += meet[g * 64];
     const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
 #pragma unroll
     for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
@@ -189,12 +205,13 @@ __global__ __launch_bounds__(kThreads) void wide_state_kernel(
 // image (p, q) at images + (2 p + q) * F::kImageBytes:
 //   natural     op[m][n] = M[p Dh + m][q Dh + n]     for products that contract over n
 //   transposed  op[n][m] = M[p Dh + m][q Dh + n]     for products that contract over m
-template <class F, bool TRANSPOSED>
+template <class F, int WAVES, bool TRANSPOSED>
 __device__ __forceinline__ void build_images(const float* __restrict__ M, float scale,
                                              unsigned char* images) {
-  constexpr int Dh = F::D, D = 2 * Dh;
-  constexpr int kPairs = D * D / 2, kBatch = 8;  // element pairs; loads of a batch travel together
-  static_assert(kPairs % (kBatch * kThreads) == 0, "state size");
+  constexpr int Dh = F::D, D = 2 * Dh, kThreads = 64 * WAVES;
+  // element pairs; the loads of a batch travel together
+  constexpr int kPairs = D * D / 2, kBatch = kPairs / kThreads < 8 ? kPairs / kThreads : 8;
+  static_assert(kBatch >= 1 && kPairs % (kBatch * kThreads) == 0, "state size");
   for (int e0 = threadIdx.x; e0 < kPairs; e0 += kBatch * kThreads) {
     float v0[kBatch], v1[kBatch];
 #pragma unroll
@@ -270,24 +287,23 @@ struct ApplyArgs {
 };
 
 // LDS of the apply kernels: [four images][per wave: four tiles, 16 floats]
-template <class F>
+template <class F, int WAVES>
 struct ApplyLds {
   static constexpr int kImages = 0;
   static constexpr int kWave = 4 * F::kImageBytes;
   static constexpr int kWaveBytes = 4 * kTileBytes + TR * 4;
-  static constexpr int kBytes = kWave + kWaves * kWaveBytes;
+  static constexpr int kBytes = kWave + WAVES * kWaveBytes;
 };
 
-extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
 // out rows = (x rows) M / r, contraction over the rows of M:  O = scale qhat S,  dV = scale khat dS.
-template <class F, bool HOLD>
+template <class F, int WAVES, bool HOLD>
 __device__ __forceinline__ void plain_role(const ApplyArgs& a) {
+  constexpr int kRoundRows = WAVES * TR;  // rows between two tiles of a wave
   const Lane L;
-  unsigned char* images = smem + ApplyLds<F>::kImages;
-  unsigned char* tiles = smem + ApplyLds<F>::kWave + L.wave * ApplyLds<F>::kWaveBytes;
+  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
+  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
-  build_images<F, true>(a.state, a.scale, images);
+  build_images<F, WAVES, true>(a.state, a.scale, images);
   __syncthreads();
   const Quadrants<F, HOLD> W(images, L);
   const WideSrc src(a.X, a.X, a.N, a.stride);
@@ -320,13 +336,14 @@ __device__ __forceinline__ void plain_role(const ApplyArgs& a) {
 
 // out rows = (g - xhat (xhat . g)) / r with g = (y rows) M^T, contraction over the columns of M:
 //   dQ from (Q, dO) and scale S;   dK from (K, V) and scale dS (masked rows come out as zeros).
-template <class F>
+template <class F, int WAVES>
 __device__ __forceinline__ void projected_role(const ApplyArgs& a) {
+  constexpr int kRoundRows = WAVES * TR;
   const Lane L;
-  unsigned char* images = smem + ApplyLds<F>::kImages;
-  unsigned char* tiles = smem + ApplyLds<F>::kWave + L.wave * ApplyLds<F>::kWaveBytes;
+  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
+  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
-  build_images<F, false>(a.state, a.scale, images);
+  build_images<F, WAVES, false>(a.state, a.scale, images);
   __syncthreads();
   const Quadrants<F, false> W(images, L);
   const WideSrc src(a.X, a.Y, a.N, a.stride);
@@ -403,8 +420,8 @@ __device__ __forceinline__ ApplyArgs role_args(const LaunchArgs& a, int dd) {
   return r;
 }
 
-template <class F>
-__global__ __launch_bounds__(kThreads) void wide_fwd_kernel(const LaunchArgs a) {
+template <class F, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void wide_fwd_kernel(const LaunchArgs a) {
   constexpr int D = 2 * F::D;
   const int bh = blockIdx.x / a.splits;
   const size_t base = a.st.slice_base(bh, a.H);
@@ -413,12 +430,12 @@ __global__ __launch_bounds__(kThreads) void wide_fwd_kernel(const LaunchArgs a) 
   r.mask = nullptr;  // queries are not masked
   r.state = a.states + static_cast<size_t>(bh) * D * D;
   r.out = a.O + base;
-  plain_role<F, true>(r);
+  plain_role<F, WAVES, true>(r);
 }
 
 // blockIdx.y: 0 dQ, 1 dV, 2 dK
-template <class F>
-__global__ __launch_bounds__(kThreads) void wide_bwd_kernel(const LaunchArgs a) {
+template <class F, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void wide_bwd_kernel(const LaunchArgs a) {
   constexpr int D = 2 * F::D;
   const int bh = blockIdx.x / a.splits;
   const size_t base = a.st.slice_base(bh, a.H);
@@ -430,20 +447,20 @@ __global__ __launch_bounds__(kThreads) void wide_bwd_kernel(const LaunchArgs a) 
     r.mask = nullptr;
     r.state = a.states + static_cast<size_t>(bh) * D * D;
     r.out = a.dQ + base;
-    projected_role<F>(r);
+    projected_role<F, WAVES>(r);
   } else if (blockIdx.y == 1) {
     r.X = a.K + base;
     r.mask = keys;
     r.state = a.dstates + static_cast<size_t>(bh) * D * D;
     r.out = a.dV + base;
-    plain_role<F, false>(r);
+    plain_role<F, WAVES, false>(r);
   } else {
     r.X = a.K + base;
     r.Y = a.V + base;
     r.mask = keys;
     r.state = a.dstates + static_cast<size_t>(bh) * D * D;
     r.out = a.dK + base;
-    projected_role<F>(r);
+    projected_role<F, WAVES>(r);
   }
 }
 
@@ -479,35 +496,63 @@ LaunchArgs launch_args(const Problem& p, const Plan& plan, const float* states, 
   return a;
 }
 
-constexpr int kMaxLdsBytes = 80 * 1024;  // two workgroups per compute unit
+// Workgroups of 8 waves (the whole LDS of a compute unit at their disposal) when the launch has
+// no more workgroups than there are compute units, of 4 waves (two per compute unit) otherwise.
+constexpr int kUnits = 256;
+template <int WAVES>
+constexpr int max_lds_bytes() {
+  return WAVES == 8 ? 160 * 1024 : 80 * 1024;
+}
+
+template <class F, int WAVES>
+hipError_t states_w(const Problem& p, const Plan& plan, bool bwd) {
+  constexpr int D = 2 * F::D;
+  constexpr int lds = WAVES * 4 * kTileBytes;
+  static_assert(lds <= max_lds_bytes<WAVES>(), "round buffer");
+  const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
+  const size_t second = static_cast<size_t>(blocks) * D * D;
+  const hipError_t err =
+      grant_dynamic_lds(reinterpret_cast<const void*>(wide_state_kernel<F, WAVES>), max_lds_bytes<WAVES>());
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL((wide_state_kernel<F, WAVES>), dim3(blocks, bwd ? 2 : 1), dim3(64 * WAVES), lds,
+                     p.stream, static_cast<const unsigned char*>(p.Q),
+                     static_cast<const unsigned char*>(p.K), static_cast<const unsigned char*>(p.V),
+                     static_cast<const unsigned char*>(p.dO), p.mask, p.workspace, p.H, p.N,
+                     plan.splits, plan.rows_per_split, second, p.eps, byte_strides(p));
+  return hipGetLastError();
+}
+
+template <class F, int WAVES>
+hipError_t apply_w(const Problem& p, const Plan& plan, const float* st, const float* dst, bool bwd) {
+  constexpr int lds = ApplyLds<F, WAVES>::kBytes;
+  static_assert(lds <= max_lds_bytes<WAVES>(), "images and tiles");
+  const LaunchArgs a = launch_args(p, plan, st, dst);
+  const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
+  const void* kern = bwd ? reinterpret_cast<const void*>(wide_bwd_kernel<F, WAVES>)
+                         : reinterpret_cast<const void*>(wide_fwd_kernel<F, WAVES>);
+  const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<WAVES>());
+  if (err != hipSuccess) return err;
+  if (bwd)
+    hipLaunchKernelGGL((wide_bwd_kernel<F, WAVES>), dim3(blocks, 3), dim3(64 * WAVES), lds, p.stream, a);
+  else
+    hipLaunchKernelGGL((wide_fwd_kernel<F, WAVES>), dim3(blocks), dim3(64 * WAVES), lds, p.stream, a);
+  return hipGetLastError();
+}
+
+// `kinds`: workgroups per (slice, split) of the launch (states or roles)
+inline bool few_workgroups(const Problem& p, const Plan& plan, int kinds) {
+  return static_cast<long>(p.B) * p.H * plan.splits * kinds <= kUnits;
+}
 
 template <class F>
 hipError_t states(const Problem& p, const Plan& plan, bool bwd) {
-  constexpr int D = 2 * F::D;
-  const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
-  const size_t second = static_cast<size_t>(blocks) * D * D;
-  hipLaunchKernelGGL(wide_state_kernel<F>, dim3(blocks, bwd ? 2 : 1), dim3(kThreads), 0, p.stream,
-                     static_cast<const unsigned char*>(p.Q), static_cast<const unsigned char*>(p.K),
-                     static_cast<const unsigned char*>(p.V), static_cast<const unsigned char*>(p.dO),
-                     p.mask, p.workspace, p.H, p.N, plan.splits, plan.rows_per_split, second, p.eps,
-                     byte_strides(p));
-  return hipGetLastError();
+  return few_workgroups(p, plan, bwd ? 2 : 1) ? states_w<F, 8>(p, plan, bwd) : states_w<F, 4>(p, plan, bwd);
 }
 
 template <class F>
 hipError_t apply(const Problem& p, const Plan& plan, const float* st, const float* dst, bool bwd) {
-  static_assert(ApplyLds<F>::kBytes <= kMaxLdsBytes, "two workgroups per compute unit");
-  const LaunchArgs a = launch_args(p, plan, st, dst);
-  const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
-  const void* kern = bwd ? reinterpret_cast<const void*>(wide_bwd_kernel<F>)
-                         : reinterpret_cast<const void*>(wide_fwd_kernel<F>);
-  const hipError_t err = grant_dynamic_lds(kern, kMaxLdsBytes);
-  if (err != hipSuccess) return err;
-  if (bwd)
-    hipLaunchKernelGGL(wide_bwd_kernel<F>, dim3(blocks, 3), dim3(kThreads), ApplyLds<F>::kBytes, p.stream, a);
-  else
-    hipLaunchKernelGGL(wide_fwd_kernel<F>, dim3(blocks), dim3(kThreads), ApplyLds<F>::kBytes, p.stream, a);
-  return hipGetLastError();
+  return few_workgroups(p, plan, bwd ? 3 : 1) ? apply_w<F, 8>(p, plan, st, dst, bwd)
+                                              : apply_w<F, 4>(p, plan, st, dst, bwd);
 }
 
 }  // namespace wide

@@ -42,7 +42,7 @@ class Workload:
     description: str = ""
 
 
-# The five configurations of the benchmark contract, in order.
+# The five configurations of the benchmark contract, in order, and one more shape.
 WORKLOADS = {
     "cfg1": Workload("cfg1", 4, 2, 50, 32, "f32", 1.0, "full", 50, 50,
                      backward=False,
@@ -57,6 +57,10 @@ WORKLOADS = {
                      description="fwd+bwd bf16 I/O, lengths U{5..200}, 1% tiny rows"),
     "cfg5": Workload("cfg5", 16, 4, 4096, 64, "bf16", 1.0, "uniform", 1024, 4096,
                      description="long-history stress, bf16 I/O, lengths U{1024..4096}"),
+    # Beside the contract: the largest embedding size of the paper's sweep (64, 128, 256) with the
+    # two heads of a BERT4Rec layer, i.e. 256-byte rows under 16-bit I/O.
+    "emb256": Workload("emb256", 128, 2, 200, 128, "bf16", 0.5, "uniform", 5, 200,
+                       description="embedding size 256, two heads: d_h = 128, bf16 I/O, lengths U{5..200}"),
 }
 
 
