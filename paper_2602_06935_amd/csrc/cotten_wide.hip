@@ -296,15 +296,12 @@ struct ApplyLds {
 };
 
 // out rows = (x rows) M / r, contraction over the rows of M:  O = scale qhat S,  dV = scale khat dS.
+// `images`: the four transposed quadrant images of scale * M; `tiles`: this wave's tile set.
 template <class F, int WAVES, bool HOLD>
-__device__ __forceinline__ void plain_role(const ApplyArgs& a) {
+__device__ __forceinline__ void plain_tiles(const ApplyArgs& a, const unsigned char* images,
+                                            unsigned char* tiles, const Lane& L) {
   constexpr int kRoundRows = WAVES * TR;  // rows between two tiles of a wave
-  const Lane L;
-  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
-  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
-  build_images<F, WAVES, true>(a.state, a.scale, images);
-  __syncthreads();
   const Quadrants<F, HOLD> W(images, L);
   const WideSrc src(a.X, a.X, a.N, a.stride);
   int row0 = a.r_begin + L.wave * TR;
@@ -334,17 +331,24 @@ __device__ __forceinline__ void plain_role(const ApplyArgs& a) {
   }
 }
 
-// out rows = (g - xhat (xhat . g)) / r with g = (y rows) M^T, contraction over the columns of M:
-//   dQ from (Q, dO) and scale S;   dK from (K, V) and scale dS (masked rows come out as zeros).
-template <class F, int WAVES>
-__device__ __forceinline__ void projected_role(const ApplyArgs& a) {
-  constexpr int kRoundRows = WAVES * TR;
+template <class F, int WAVES, bool HOLD>
+__device__ __forceinline__ void plain_role(const ApplyArgs& a) {
   const Lane L;
   unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
   unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
-  float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
-  build_images<F, WAVES, false>(a.state, a.scale, images);
+  build_images<F, WAVES, true>(a.state, a.scale, images);
   __syncthreads();
+  plain_tiles<F, WAVES, HOLD>(a, images, tiles, L);
+}
+
+// out rows = (g - xhat (xhat . g)) / r with g = (y rows) M^T, contraction over the columns of M:
+//   dQ from (Q, dO) and scale S;   dK from (K, V) and scale dS (masked rows come out as zeros).
+// `images`: the four natural quadrant images of scale * M.
+template <class F, int WAVES>
+__device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsigned char* images,
+                                                unsigned char* tiles, const Lane& L) {
+  constexpr int kRoundRows = WAVES * TR;
+  float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
   const Quadrants<F, false> W(images, L);
   const WideSrc src(a.X, a.Y, a.N, a.stride);
   int row0 = a.r_begin + L.wave * TR;
@@ -388,6 +392,16 @@ __device__ __forceinline__ void projected_role(const ApplyArgs& a) {
     }
     wave_lds_fence();
   }
+}
+
+template <class F, int WAVES>
+__device__ __forceinline__ void projected_role(const ApplyArgs& a) {
+  const Lane L;
+  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
+  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
+  build_images<F, WAVES, false>(a.state, a.scale, images);
+  __syncthreads();
+  projected_tiles<F, WAVES>(a, images, tiles, L);
 }
 
 struct LaunchArgs {
@@ -462,6 +476,218 @@ __global__ __launch_bounds__(64 * WAVES) void wide_bwd_kernel(const LaunchArgs a
     r.out = a.dK + base;
     projected_role<F, WAVES>(r);
   }
+}
+
+// ---- one launch per direction: a workgroup of eight waves per slice ------------------------------
+//
+// When a sequence is not cut (one partial state per slice), the state need not leave the compute
+// unit: the quadrant sums go from the accumulators straight into the operand images in LDS and
+// the same workgroup streams the slice a second time through the apply roles.
+//
+//   forward   all eight waves reduce (K, V) to S (two waves per quadrant, rounds of 128 rows, the
+//             sums meet in LDS), then stream Q through the transposed images of scale S.
+//   backward  waves 0-3 reduce (K, V) to S, waves 4-7 (Q, dO) to dS, rounds of 64 rows each; then
+//             all waves run dQ (natural images of S) and dV (transposed images of dS), and, the
+//             images of S overwritten by the natural images of dS, dK.
+//
+// LDS: [SETS x four images][per wave: four tiles, 16 floats]; the tile sets double as the round
+// buffer of the state phase and as the place where accumulators meet.
+template <class F, int SETS>
+struct FusedLds {
+  static constexpr int kWaves = 8;
+  static constexpr int kSetBytes = 4 * F::kImageBytes;
+  static constexpr int kTiles = SETS * kSetBytes;
+  static constexpr int kWaveBytes = 4 * kTileBytes + TR * 4;
+  static constexpr int kBytes = kTiles + kWaves * kWaveBytes;
+  static_assert(4 * F::Acc::kGroups * 64 * 16 + 64 <= kWaves * kWaveBytes, "accumulators meet in the tile sets");
+};
+
+// The state phase of a group of four waves (wave & 3: the quadrant): every wave stages the 16 rows
+// from `first_row` on of each round into its own tile set and adds the four tile sets of its group
+// (wave >> 2) to its quadrant.  Rows at and beyond N, and masked rows, are never fetched.
+template <class F, int WAVE_BYTES>
+__device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const WideSrc& src,
+                                                 const uint8_t* __restrict__ m, int N, int first_row,
+                                                 int round_rows, float eps, unsigned char* sets,
+                                                 const Lane& L) {
+  const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, group = L.wave >> 2;
+  unsigned char* mine = sets + L.wave * WAVE_BYTES;
+  acc.zero();
+  WideRaw cur;
+  load_wide<true>(cur, L, src, first_row, row_bits(m, first_row, N, L));
+  int next_bits = row_bits(m, first_row + round_rows, N, L);
+  for (int r0 = 0; r0 < N; r0 += round_rows) {
+    float inv[2];
+    stage_wide<F, true, true>(cur, L, eps, mine, inv);
+    load_wide<true>(cur, L, src, r0 + round_rows + first_row, next_bits);
+    next_bits = row_bits(m, r0 + 2 * round_rows + first_row, N, L);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const unsigned char* tile = sets + (4 * group + t) * WAVE_BYTES;
+      acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
+    }
+    __syncthreads();  // the tile sets are overwritten next
+  }
+}
+
+// A quadrant of scale * M from the accumulator layout (`get(g)`: group g, four consecutive rows of
+// one column) into its operand image: transposed straight from the lane (two row pairs of its
+// column), natural with the neighbouring lane's column (even lanes write the first two rows of a
+// group, odd lanes the last two; each gets the other column of its rows from its neighbour).
+template <class F, bool NATURAL, class Get>
+__device__ __forceinline__ void quadrant_image(Get get, float scale, unsigned char* image, const Lane& L) {
+#pragma unroll
+  for (int g = 0; g < F::Acc::kGroups; ++g) {
+    const f32x4_t v = get(g) * scale;
+    const int row = F::Acc::group_row(g, L), col = F::Acc::group_col(g, L);
+    if (!NATURAL) {
+      F::write_image_pair(image, col, row, v[0], v[1]);
+      F::write_image_pair(image, col, row + 2, v[2], v[3]);
+    } else {
+      // The lane sends what its neighbour wants (the choice is made on the sending side: a
+      // choice between two values received from the neighbour would be evaluated over there).
+      const bool odd = (col & 1) != 0;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const float mine = odd ? v[2 + i] : v[i];
+        int sent = __builtin_bit_cast(int, odd ? v[i] : v[2 + i]);
+        asm volatile("" : "+v"(sent));
+        int got = __builtin_amdgcn_update_dpp(0, sent, 0xB1, 0xF, 0xF, true);  // lane ^ 1
+        asm volatile("" : "+v"(got));
+        const float other = __builtin_bit_cast(float, got);
+        F::write_image_pair(image, row + (odd ? 2 : 0) + i, col & ~1, odd ? other : mine, odd ? mine : other);
+      }
+    }
+  }
+}
+
+template <class F>
+__global__ __launch_bounds__(512) void wide_fused_fwd_kernel(const LaunchArgs a, float* __restrict__ kept) {
+  using Lds = FusedLds<F, 1>;
+  constexpr int Dh = F::D, D = 2 * Dh;
+  const Lane L;
+  const int bh = blockIdx.x;
+  const size_t base = a.st.slice_base(bh, a.H);
+  unsigned char* images = smem;
+  unsigned char* sets = smem + Lds::kTiles;
+  const int quadrant = L.wave & 3, part = L.wave >> 2;
+  typename F::Acc acc;
+  {
+    const WideSrc kv(a.K + base, a.V + base, a.N, a.st.row.stride);
+    const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
+    fused_state_pass<F, Lds::kWaveBytes>(acc, kv, keys, a.N, L.wave * TR, 8 * TR, a.eps, sets, L);
+  }
+  // the two sums of a quadrant meet (the tile sets are free), in a fixed order
+  f32x4_t* meet = reinterpret_cast<f32x4_t*>(sets) + quadrant * F::Acc::kGroups * 64 + L.lane;
+  if (part == 1) {
+#pragma unroll
+    for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+  }
+  __syncthreads();
+  const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
+  if (part == 0) {
+    const auto sum = [&](int g) { return acc.group(g) + meet[g * 64]; };
+    quadrant_image<F, false>(sum, scale, images + quadrant * F::kImageBytes, L);
+    if (kept != nullptr) {  // S as it is, row-major, for the caller's backward call
+      float* __restrict__ out = kept + static_cast<size_t>(bh) * D * D;
+      const int p = quadrant >> 1, q = quadrant & 1;
+#pragma unroll
+      for (int g = 0; g < F::Acc::kGroups; ++g) {
+        const f32x4_t v = sum(g);
+        const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
+      }
+    }
+  }
+  __syncthreads();
+  ApplyArgs r{};
+  r.X = a.Q + base;
+  r.mask = nullptr;  // queries are not masked
+  r.out = a.O + base;
+  r.N = a.N;
+  r.r_begin = 0;
+  r.r_end = a.N;
+  r.stride = a.st.row.stride;
+  r.scale = scale;
+  r.eps = a.eps;
+  plain_tiles<F, 8, true>(r, images, sets + L.wave * Lds::kWaveBytes, L);
+}
+
+template <class F>
+__global__ __launch_bounds__(512) void wide_fused_bwd_kernel(const LaunchArgs a, float* __restrict__ dlog) {
+  using Lds = FusedLds<F, 2>;
+  const Lane L;
+  const int bh = blockIdx.x;
+  const size_t base = a.st.slice_base(bh, a.H);
+  unsigned char* images_a = smem;                    // S natural, later dS natural
+  unsigned char* images_b = smem + Lds::kSetBytes;   // dS transposed
+  unsigned char* sets = smem + Lds::kTiles;
+  const int quadrant = L.wave & 3;
+  const bool second = L.wave >= 4;  // waves 4-7: dS = sum_i qhat_i^T dO_i
+  const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
+  typename F::Acc acc;
+  {
+    const WideSrc src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, a.N, a.st.row.stride);
+    fused_state_pass<F, Lds::kWaveBytes>(acc, src, second ? nullptr : keys, a.N, quadrant * TR, 4 * TR,
+                                         a.eps, sets, L);
+  }
+  const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
+  const auto own = [&](int g) { return acc.group(g); };
+  if (dlog != nullptr) {  // d loss / d log(scale) = scale <S, dS>: dS meets S in the tile sets
+    f32x4_t* meet = reinterpret_cast<f32x4_t*>(sets) + quadrant * F::Acc::kGroups * 64 + L.lane;
+    float* partial = reinterpret_cast<float*>(sets + 4 * F::Acc::kGroups * 64 * 16);
+    if (second) {
+#pragma unroll
+      for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+    }
+    __syncthreads();
+    if (!second) {
+      float dot = 0.0f;
+#pragma unroll
+      for (int g = 0; g < F::Acc::kGroups; ++g) {
+        const f32x4_t s = acc.group(g), d = meet[g * 64];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dot += s[i] * d[i];
+      }
+      dot = wave_sum(dot);
+      if (L.lane == 0) partial[quadrant] = dot;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) dlog[bh] = (((partial[0] + partial[1]) + partial[2]) + partial[3]) * scale;
+    __syncthreads();  // the tile sets are staged into next
+  }
+  if (!second) quadrant_image<F, true>(own, scale, images_a + quadrant * F::kImageBytes, L);
+  else quadrant_image<F, false>(own, scale, images_b + quadrant * F::kImageBytes, L);
+  __syncthreads();
+
+  unsigned char* tiles = sets + L.wave * Lds::kWaveBytes;
+  ApplyArgs r{};
+  r.N = a.N;
+  r.r_begin = 0;
+  r.r_end = a.N;
+  r.stride = a.st.row.stride;
+  r.scale = scale;
+  r.eps = a.eps;
+  // dQ
+  r.X = a.Q + base;
+  r.Y = a.dO + base;
+  r.mask = nullptr;
+  r.out = a.dQ + base;
+  projected_tiles<F, 8>(r, images_a, tiles, L);
+  __syncthreads();  // nobody reads the images of S any more
+  if (second) quadrant_image<F, true>(own, scale, images_a + quadrant * F::kImageBytes, L);
+  // dV
+  r.X = a.K + base;
+  r.mask = keys;
+  r.out = a.dV + base;
+  plain_tiles<F, 8, false>(r, images_b, tiles, L);
+  __syncthreads();  // the natural images of dS are complete
+  // dK
+  r.Y = a.V + base;
+  r.out = a.dK + base;
+  projected_tiles<F, 8>(r, images_a, tiles, L);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -555,6 +781,25 @@ hipError_t apply(const Problem& p, const Plan& plan, const float* st, const floa
                                               : apply_w<F, 4>(p, plan, st, dst, bwd);
 }
 
+template <class F>
+hipError_t fused(const Problem& p, const Plan& plan, bool bwd) {
+  static_assert(FusedLds<F, 2>::kBytes <= max_lds_bytes<8>(), "two image sets and the tile sets");
+  constexpr int lds_fwd = FusedLds<F, 1>::kBytes, lds_bwd = FusedLds<F, 2>::kBytes;
+  const LaunchArgs a = launch_args(p, plan, nullptr, nullptr);
+  const unsigned blocks = static_cast<unsigned>(p.B) * p.H;
+  const void* kern = bwd ? reinterpret_cast<const void*>(wide_fused_bwd_kernel<F>)
+                         : reinterpret_cast<const void*>(wide_fused_fwd_kernel<F>);
+  const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<8>());
+  if (err != hipSuccess) return err;
+  if (bwd)
+    hipLaunchKernelGGL((wide_fused_bwd_kernel<F>), dim3(blocks), dim3(512), lds_bwd,
+                       p.stream, a, p.dlog_scale);
+  else
+    hipLaunchKernelGGL((wide_fused_fwd_kernel<F>), dim3(blocks), dim3(512), lds_fwd,
+                       p.stream, a, p.saved_state);
+  return hipGetLastError();
+}
+
 }  // namespace wide
 }  // namespace
 
@@ -565,6 +810,14 @@ hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd) {
   return p.dtype == 0   ? wide::states<F32x32>(p, plan, bwd)
          : p.dtype == 1 ? wide::states<Bf16x64>(p, plan, bwd)
                         : wide::states<F16x64>(p, plan, bwd);
+}
+
+hipError_t launch_wide_fused(const Problem& p, const Plan& plan, bool bwd) {
+  using namespace mfma;
+  if (plan.splits != 1) return hipErrorInvalidValue;
+  return p.dtype == 0   ? wide::fused<F32x32>(p, plan, bwd)
+         : p.dtype == 1 ? wide::fused<Bf16x64>(p, plan, bwd)
+                        : wide::fused<F16x64>(p, plan, bwd);
 }
 
 hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
