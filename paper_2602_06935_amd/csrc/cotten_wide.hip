@@ -296,38 +296,57 @@ struct ApplyLds {
 };
 
 // out rows = (x rows) M / r, contraction over the rows of M:  O = scale qhat S,  dV = scale khat dS.
-// `images`: the four transposed quadrant images of scale * M; `tiles`: this wave's tile set.
-template <class F, int WAVES, bool HOLD>
-__device__ __forceinline__ void plain_tiles(const ApplyArgs& a, const unsigned char* images,
-                                            unsigned char* tiles, const Lane& L) {
-  constexpr int kRoundRows = WAVES * TR;  // rows between two tiles of a wave
+// One tile of the plain role: `cur` staged raw into the wave's tile set, out rows = x W / r.
+template <class F, bool HOLD>
+__device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD>& W, const WideRaw& cur, int row0,
+                                           int r_end, unsigned char* out, int stride, float eps,
+                                           unsigned char* tiles, const Lane& L) {
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
+  float inv[2];
+  stage_wide<F, false, false>(cur, L, eps, tiles, inv);
+  const float inv_r = inv_by_row(inv_slot, L, inv);
+  typename F::TileRows X[2];
+  X[0].load(tiles, L);
+  X[1].load(tiles + kTileBytes, L);
+  const int row = row0 + L.i16;
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    float o[2 * F::EPL];
+    W.apply(X, q, 2 + q, L, o);
+#pragma unroll
+    for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
+    if (row < r_end)
+      store_product_row<F, kStoreStreamed>(out + q * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, o);
+  }
+  wave_lds_fence();
+}
+
+// `images`: the four transposed quadrant images of scale * M; `tiles`: this wave's tile set.
+// The wave's first tile: requested here, or (REQUESTED) by the caller with request_first_tile.
+template <int WAVES>
+__device__ __forceinline__ void request_first_tile(WideRaw& cur, const ApplyArgs& a, const Lane& L) {
+  const WideSrc src(a.X, a.X, a.N, a.stride);
+  const int row0 = a.r_begin + L.wave * TR;
+  load_wide<false>(cur, L, src, row0, row_bits(a.mask, row0, a.r_end, L));
+}
+
+template <class F, int WAVES, bool HOLD, bool REQUESTED = false>
+__device__ __forceinline__ void plain_tiles(const ApplyArgs& a, const unsigned char* images,
+                                            unsigned char* tiles, const Lane& L,
+                                            const WideRaw* first = nullptr) {
+  constexpr int kRoundRows = WAVES * TR;  // rows between two tiles of a wave
   const Quadrants<F, HOLD> W(images, L);
   const WideSrc src(a.X, a.X, a.N, a.stride);
   int row0 = a.r_begin + L.wave * TR;
   WideRaw cur;
-  load_wide<false>(cur, L, src, row0, row_bits(a.mask, row0, a.r_end, L));
+  if (REQUESTED) cur = *first;
+  else request_first_tile<WAVES>(cur, a, L);
   int next_bits = row_bits(a.mask, row0 + kRoundRows, a.r_end, L);
   for (; row0 < a.r_end; row0 += kRoundRows) {
-    float inv[2];
-    stage_wide<F, false, false>(cur, L, a.eps, tiles, inv);
+    const WideRaw tile = cur;
     load_wide<false>(cur, L, src, row0 + kRoundRows, next_bits);
     next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
-    const float inv_r = inv_by_row(inv_slot, L, inv);
-    typename F::TileRows X[2];
-    X[0].load(tiles, L);
-    X[1].load(tiles + kTileBytes, L);
-    const int row = row0 + L.i16;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      float o[2 * F::EPL];
-      W.apply(X, q, 2 + q, L, o);
-#pragma unroll
-      for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
-      if (row < a.r_end)
-        store_product_row<F, kStoreStreamed>(a.out + q * kHalfBytes, row, RowAddr{a.stride, kHalfBytes}, L, o);
-    }
-    wave_lds_fence();
+    plain_tile<F, HOLD>(W, tile, row0, a.r_end, a.out, a.stride, a.eps, tiles, L);
   }
 }
 
@@ -562,6 +581,38 @@ __device__ __forceinline__ void quadrant_image(Get get, float scale, unsigned ch
   }
 }
 
+// End of the forward's state phase: the two sums of a quadrant meet in `meet_area` (free by then),
+// in a fixed order; the waves of the first group write the transposed images of scale * S and, if
+// asked, S itself (row-major, for the caller's backward call).  Ends with a barrier.
+template <class F>
+__device__ __forceinline__ void forward_images(const typename F::Acc& acc, float scale,
+                                               unsigned char* images, unsigned char* meet_area,
+                                               float* __restrict__ kept, const Lane& L) {
+  constexpr int Dh = F::D, D = 2 * Dh;
+  const int quadrant = L.wave & 3, part = L.wave >> 2;
+  f32x4_t* meet = reinterpret_cast<f32x4_t*>(meet_area) + quadrant * F::Acc::kGroups * 64 + L.lane;
+  if (part == 1) {
+#pragma unroll
+    for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+  }
+  __syncthreads();
+  if (part == 0) {
+    const auto sum = [&](int g) { return acc.group(g) + meet[g * 64]; };
+    quadrant_image<F, false>(sum, scale, images + quadrant * F::kImageBytes, L);
+    if (kept != nullptr) {
+      const int p = quadrant >> 1, q = quadrant & 1;
+#pragma unroll
+      for (int g = 0; g < F::Acc::kGroups; ++g) {
+        const f32x4_t v = sum(g);
+        const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kept[(row + i) * D + col] = v[i];
+      }
+    }
+  }
+  __syncthreads();
+}
+
 template <class F>
 __global__ __launch_bounds__(512) void wide_fused_fwd_kernel(const LaunchArgs a, float* __restrict__ kept) {
   using Lds = FusedLds<F, 1>;
@@ -571,37 +622,13 @@ __global__ __launch_bounds__(512) void wide_fused_fwd_kernel(const LaunchArgs a,
   const size_t base = a.st.slice_base(bh, a.H);
   unsigned char* images = smem;
   unsigned char* sets = smem + Lds::kTiles;
-  const int quadrant = L.wave & 3, part = L.wave >> 2;
   typename F::Acc acc;
   {
     const WideSrc kv(a.K + base, a.V + base, a.N, a.st.row.stride);
     const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
     fused_state_pass<F, Lds::kWaveBytes>(acc, kv, keys, a.N, L.wave * TR, 8 * TR, a.eps, sets, L);
   }
-  // the two sums of a quadrant meet (the tile sets are free), in a fixed order
-  f32x4_t* meet = reinterpret_cast<f32x4_t*>(sets) + quadrant * F::Acc::kGroups * 64 + L.lane;
-  if (part == 1) {
-#pragma unroll
-    for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
-  }
-  __syncthreads();
   const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
-  if (part == 0) {
-    const auto sum = [&](int g) { return acc.group(g) + meet[g * 64]; };
-    quadrant_image<F, false>(sum, scale, images + quadrant * F::kImageBytes, L);
-    if (kept != nullptr) {  // S as it is, row-major, for the caller's backward call
-      float* __restrict__ out = kept + static_cast<size_t>(bh) * D * D;
-      const int p = quadrant >> 1, q = quadrant & 1;
-#pragma unroll
-      for (int g = 0; g < F::Acc::kGroups; ++g) {
-        const f32x4_t v = sum(g);
-        const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
-      }
-    }
-  }
-  __syncthreads();
   ApplyArgs r{};
   r.X = a.Q + base;
   r.mask = nullptr;  // queries are not masked
@@ -612,7 +639,41 @@ __global__ __launch_bounds__(512) void wide_fused_fwd_kernel(const LaunchArgs a,
   r.stride = a.st.row.stride;
   r.scale = scale;
   r.eps = a.eps;
-  plain_tiles<F, 8, true>(r, images, sets + L.wave * Lds::kWaveBytes, L);
+  // the first tile of Q travels while the images are made
+  WideRaw first;
+  request_first_tile<8>(first, r, L);
+  forward_images<F>(acc, scale, images, sets, kept == nullptr ? nullptr : kept + static_cast<size_t>(bh) * D * D, L);
+  plain_tiles<F, 8, true, true>(r, images, sets + L.wave * Lds::kWaveBytes, L, &first);
+}
+
+// d loss / d log(scale) = scale <S, dS> of the slice: the dS accumulators (waves 4-7) meet the S
+// accumulators (waves 0-3) in `area` (free at that point), the sum in a fixed order.  Ends with
+// a barrier.
+template <class F>
+__device__ __forceinline__ void state_dot(const typename F::Acc& acc, bool second, float scale,
+                                          unsigned char* area, float* __restrict__ out, const Lane& L) {
+  const int quadrant = L.wave & 3;
+  f32x4_t* meet = reinterpret_cast<f32x4_t*>(area) + quadrant * F::Acc::kGroups * 64 + L.lane;
+  float* partial = reinterpret_cast<float*>(area + 4 * F::Acc::kGroups * 64 * 16);
+  if (second) {
+#pragma unroll
+    for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+  }
+  __syncthreads();
+  if (!second) {
+    float dot = 0.0f;
+#pragma unroll
+    for (int g = 0; g < F::Acc::kGroups; ++g) {
+      const f32x4_t s = acc.group(g), d = meet[g * 64];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dot += s[i] * d[i];
+    }
+    dot = wave_sum(dot);
+    if (L.lane == 0) partial[quadrant] = dot;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) *out = (((partial[0] + partial[1]) + partial[2]) + partial[3]) * scale;
+  __syncthreads();  // the area is written again next
 }
 
 template <class F>
@@ -635,29 +696,7 @@ __global__ __launch_bounds__(512) void wide_fused_bwd_kernel(const LaunchArgs a,
   }
   const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
   const auto own = [&](int g) { return acc.group(g); };
-  if (dlog != nullptr) {  // d loss / d log(scale) = scale <S, dS>: dS meets S in the tile sets
-    f32x4_t* meet = reinterpret_cast<f32x4_t*>(sets) + quadrant * F::Acc::kGroups * 64 + L.lane;
-    float* partial = reinterpret_cast<float*>(sets + 4 * F::Acc::kGroups * 64 * 16);
-    if (second) {
-#pragma unroll
-      for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
-    }
-    __syncthreads();
-    if (!second) {
-      float dot = 0.0f;
-#pragma unroll
-      for (int g = 0; g < F::Acc::kGroups; ++g) {
-        const f32x4_t s = acc.group(g), d = meet[g * 64];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dot += s[i] * d[i];
-      }
-      dot = wave_sum(dot);
-      if (L.lane == 0) partial[quadrant] = dot;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) dlog[bh] = (((partial[0] + partial[1]) + partial[2]) + partial[3]) * scale;
-    __syncthreads();  // the tile sets are staged into next
-  }
+  if (dlog != nullptr) state_dot<F>(acc, second, scale, sets, dlog + bh, L);
   if (!second) quadrant_image<F, true>(own, scale, images_a + quadrant * F::kImageBytes, L);
   else quadrant_image<F, false>(own, scale, images_b + quadrant * F::kImageBytes, L);
   __syncthreads();
@@ -688,6 +727,169 @@ __global__ __launch_bounds__(512) void wide_fused_bwd_kernel(const LaunchArgs a,
   r.Y = a.V + base;
   r.out = a.dK + base;
   projected_tiles<F, 8>(r, images_a, tiles, L);
+}
+
+// ---- short sequences (N <= 256), backward: every tile requested at once and kept in registers -----
+//
+// The backward for sequences of at most 256 rows: a wave asks for all its tiles at the start
+// (everything the slice needs is in flight together) and keeps them in registers, so the apply
+// roles read nothing again.  Waves 0-3, which hold (K, V) tiles, compute dV and dK for them and
+// waves 4-7, which hold (Q, dO) tiles, dQ; all three image sets are written as
+// soon as the states are complete (LDS: [S natural | dS natural | dS transposed][per wave: two
+// tiles, 16 floats]; the unit rows and the other tensor's rows of a tile take turns in the two
+// tiles), and the round buffer of the state phase lies over the same memory.
+constexpr int kKeptRows = 256;
+
+template <class F>
+struct KeptLds {
+  static constexpr int kSetBytes = 4 * F::kImageBytes;
+  static constexpr int kTiles = 3 * kSetBytes;
+  static constexpr int kWaveBytes = 2 * kTileBytes + TR * 4;
+  static constexpr int kRoundWave = 4 * kTileBytes;  // state phase, from offset 0
+  static constexpr int kBytes =
+      kTiles + 8 * kWaveBytes > 8 * kRoundWave ? kTiles + 8 * kWaveBytes : 8 * kRoundWave;
+  static_assert(4 * F::Acc::kGroups * 64 * 16 + 64 <= kBytes, "accumulators meet in the same memory");
+};
+
+// The state phase over tiles already in registers (see fused_state_pass); `rounds`: how many of
+// them hold rows of the sequence.
+template <class F, int ROUNDS, int WAVE_BYTES>
+__device__ __forceinline__ void kept_state_pass(typename F::Acc& acc, const WideRaw (&kept)[ROUNDS],
+                                                int rounds, float eps, unsigned char* sets,
+                                                const Lane& L) {
+  const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, group = L.wave >> 2;
+  unsigned char* mine = sets + L.wave * WAVE_BYTES;
+  acc.zero();
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    if (r < rounds) {
+      float inv[2];
+      stage_wide<F, true, true>(kept[r], L, eps, mine, inv);
+      __syncthreads();
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const unsigned char* tile = sets + (4 * group + t) * WAVE_BYTES;
+        acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// The y rows of a tile, as they are, into the two tiles of a wave.
+__device__ __forceinline__ void stage_y(const WideRaw& r, const Lane& L, unsigned char* tiles) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4_t*>(tiles + c * kTileBytes + off) = r.y[h][c];
+  }
+}
+
+// One kept tile in the backward: xhat rows staged, then (K tiles only) dV = khat (scale dS); the y
+// rows staged over them, g = y (natural images)^T and out = (g - xhat (xhat . g)) / r.
+template <class F>
+__device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N, bool plain_too,
+                                              const unsigned char* natural,
+                                              const unsigned char* transposed,
+                                              unsigned char* out_projected, unsigned char* out_plain,
+                                              int stride, float eps, unsigned char* tiles,
+                                              const Lane& L) {
+  float* inv_slot = reinterpret_cast<float*>(tiles + 2 * kTileBytes);
+  float inv[2];
+  stage_wide<F, true, false>(t, L, eps, tiles, inv);
+  const float inv_r = inv_by_row(inv_slot, L, inv);
+  typename F::TileRows E[2];
+  E[0].load(tiles, L);
+  E[1].load(tiles + kTileBytes, L);
+  const int row = row0 + L.i16;
+  if (plain_too) {
+    const Quadrants<F, false> W(transposed, L);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      float o[2 * F::EPL];
+      W.apply(E, q, 2 + q, L, o);
+      if (row < N)
+        store_product_row<F, kStoreStreamed>(out_plain + q * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, o);
+    }
+  }
+  wave_lds_fence();
+  stage_y(t, L, tiles);
+  wave_lds_fence();
+  typename F::TileRows Y[2];
+  Y[0].load(tiles, L);
+  Y[1].load(tiles + kTileBytes, L);
+  const Quadrants<F, false> W(natural, L);
+  float g[2][2 * F::EPL];
+#pragma unroll
+  for (int p = 0; p < 2; ++p) W.apply(Y, 2 * p, 2 * p + 1, L, g[p]);
+  float proj = 0.0f;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    float u[2 * F::EPL];
+    E[p].unpack(u);
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * g[p][c];
+    E[p].forget_unpacked();
+  }
+  proj = row_sum_groups(proj, L);
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    float u[2 * F::EPL];
+    E[p].unpack(u);
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) g[p][c] = (g[p][c] - u[c] * proj) * inv_r;
+    if (row < N)
+      store_product_row<F, kStoreStreamed>(out_projected + p * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, g[p]);
+  }
+  wave_lds_fence();
+}
+
+template <class F>
+__global__ __launch_bounds__(512) void wide_kept_bwd_kernel(const LaunchArgs a, float* __restrict__ dlog) {
+  using Lds = KeptLds<F>;
+  constexpr int kRounds = kKeptRows / (4 * TR);
+  const Lane L;
+  const int bh = blockIdx.x;
+  const size_t base = a.st.slice_base(bh, a.H);
+  const int stride = a.st.row.stride;
+  const int quadrant = L.wave & 3;
+  const bool second = L.wave >= 4;  // waves 4-7: (Q, dO) tiles, dS = sum_i qhat_i^T dO_i, dQ
+  WideRaw kept[kRounds];
+  {
+    const WideSrc src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, a.N, stride);
+    const uint8_t* m = (second || a.mask == nullptr) ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const int row0 = (4 * r + quadrant) * TR;
+      load_wide<true>(kept[r], L, src, row0, row_bits(m, row0, a.N, L));
+    }
+  }
+  const int rounds = (a.N + 4 * TR - 1) / (4 * TR);
+  typename F::Acc acc;
+  kept_state_pass<F, kRounds, Lds::kRoundWave>(acc, kept, rounds, a.eps, smem, L);
+  const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
+  if (dlog != nullptr) state_dot<F>(acc, second, scale, smem, dlog + bh, L);
+  const auto own = [&](int g) { return acc.group(g); };
+  if (!second) {
+    quadrant_image<F, true>(own, scale, smem + quadrant * F::kImageBytes, L);
+  } else {
+    quadrant_image<F, true>(own, scale, smem + Lds::kSetBytes + quadrant * F::kImageBytes, L);
+    quadrant_image<F, false>(own, scale, smem + 2 * Lds::kSetBytes + quadrant * F::kImageBytes, L);
+  }
+  __syncthreads();
+  unsigned char* tiles = smem + Lds::kTiles + L.wave * Lds::kWaveBytes;
+  const unsigned char* natural = smem + (second ? 0 : Lds::kSetBytes);
+  unsigned char* out_projected = (second ? a.dQ : a.dK) + base;
+#pragma unroll 1
+  for (int r = 0; r < rounds; ++r) {
+    const int row0 = (4 * r + quadrant) * TR;
+    if (row0 < a.N)
+      kept_tile_bwd<F>(kept[0], row0, a.N, !second, natural, smem + 2 * Lds::kSetBytes, out_projected,
+                       a.dV + base, stride, a.eps, tiles, L);
+#pragma unroll
+    for (int k = 0; k + 1 < kRounds; ++k) kept[k] = kept[k + 1];
+  }
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -787,6 +989,16 @@ hipError_t fused(const Problem& p, const Plan& plan, bool bwd) {
   constexpr int lds_fwd = FusedLds<F, 1>::kBytes, lds_bwd = FusedLds<F, 2>::kBytes;
   const LaunchArgs a = launch_args(p, plan, nullptr, nullptr);
   const unsigned blocks = static_cast<unsigned>(p.B) * p.H;
+  if (bwd && p.N <= kKeptRows) {
+    constexpr int lds_kept = KeptLds<F>::kBytes;
+    static_assert(lds_kept <= max_lds_bytes<8>(), "three image sets and the tile sets");
+    const hipError_t err =
+        grant_dynamic_lds(reinterpret_cast<const void*>(wide_kept_bwd_kernel<F>), max_lds_bytes<8>());
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((wide_kept_bwd_kernel<F>), dim3(blocks), dim3(512), lds_kept, p.stream, a,
+                       p.dlog_scale);
+    return hipGetLastError();
+  }
   const void* kern = bwd ? reinterpret_cast<const void*>(wide_fused_bwd_kernel<F>)
                          : reinterpret_cast<const void*>(wide_fused_fwd_kernel<F>);
   const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<8>());
