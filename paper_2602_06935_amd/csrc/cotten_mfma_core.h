@@ -307,6 +307,14 @@ struct Half64 {
     X.load(T, L);
     apply(X, W, out);
   }
+  // out += (tile rows) x W
+  static __device__ __forceinline__ void apply_onto(const TileRows& X, const Operand& W,
+                                                    f32x4_t (&out)[4]) {
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) out[nt] = E::mfma16(W.frag[nt][ks], X.a[ks], out[nt]);
+  }
 
   // Products of two 16-row tiles, for the kernels that work tile pair by tile pair:
   // dots(a, b) = X_a X_b^T: lane (j, g) gets rows 4g .. 4g+3 (rows of a) of column j (row of b).
@@ -398,6 +406,14 @@ struct Half64 {
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
                                                           float v0, float v1) {
     *reinterpret_cast<uint32_t*>(image + (image_row(n) * kImageStride + k) * 2) = E::pack2(v0, v1);
+  }
+  // The same in two steps, for writers that split (n, k) into a per-lane and a compile-time part:
+  // image_offset is additive over parts that share no bit of n (a permutation of bits) and in k.
+  static __device__ __forceinline__ int image_offset(int n, int k) {
+    return (image_row(n) * kImageStride + k) * 2;
+  }
+  static __device__ __forceinline__ void write_pair_at(unsigned char* at, float v0, float v1) {
+    *reinterpret_cast<uint32_t*>(at) = E::pack2(v0, v1);
   }
   // element k of image row n
   static __device__ __forceinline__ float image_at(const unsigned char* image, int n, int k) {
@@ -515,6 +531,15 @@ struct F32x32 {
     X.load(T, L);
     apply(X, W, out);
   }
+  // out += (tile rows) x W
+  static __device__ __forceinline__ void apply_onto(const TileRows& X, const Operand& W,
+                                                    f32x4_t (&out)[2]) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        out[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(W.frag[nt][s], X.a[s], out[nt], 0, 0, 0);
+  }
 
   // Products of two 16-row tiles (see Half64): dots(a, b) = X_a X_b^T, lane (j, g) gets rows
   // 4g .. 4g+3 of column j; eight 16x16x4 steps, each lane feeding the column it holds.
@@ -542,6 +567,12 @@ struct F32x32 {
   static __device__ __forceinline__ void write_image_pair(unsigned char* image, int n, int k,
                                                           float v0, float v1) {
     float* p = reinterpret_cast<float*>(image + (n * kImageStride + k) * 4);
+    p[0] = v0;
+    p[1] = v1;
+  }
+  static __device__ __forceinline__ int image_offset(int n, int k) { return (n * kImageStride + k) * 4; }
+  static __device__ __forceinline__ void write_pair_at(unsigned char* at, float v0, float v1) {
+    float* p = reinterpret_cast<float*>(at);
     p[0] = v0;
     p[1] = v1;
   }

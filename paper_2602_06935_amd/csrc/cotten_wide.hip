@@ -128,6 +128,26 @@ __device__ __forceinline__ float inv_by_row(float* slot, const Lane& L, const fl
   return slot[L.i16];
 }
 
+// No row of the tile takes part (all of them masked or beyond the sequence): the wave can write
+// the zeros such rows come out as without computing them.
+__device__ __forceinline__ bool tile_dead(const WideRaw& r) {
+  return __builtin_amdgcn_ballot_w64(r.live != 0) == 0;
+}
+
+template <class F>
+__device__ __forceinline__ void store_zero_rows(unsigned char* out, int row0, int r_end, int stride,
+                                                const Lane& L) {
+  float z[2 * F::EPL];
+#pragma unroll
+  for (int i = 0; i < 2 * F::EPL; ++i) z[i] = 0.0f;
+  const int row = row0 + L.i16;
+  if (row < r_end) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      store_product_row<F, kStoreStreamed>(out + q * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, z);
+  }
+}
+
 extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
 // ---- state kernel -------------------------------------------------------------------------------
@@ -257,19 +277,17 @@ struct Quadrants {
   // out = X[half 0] W(i0) + X[half 1] W(i1), images numbered 2 p + q
   __device__ __forceinline__ void apply(const typename F::TileRows (&X)[2], int i0, int i1,
                                         const Lane& L, float (&out)[2 * F::EPL]) const {
-    f32x4_t a[F::NT], b[F::NT];
+    f32x4_t a[F::NT];
     if (HOLD) {
       F::apply(X[0], held[i0], a);
-      F::apply(X[1], held[i1], b);
+      F::apply_onto(X[1], held[i1], a);
     } else {
       typename F::Operand W;
       W.load(images + i0 * F::kImageBytes, L);
       F::apply(X[0], W, a);
       W.load(images + i1 * F::kImageBytes, L);
-      F::apply(X[1], W, b);
+      F::apply_onto(X[1], W, a);
     }
-#pragma unroll
-    for (int nt = 0; nt < F::NT; ++nt) a[nt] += b[nt];
     product_rows<F>(a, out);
   }
 };
@@ -301,6 +319,10 @@ template <class F, bool HOLD>
 __device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD>& W, const WideRaw& cur, int row0,
                                            int r_end, unsigned char* out, int stride, float eps,
                                            unsigned char* tiles, const Lane& L) {
+  if (tile_dead(cur)) {
+    store_zero_rows<F>(out, row0, r_end, stride, L);
+    return;
+  }
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
   float inv[2];
   stage_wide<F, false, false>(cur, L, eps, tiles, inv);
@@ -375,6 +397,12 @@ __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsign
   load_wide<true>(cur, L, src, row0, row_bits(a.mask, row0, a.r_end, L));
   int next_bits = row_bits(a.mask, row0 + kRoundRows, a.r_end, L);
   for (; row0 < a.r_end; row0 += kRoundRows) {
+    if (tile_dead(cur)) {  // nothing was fetched: zeros
+      load_wide<true>(cur, L, src, row0 + kRoundRows, next_bits);
+      next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
+      store_zero_rows<F>(a.out, row0, a.r_end, a.stride, L);
+      continue;
+    }
     float inv[2];
     stage_wide<F, true, true>(cur, L, a.eps, tiles, inv);
     load_wide<true>(cur, L, src, row0 + kRoundRows, next_bits);
@@ -523,13 +551,16 @@ struct FusedLds {
 
 // The state phase of a group of four waves (wave & 3: the quadrant): every wave stages the 16 rows
 // from `first_row` on of each round into its own tile set and adds the four tile sets of its group
-// (wave >> 2) to its quadrant.  Rows at and beyond N, and masked rows, are never fetched.
+// (wave >> 2) to its quadrant - or, `swapped`, the transposed sum (y tile)^T (x tile) with the two
+// operands changing places, from which the natural image is the one that can be written
+// straight from the lane.  Rows at and beyond N, and masked rows, are never fetched.
 template <class F, int WAVE_BYTES>
 __device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const WideSrc& src,
                                                  const uint8_t* __restrict__ m, int N, int first_row,
                                                  int round_rows, float eps, unsigned char* sets,
-                                                 const Lane& L) {
+                                                 const Lane& L, bool swapped = false) {
   const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, group = L.wave >> 2;
+  const int left = (swapped ? 2 + q : p) * kTileBytes, right = (swapped ? p : 2 + q) * kTileBytes;
   unsigned char* mine = sets + L.wave * WAVE_BYTES;
   acc.zero();
   WideRaw cur;
@@ -544,7 +575,7 @@ __device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const Wid
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const unsigned char* tile = sets + (4 * group + t) * WAVE_BYTES;
-      acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
+      acc.mfma(tile + left, tile + right, L);
     }
     __syncthreads();  // the tile sets are overwritten next
   }
@@ -556,17 +587,25 @@ __device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const Wid
 // group, odd lanes the last two; each gets the other column of its rows from its neighbour).
 template <class F, bool NATURAL, class Get>
 __device__ __forceinline__ void quadrant_image(Get get, float scale, unsigned char* image, const Lane& L) {
+  // (row, column) of the first value of a group = a part that depends on the lane only plus a
+  // part that depends on the group only; the image offsets of the two add up, so the second
+  // becomes the immediate offset of the write
+  const int lane_row = F::Acc::group_row(0, L), lane_col = F::Acc::group_col(0, L);
+  const bool odd = (lane_col & 1) != 0;
+  Lane zero = L;
+  zero.set(0);
+  unsigned char* at = image + (NATURAL ? F::image_offset(lane_row + (odd ? 2 : 0), lane_col & ~1)
+                                       : F::image_offset(lane_col, lane_row));
 #pragma unroll
   for (int g = 0; g < F::Acc::kGroups; ++g) {
     const f32x4_t v = get(g) * scale;
-    const int row = F::Acc::group_row(g, L), col = F::Acc::group_col(g, L);
+    const int row = F::Acc::group_row(g, zero), col = F::Acc::group_col(g, zero);  // the group's part
     if (!NATURAL) {
-      F::write_image_pair(image, col, row, v[0], v[1]);
-      F::write_image_pair(image, col, row + 2, v[2], v[3]);
+      F::write_pair_at(at + F::image_offset(col, row), v[0], v[1]);
+      F::write_pair_at(at + F::image_offset(col, row + 2), v[2], v[3]);
     } else {
       // The lane sends what its neighbour wants (the choice is made on the sending side: a
       // choice between two values received from the neighbour would be evaluated over there).
-      const bool odd = (col & 1) != 0;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const float mine = odd ? v[2 + i] : v[i];
@@ -575,7 +614,7 @@ __device__ __forceinline__ void quadrant_image(Get get, float scale, unsigned ch
         int got = __builtin_amdgcn_update_dpp(0, sent, 0xB1, 0xF, 0xF, true);  // lane ^ 1
         asm volatile("" : "+v"(got));
         const float other = __builtin_bit_cast(float, got);
-        F::write_image_pair(image, row + (odd ? 2 : 0) + i, col & ~1, odd ? other : mine, odd ? mine : other);
+        F::write_pair_at(at + F::image_offset(row + i, col), odd ? other : mine, odd ? mine : other);
       }
     }
   }
@@ -688,16 +727,20 @@ __global__ __launch_bounds__(512) void wide_fused_bwd_kernel(const LaunchArgs a,
   const int quadrant = L.wave & 3;
   const bool second = L.wave >= 4;  // waves 4-7: dS = sum_i qhat_i^T dO_i
   const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
+  // S is needed as natural images only: its waves sum up the transposed quadrants, unless the
+  // accumulators of S and dS are to meet lane by lane for <S, dS>
+  const bool swapped = !second && dlog == nullptr;
   typename F::Acc acc;
   {
     const WideSrc src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, a.N, a.st.row.stride);
     fused_state_pass<F, Lds::kWaveBytes>(acc, src, second ? nullptr : keys, a.N, quadrant * TR, 4 * TR,
-                                         a.eps, sets, L);
+                                         a.eps, sets, L, swapped);
   }
   const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
   const auto own = [&](int g) { return acc.group(g); };
   if (dlog != nullptr) state_dot<F>(acc, second, scale, sets, dlog + bh, L);
-  if (!second) quadrant_image<F, true>(own, scale, images_a + quadrant * F::kImageBytes, L);
+  if (swapped) quadrant_image<F, false>(own, scale, images_a + quadrant * F::kImageBytes, L);
+  else if (!second) quadrant_image<F, true>(own, scale, images_a + quadrant * F::kImageBytes, L);
   else quadrant_image<F, false>(own, scale, images_b + quadrant * F::kImageBytes, L);
   __syncthreads();
 
@@ -737,7 +780,7 @@ __global__ __launch_bounds__(512) void wide_fused_bwd_kernel(const LaunchArgs a,
 // waves 4-7, which hold (Q, dO) tiles, dQ; all three image sets are written as
 // soon as the states are complete (LDS: [S natural | dS natural | dS transposed][per wave: two
 // tiles, 16 floats]; the unit rows and the other tensor's rows of a tile take turns in the two
-// tiles), and the round buffer of the state phase lies over the same memory.
+// tiles), and the two round buffers of the state phase lie over the same memory.
 constexpr int kKeptRows = 256;
 
 template <class F>
@@ -745,35 +788,42 @@ struct KeptLds {
   static constexpr int kSetBytes = 4 * F::kImageBytes;
   static constexpr int kTiles = 3 * kSetBytes;
   static constexpr int kWaveBytes = 2 * kTileBytes + TR * 4;
-  static constexpr int kRoundWave = 4 * kTileBytes;  // state phase, from offset 0
+  static constexpr int kRoundWave = 4 * kTileBytes;  // state phase: two round buffers from offset 0
+  static constexpr int kRoundBuffer = 8 * kRoundWave;
   static constexpr int kBytes =
-      kTiles + 8 * kWaveBytes > 8 * kRoundWave ? kTiles + 8 * kWaveBytes : 8 * kRoundWave;
+      kTiles + 8 * kWaveBytes > 2 * kRoundBuffer ? kTiles + 8 * kWaveBytes : 2 * kRoundBuffer;
   static_assert(4 * F::Acc::kGroups * 64 * 16 + 64 <= kBytes, "accumulators meet in the same memory");
 };
 
 // The state phase over tiles already in registers (see fused_state_pass); `rounds`: how many of
-// them hold rows of the sequence.
-template <class F, int ROUNDS, int WAVE_BYTES>
+// them hold rows of the sequence.  Two round buffers (the second `SECOND_BUFFER` bytes behind the
+// first) take turns: the tiles of the next round are staged while those of this one are added
+// up, one barrier per round.  Ends with a barrier (the buffers are free).
+template <class F, int ROUNDS, int WAVE_BYTES, int SECOND_BUFFER>
 __device__ __forceinline__ void kept_state_pass(typename F::Acc& acc, const WideRaw (&kept)[ROUNDS],
                                                 int rounds, float eps, unsigned char* sets,
-                                                const Lane& L) {
+                                                const Lane& L, bool swapped) {
   const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, group = L.wave >> 2;
+  const int left = (swapped ? 2 + q : p) * kTileBytes, right = (swapped ? p : 2 + q) * kTileBytes;
   unsigned char* mine = sets + L.wave * WAVE_BYTES;
   acc.zero();
+  float inv[2];
+  stage_wide<F, true, true>(kept[0], L, eps, mine, inv);
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
     if (r < rounds) {
-      float inv[2];
-      stage_wide<F, true, true>(kept[r], L, eps, mine, inv);
-      __syncthreads();
+      __syncthreads();  // round r is staged; nobody reads the other buffer any more
+      if (r + 1 < ROUNDS && r + 1 < rounds)
+        stage_wide<F, true, true>(kept[r + 1 < ROUNDS ? r + 1 : 0], L, eps,
+                                  mine + ((r + 1) & 1) * SECOND_BUFFER, inv);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const unsigned char* tile = sets + (4 * group + t) * WAVE_BYTES;
-        acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
+        const unsigned char* tile = sets + (r & 1) * SECOND_BUFFER + (4 * group + t) * WAVE_BYTES;
+        acc.mfma(tile + left, tile + right, L);
       }
-      __syncthreads();
     }
   }
+  __syncthreads();
 }
 
 // The y rows of a tile, as they are, into the two tiles of a wave.
@@ -795,6 +845,11 @@ __device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N,
                                               unsigned char* out_projected, unsigned char* out_plain,
                                               int stride, float eps, unsigned char* tiles,
                                               const Lane& L) {
+  if (tile_dead(t)) {
+    if (plain_too) store_zero_rows<F>(out_plain, row0, N, stride, L);
+    store_zero_rows<F>(out_projected, row0, N, stride, L);
+    return;
+  }
   float* inv_slot = reinterpret_cast<float*>(tiles + 2 * kTileBytes);
   float inv[2];
   stage_wide<F, true, false>(t, L, eps, tiles, inv);
@@ -855,23 +910,31 @@ __global__ __launch_bounds__(512) void wide_kept_bwd_kernel(const LaunchArgs a, 
   const int stride = a.st.row.stride;
   const int quadrant = L.wave & 3;
   const bool second = L.wave >= 4;  // waves 4-7: (Q, dO) tiles, dS = sum_i qhat_i^T dO_i, dQ
+  // which 16 rows of a round the wave holds: the two waves of a SIMD (w and w + 4) take different
+  // ones, so that the round with a ragged end does not leave both with a tile more than the rest
+  const int slot = second ? (quadrant + 2) & 3 : quadrant;
   WideRaw kept[kRounds];
   {
     const WideSrc src((second ? a.Q : a.K) + base, (second ? a.dO : a.V) + base, a.N, stride);
     const uint8_t* m = (second || a.mask == nullptr) ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
-      const int row0 = (4 * r + quadrant) * TR;
+      const int row0 = (4 * r + slot) * TR;
       load_wide<true>(kept[r], L, src, row0, row_bits(m, row0, a.N, L));
     }
   }
   const int rounds = (a.N + 4 * TR - 1) / (4 * TR);
   typename F::Acc acc;
-  kept_state_pass<F, kRounds, Lds::kRoundWave>(acc, kept, rounds, a.eps, smem, L);
+  // S is needed as natural images only: its waves sum up the transposed quadrants, unless the
+  // accumulators of S and dS are to meet lane by lane for <S, dS>
+  const bool swapped = !second && dlog == nullptr;
+  kept_state_pass<F, kRounds, Lds::kRoundWave, Lds::kRoundBuffer>(acc, kept, rounds, a.eps, smem, L, swapped);
   const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
   if (dlog != nullptr) state_dot<F>(acc, second, scale, smem, dlog + bh, L);
   const auto own = [&](int g) { return acc.group(g); };
-  if (!second) {
+  if (swapped) {
+    quadrant_image<F, false>(own, scale, smem + quadrant * F::kImageBytes, L);
+  } else if (!second) {
     quadrant_image<F, true>(own, scale, smem + quadrant * F::kImageBytes, L);
   } else {
     quadrant_image<F, true>(own, scale, smem + Lds::kSetBytes + quadrant * F::kImageBytes, L);
@@ -883,7 +946,7 @@ __global__ __launch_bounds__(512) void wide_kept_bwd_kernel(const LaunchArgs a, 
   unsigned char* out_projected = (second ? a.dQ : a.dK) + base;
 #pragma unroll 1
   for (int r = 0; r < rounds; ++r) {
-    const int row0 = (4 * r + quadrant) * TR;
+    const int row0 = (4 * r + slot) * TR;
     if (row0 < a.N)
       kept_tile_bwd<F>(kept[0], row0, a.N, !second, natural, smem + 2 * Lds::kSetBytes, out_projected,
                        a.dV + base, stride, a.eps, tiles, L);

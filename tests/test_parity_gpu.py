@@ -60,7 +60,7 @@ def test_cfg1_forward_full_size(oracle, seed):
 
 
 @pytest.mark.parametrize("name,seed", [("cfg2", 0), ("cfg2", 42), ("cfg3", 0), ("cfg3", 123),
-                                       ("cfg4", 0), ("cfg4", 42)])
+                                       ("cfg4", 0), ("cfg4", 42), ("emb256", 0), ("emb256", 42)])
 def test_workloads_full_size(oracle, name, seed):
     _check_batch(oracle, make_batch(name, seed))
 
