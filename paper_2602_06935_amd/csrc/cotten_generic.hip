@@ -463,7 +463,7 @@ hipError_t run_bwd(const Problem& p, const Plan& plan) {
 // The same launch structure with the matrix-core kernels for 256-byte rows (cotten_wide.hip) in
 // place of the vector-ALU state and apply kernels; reduction, kept state and <S, dS> as above.
 hipError_t run_wide(const Problem& p, const Plan& plan, bool bwd) {
-  if (plan.splits == 1) return launch_wide_fused(p, plan, bwd);
+  if (wide_fused_applies(p.B, p.H, plan.splits, bwd)) return launch_wide_fused(p, plan, bwd);
   const int BH = p.B * p.H;
   const int dd = p.D * p.D;
   if (hipError_t err = launch_wide_states(p, plan, bwd)) return err;
@@ -573,7 +573,7 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_re
     // partial states, plus the reduced states when there is more than one partial
     // (256-byte rows, sequence not cut: the state never leaves the compute unit)
     plan.workspace_floats =
-        wide_supports(dtype, D) && splits == 1
+        wide_supports(dtype, D) && wide_fused_applies(B, H, static_cast<int>(splits), is_bwd)
             ? 0
             : static_cast<size_t>(BH) * D * D * nstates * (splits + (splits > 1 ? 1 : 0));
   }

@@ -78,8 +78,9 @@ bool wide_supports(int dtype, int D);
 hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd);
 hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
                              const float* dstates, bool bwd);
-// Sequences that are not cut (plan.splits == 1): one launch per direction, the state stays in
+// Sequences that are not cut (wide_fused_applies): one launch per direction, the state stays in
 // LDS, no workspace; the forward writes p.saved_state, the backward p.dlog_scale, when given.
+bool wide_fused_applies(int B, int H, int splits, bool bwd);
 hipError_t launch_wide_fused(const Problem& p, const Plan& plan, bool bwd);
 
 // MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows), and

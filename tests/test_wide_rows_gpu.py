@@ -42,6 +42,11 @@ def _inputs(seed, dtype, B, H, N, d):
     ("f32", 280, 2, 100, 64),
     ("bf16", 2, 2, 3000, 128),      # long sequences cut over many workgroups
     ("f32", 1, 3, 2500, 64),
+    ("bf16", 130, 2, 300, 128),     # one launch per direction, tiles streamed (N > 256)
+    ("f32", 128, 2, 520, 64),
+    ("f16", 100, 1, 200, 128),      # one launch per direction, the backward's tiles kept
+    ("bf16", 100, 1, 256, 128),     # the longest sequence the kept backward takes
+    ("bf16", 100, 1, 257, 128),     # the shortest it does not
 ])
 def test_wide_rows_parity(oracle, dtype, B, H, N, d):
     print(f"[wide rows] {dtype} B={B} H={H} N={N} d={d}", flush=True)
@@ -66,11 +71,15 @@ def test_wide_rows_parity(oracle, dtype, B, H, N, d):
     assert torch.equal(O, O2) and all(torch.equal(a, c) for a, c in zip((dQ, dK, dV), g2))
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
-def test_wide_rows_layout_scales_state_dlog(oracle, dtype, d):
+@pytest.mark.parametrize("dtype,d,B,H,N", [
+    ("bf16", 128, 3, 3, 333), ("f32", 64, 3, 3, 333),    # state, reduction, apply launches
+    ("bf16", 128, 45, 2, 120), ("f32", 64, 45, 2, 120),  # one launch, the backward's tiles kept
+    ("bf16", 128, 130, 2, 300), ("f32", 64, 130, 2, 300),  # one launch, tiles streamed
+])
+def test_wide_rows_layout_scales_state_dlog(oracle, dtype, d, B, H, N):
     """[B,N,H,d] layout bit for bit; per-slice scales; the kept state against the oracle's and
     read back by the backward; d loss / d log(scale) = sum_i dO_i . O_i; garbage in masked rows."""
-    B, H, N = 3, 3, 333
+    print(f"[wide rows] layout / scales / state / dlog: {dtype} B={B} H={H} N={N} d={d}", flush=True)
     Q, K, V, dO, mask = _inputs(7999 + d, dtype, B, H, N, d)
     tq, tk, tv, tg = (to_gpu(x, dtype) for x in (Q, K, V, dO))
     tm = torch.from_numpy(mask).cuda()
