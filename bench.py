@@ -250,7 +250,7 @@ def read_clocks():
 # kernels one call launches (slice kept in LDS or one workgroup per slice: one kernel; long
 # sequences cut over several workgroups: two forward, three backward)
 BWD_KERNELS = ("resident_bwd_kernel", "fused_bwd_kernel", "split_state_kernel", "split_q_kernel",
-               "split_kv_kernel")
+               "split_kv_kernel", "wide_kept_bwd_kernel", "wide_fused_bwd_kernel")
 
 
 def profile_figures(workload, kernel_tags):
