@@ -47,6 +47,11 @@ def _inputs(seed, dtype, B, H, N, d):
     ("f16", 100, 1, 200, 128),      # one launch per direction, the backward's tiles kept
     ("bf16", 100, 1, 256, 128),     # the longest sequence the kept backward takes
     ("bf16", 100, 1, 257, 128),     # the shortest it does not
+    ("f16", 128, 2, 300, 128),      # one launch, tiles streamed, fp16
+    ("f16", 2, 2, 600, 128),        # three launches, workgroups of eight waves, fp16
+    ("bf16", 100, 2, 600, 128),     # three launches, workgroups of four waves (600 of them)
+    ("f32", 100, 2, 600, 64),
+    ("f16", 100, 2, 600, 128),
 ])
 def test_wide_rows_parity(oracle, dtype, B, H, N, d):
     print(f"[wide rows] {dtype} B={B} H={H} N={N} d={d}", flush=True)
