@@ -107,7 +107,8 @@ int run(bool bwd, const void* Q, const void* K, const void* V, const uint8_t* ma
     return COTTEN_ERR_BAD_PARAM;
   if (prm->feature_map == COTTEN_MAP_ELU1) {
     if (prm->causal != 0) return COTTEN_ERR_BAD_PARAM;
-    if (!cotten::mfma_supports(prm->dtype, d_h)) return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
+    if (!cotten::mfma_supports(prm->dtype, d_h) && !cotten::wide_supports(prm->dtype, d_h))
+      return COTTEN_ERR_UNSUPPORTED_HEAD_DIM;
   }
   p.feature_map = prm->feature_map;
   const bool causal = prm->causal != 0;

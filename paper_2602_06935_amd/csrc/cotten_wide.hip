@@ -87,14 +87,30 @@ __device__ __forceinline__ void load_wide(WideRaw& r, const Lane& L, const WideS
 }
 
 // The tile into LDS as four 16 x 128-byte tiles [x half 0 | x half 1 | y half 0 | y half 1]
-// (each in the layout of cotten_mfma_core.h); x normalised over the whole row, or raw.
-// inv[h] = 1/r of row r8 + 8 h (0 for a row that does not take part).
-template <class F, bool NORMALIZE, bool USE_Y>
+// (each in the layout of cotten_mfma_core.h); x raw, normalised over the whole row, or through
+// the element-wise map of the format (XMODE, see stage() in cotten_mfma_core.h).
+// inv[h] = 1/r of row r8 + 8 h (0 for a row that does not take part; with the element-wise map 1
+// for a row that does, and a row that does not is written as zeros explicitly: phi(0) is not 0).
+template <class F, int XMODE, bool USE_Y>
 __device__ __forceinline__ void stage_wide(const WideRaw& r, const Lane& L, float eps,
                                            unsigned char* tiles, float (&inv)[2]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     float f[2][F::EPL];
+    const bool live = ((r.live >> h) & 1) != 0;
+    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+    if (XMODE == kXFeature) {
+      inv[h] = live ? 1.0f : 0.0f;
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        F::unpack(r.x[h][c], f[c]);
+#pragma unroll
+        for (int i = 0; i < F::EPL; ++i) f[c][i] = live ? elu1(f[c][i]) : 0.0f;
+        *reinterpret_cast<u32x4_t*>(tiles + c * kTileBytes + off) = F::pack(f[c]);
+        if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (2 + c) * kTileBytes + off) = r.y[h][c];
+      }
+      continue;
+    }
     float ss = 0.0f;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -102,11 +118,10 @@ __device__ __forceinline__ void stage_wide(const WideRaw& r, const Lane& L, floa
 #pragma unroll
       for (int i = 0; i < F::EPL; ++i) ss += f[c][i] * f[c][i];
     }
-    inv[h] = inv_norm_or_zero(row_sum8(ss), eps, (r.live >> h) & 1);
-    const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
+    inv[h] = inv_norm_or_zero(row_sum8(ss), eps, live);
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-      if (NORMALIZE) {
+      if (XMODE == kXNormalized) {
 #pragma unroll
         for (int i = 0; i < F::EPL; ++i) f[c][i] *= inv[h];
         *reinterpret_cast<u32x4_t*>(tiles + c * kTileBytes + off) = F::pack(f[c]);
@@ -116,6 +131,13 @@ __device__ __forceinline__ void stage_wide(const WideRaw& r, const Lane& L, floa
       if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (2 + c) * kTileBytes + off) = r.y[h][c];
     }
   }
+}
+
+// How the x rows enter a product whose result is divided by r afterwards: raw under the cosine
+// map (1/r applied to the result), mapped under the element-wise one (1/r is then 1).
+template <class F>
+constexpr int plain_mode() {
+  return F::kMap == kMapElu1 ? kXFeature : kXRaw;
 }
 
 // 1/r of the tile's rows from the load layout to the product layout, through 16 floats of LDS.
@@ -184,7 +206,7 @@ __global__ __launch_bounds__(64 * WAVES) void wide_state_kernel(
   int next_bits = row_bits(m, r_begin + kRoundRows + L.wave * TR, r_end, L);
   for (int r0 = r_begin; r0 < r_end; r0 += kRoundRows) {
     float inv[2];
-    stage_wide<F, true, true>(cur, L, eps, mine, inv);
+    stage_wide<F, mapped_mode<F>(), true>(cur, L, eps, mine, inv);
     // the wave's tile of the next round travels while this round is added up
     load_wide<true>(cur, L, src, r0 + kRoundRows + L.wave * TR, next_bits);
     next_bits = row_bits(m, r0 + 2 * kRoundRows + L.wave * TR, r_end, L);
@@ -325,7 +347,7 @@ __device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD>& W, const Wi
   }
   float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
   float inv[2];
-  stage_wide<F, false, false>(cur, L, eps, tiles, inv);
+  stage_wide<F, plain_mode<F>(), false>(cur, L, eps, tiles, inv);
   const float inv_r = inv_by_row(inv_slot, L, inv);
   typename F::TileRows X[2];
   X[0].load(tiles, L);
@@ -382,6 +404,35 @@ __device__ __forceinline__ void plain_role(const ApplyArgs& a) {
   plain_tiles<F, WAVES, HOLD>(a, images, tiles, L);
 }
 
+// The row epilogue of dQ and dK over both halves of a row, E holding the mapped rows (xhat, or
+// phi(x)):  cosine map  g <- (g - xhat (xhat . g)) / r;   ELU + 1  g <- g * phi'(x), phi' = min(phi, 1).
+template <class F>
+__device__ __forceinline__ void finish_projected(float (&g)[2][2 * F::EPL], typename F::TileRows (&E)[2],
+                                                 float inv_r, const Lane& L) {
+  if (F::kMap == kMapElu1) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) feature_grad_rows<F>(g[p], E[p]);
+    return;
+  }
+  float proj = 0.0f;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    float u[2 * F::EPL];
+    E[p].unpack(u);
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * g[p][c];
+    E[p].forget_unpacked();
+  }
+  proj = row_sum_groups(proj, L);
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    float u[2 * F::EPL];
+    E[p].unpack(u);
+#pragma unroll
+    for (int c = 0; c < 2 * F::EPL; ++c) g[p][c] = (g[p][c] - u[c] * proj) * inv_r;
+  }
+}
+
 // out rows = (g - xhat (xhat . g)) / r with g = (y rows) M^T, contraction over the columns of M:
 //   dQ from (Q, dO) and scale S;   dK from (K, V) and scale dS (masked rows come out as zeros).
 // `images`: the four natural quadrant images of scale * M.
@@ -404,7 +455,7 @@ __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsign
       continue;
     }
     float inv[2];
-    stage_wide<F, true, true>(cur, L, a.eps, tiles, inv);
+    stage_wide<F, mapped_mode<F>(), true>(cur, L, a.eps, tiles, inv);
     load_wide<true>(cur, L, src, row0 + kRoundRows, next_bits);
     next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
     const float inv_r = inv_by_row(inv_slot, L, inv);
@@ -417,23 +468,10 @@ __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsign
       W.apply(Y, 2 * p, 2 * p + 1, L, g[p]);
     E[0].load(tiles, L);
     E[1].load(tiles + kTileBytes, L);
-    float proj = 0.0f;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      float u[2 * F::EPL];
-      E[p].unpack(u);
-#pragma unroll
-      for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * g[p][c];
-      E[p].forget_unpacked();
-    }
-    proj = row_sum_groups(proj, L);
+    finish_projected<F>(g, E, inv_r, L);
     const int row = row0 + L.i16;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-      float u[2 * F::EPL];
-      E[p].unpack(u);
-#pragma unroll
-      for (int c = 0; c < 2 * F::EPL; ++c) g[p][c] = (g[p][c] - u[c] * proj) * inv_r;
       if (row < a.r_end)
         store_product_row<F, kStoreStreamed>(a.out + p * kHalfBytes, row, RowAddr{a.stride, kHalfBytes}, L, g[p]);
     }
@@ -568,7 +606,7 @@ __device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const Wid
   int next_bits = row_bits(m, first_row + round_rows, N, L);
   for (int r0 = 0; r0 < N; r0 += round_rows) {
     float inv[2];
-    stage_wide<F, true, true>(cur, L, eps, mine, inv);
+    stage_wide<F, mapped_mode<F>(), true>(cur, L, eps, mine, inv);
     load_wide<true>(cur, L, src, r0 + round_rows + first_row, next_bits);
     next_bits = row_bits(m, r0 + 2 * round_rows + first_row, N, L);
     __syncthreads();
@@ -808,13 +846,13 @@ __device__ __forceinline__ void kept_state_pass(typename F::Acc& acc, const Wide
   unsigned char* mine = sets + L.wave * WAVE_BYTES;
   acc.zero();
   float inv[2];
-  stage_wide<F, true, true>(kept[0], L, eps, mine, inv);
+  stage_wide<F, mapped_mode<F>(), true>(kept[0], L, eps, mine, inv);
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
     if (r < rounds) {
       __syncthreads();  // round r is staged; nobody reads the other buffer any more
       if (r + 1 < ROUNDS && r + 1 < rounds)
-        stage_wide<F, true, true>(kept[r + 1 < ROUNDS ? r + 1 : 0], L, eps,
+        stage_wide<F, mapped_mode<F>(), true>(kept[r + 1 < ROUNDS ? r + 1 : 0], L, eps,
                                   mine + ((r + 1) & 1) * SECOND_BUFFER, inv);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -852,7 +890,7 @@ __device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N,
   }
   float* inv_slot = reinterpret_cast<float*>(tiles + 2 * kTileBytes);
   float inv[2];
-  stage_wide<F, true, false>(t, L, eps, tiles, inv);
+  stage_wide<F, mapped_mode<F>(), false>(t, L, eps, tiles, inv);
   const float inv_r = inv_by_row(inv_slot, L, inv);
   typename F::TileRows E[2];
   E[0].load(tiles, L);
@@ -878,22 +916,9 @@ __device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N,
   float g[2][2 * F::EPL];
 #pragma unroll
   for (int p = 0; p < 2; ++p) W.apply(Y, 2 * p, 2 * p + 1, L, g[p]);
-  float proj = 0.0f;
+  finish_projected<F>(g, E, inv_r, L);
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
-    float u[2 * F::EPL];
-    E[p].unpack(u);
-#pragma unroll
-    for (int c = 0; c < 2 * F::EPL; ++c) proj += u[c] * g[p][c];
-    E[p].forget_unpacked();
-  }
-  proj = row_sum_groups(proj, L);
-#pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    float u[2 * F::EPL];
-    E[p].unpack(u);
-#pragma unroll
-    for (int c = 0; c < 2 * F::EPL; ++c) g[p][c] = (g[p][c] - u[c] * proj) * inv_r;
     if (row < N)
       store_product_row<F, kStoreStreamed>(out_projected + p * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, g[p]);
   }
@@ -1080,11 +1105,21 @@ hipError_t fused(const Problem& p, const Plan& plan, bool bwd) {
 
 bool wide_supports(int dtype, int D) { return dtype == 0 ? D == 64 : D == 128; }
 
-hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd) {
+namespace {
+// fn(F{}) for the element format of the problem, with the feature map of its params
+template <class Fn>
+hipError_t for_format(const Problem& p, Fn fn) {
   using namespace mfma;
-  return p.dtype == 0   ? wide::states<F32x32>(p, plan, bwd)
-         : p.dtype == 1 ? wide::states<Bf16x64>(p, plan, bwd)
-                        : wide::states<F16x64>(p, plan, bwd);
+  if (p.feature_map == kMapElu1)
+    return p.dtype == 0   ? fn(WithElu1<F32x32>{})
+           : p.dtype == 1 ? fn(WithElu1<Bf16x64>{})
+                          : fn(WithElu1<F16x64>{});
+  return p.dtype == 0 ? fn(F32x32{}) : p.dtype == 1 ? fn(Bf16x64{}) : fn(F16x64{});
+}
+}  // namespace
+
+hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd) {
+  return for_format(p, [&](auto f) { return wide::states<decltype(f)>(p, plan, bwd); });
 }
 
 // One launch per direction whenever the sequence is not cut - except a backward over so few
@@ -1095,19 +1130,13 @@ bool wide_fused_applies(int B, int H, int splits, bool bwd) {
 }
 
 hipError_t launch_wide_fused(const Problem& p, const Plan& plan, bool bwd) {
-  using namespace mfma;
   if (!wide_fused_applies(p.B, p.H, plan.splits, bwd)) return hipErrorInvalidValue;
-  return p.dtype == 0   ? wide::fused<F32x32>(p, plan, bwd)
-         : p.dtype == 1 ? wide::fused<Bf16x64>(p, plan, bwd)
-                        : wide::fused<F16x64>(p, plan, bwd);
+  return for_format(p, [&](auto f) { return wide::fused<decltype(f)>(p, plan, bwd); });
 }
 
 hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
                              const float* dstates, bool bwd) {
-  using namespace mfma;
-  return p.dtype == 0   ? wide::apply<F32x32>(p, plan, states, dstates, bwd)
-         : p.dtype == 1 ? wide::apply<Bf16x64>(p, plan, states, dstates, bwd)
-                        : wide::apply<F16x64>(p, plan, states, dstates, bwd);
+  return for_format(p, [&](auto f) { return wide::apply<decltype(f)>(p, plan, states, dstates, bwd); });
 }
 
 }  // namespace cotten

@@ -1,6 +1,7 @@
 """GPU parity of the ELU + 1 feature map (params->feature_map = COTTEN_MAP_ELU1, the
 linear-attention comparison model of the paper's section "Linear Attention Models") against the
-oracle's N x N statement of it, on the fused and split matrix-core kernels."""
+oracle's N x N statement of it, on the fused and split matrix-core kernels and those for
+256-byte rows."""
 import numpy as np
 import pytest
 import torch
@@ -23,6 +24,11 @@ CASES = [
     ("f32", 2, 2, 1030, 32),     # sequence cut over several workgroups
     ("bf16", 2, 2, 1500, 64),
     ("f32", 1, 1, 1, 32),
+    ("bf16", 4, 2, 200, 128),    # 256-byte rows: one-launch forward, three-launch backward
+    ("bf16", 100, 1, 130, 128),  # one launch per direction, the backward's tiles kept
+    ("f32", 100, 1, 77, 64),
+    ("f32", 128, 2, 300, 64),    # one launch per direction, tiles streamed
+    ("f16", 2, 2, 600, 128),     # sequence cut over several workgroups
 ]
 
 
@@ -94,7 +100,7 @@ def test_elu_feature_map_layout_and_refusals(oracle):
     with pytest.raises(binding.CottenError) as e:
         binding.cotten_attn_fwd(tq, tk, tv, tm, feature_map="elu1", causal=True)
     assert e.value.status == -7
-    big = torch.zeros(1, 1, 8, 64, device="cuda")     # fp32 d_h = 64: vector-ALU kernels only
+    big = torch.zeros(1, 1, 8, 128, device="cuda")    # fp32 d_h = 128: vector-ALU kernels only
     with pytest.raises(binding.CottenError) as e:
         binding.cotten_attn_fwd(big, big, big, None, feature_map="elu1")
     assert e.value.status == -3
