@@ -125,3 +125,20 @@ def test_wide_rows_layout_scales_state_dlog(oracle, dtype, d, B, H, N):
     assert rel_l2(dlog.double().cpu().numpy(), ref_dlog) <= 5 * bar
     ref_state = oracle.state(K, V, mask)
     assert rel_l2(state.double().cpu().numpy(), ref_state) <= bar
+
+
+@pytest.mark.parametrize("dtype,B,H,N,d", [("bf16", 100, 1, 200, 128), ("f32", 128, 2, 300, 64),
+                                           ("bf16", 3, 1, 700, 128)])
+def test_wide_rows_without_mask(oracle, dtype, B, H, N, d):
+    """mask = NULL: every key takes part (kept tiles, streamed tiles, three launches)."""
+    print(f"[wide rows] no mask: {dtype} B={B} H={H} N={N} d={d}", flush=True)
+    Q, K, V, dO, _ = _inputs(7100 + N + d, dtype, B, H, N, d)
+    tq, tk, tv, tg = (to_gpu(x, dtype) for x in (Q, K, V, dO))
+    O = binding.cotten_attn_fwd(tq, tk, tv, None, scale=0.03, eps=1e-6)
+    grads = binding.cotten_attn_bwd(tq, tk, tv, None, tg, scale=0.03, eps=1e-6)
+    torch.cuda.synchronize()
+    ref_o = oracle.fwd_linear(Q, K, V, None, scale=0.03, eps=1e-6)
+    ref_g = oracle.bwd(Q, K, V, dO, None, scale=0.03, eps=1e-6)
+    bar = bar_for(dtype)
+    for n, g, r in zip(("O", "dQ", "dK", "dV"), (O, *grads), (ref_o, *ref_g)):
+        check_tensor(n, to_f64(g), r, bar)
