@@ -1,6 +1,8 @@
 // Generic two-kernel path of the cosine attention: vector-ALU arithmetic, tiles
-// staged through LDS.  Works for every supported (dtype, d_h, N); the tuned
-// kernels take over the shapes they cover.
+// staged through LDS.  Written for every supported (dtype, d_h, N); the matrix-core
+// kernels take over the shapes they cover, which leaves fp32 d_h = 128 to these
+// (and their launch structure, reduction and workspace layout to the kernels for
+// 256-byte rows).
 //
 //   state kernel : one workgroup reduces a block of rows of one slice to a
 //                  partial d x d state  sum_j xhat_j^T y_j   (x,y) = (K,V) under
@@ -481,17 +483,6 @@ hipError_t run_wide(const Problem& p, const Plan& plan, bool bwd) {
   return hipGetLastError();
 }
 
-template <typename T>
-hipError_t dispatch_d(const Problem& p, const Plan& plan, bool bwd) {
-  switch (p.D) {
-    case 16: return bwd ? run_bwd<T, 16>(p, plan) : run_fwd<T, 16>(p, plan);
-    case 32: return bwd ? run_bwd<T, 32>(p, plan) : run_fwd<T, 32>(p, plan);
-    case 64: return bwd ? run_bwd<T, 64>(p, plan) : run_fwd<T, 64>(p, plan);
-    case 128: return bwd ? run_bwd<T, 128>(p, plan) : run_fwd<T, 128>(p, plan);
-    default: return hipErrorInvalidValue;
-  }
-}
-
 }  // namespace
 
 void launch_reduce_states(const float* partial, float* reduced, int splits, int dd, size_t slices,
@@ -580,18 +571,18 @@ Plan make_plan(int B, int H, int N, int D, int dtype, bool is_bwd, bool allow_re
   return plan;
 }
 
+// The vector-ALU kernels are written for any (element type, d_h); the one instance compiled in is
+// the shape no matrix-core kernel serves, fp32 rows of 512 bytes.
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan) {
   if (wide_supports(p.dtype, p.D)) return run_wide(p, plan, false);
-  return p.dtype == 0   ? dispatch_d<float>(p, plan, false)
-         : p.dtype == 1 ? dispatch_d<bf16>(p, plan, false)
-                        : dispatch_d<f16>(p, plan, false);
+  if (p.dtype == 0 && p.D == 128) return run_fwd<float, 128>(p, plan);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan) {
   if (wide_supports(p.dtype, p.D)) return run_wide(p, plan, true);
-  return p.dtype == 0   ? dispatch_d<float>(p, plan, true)
-         : p.dtype == 1 ? dispatch_d<bf16>(p, plan, true)
-                        : dispatch_d<f16>(p, plan, true);
+  if (p.dtype == 0 && p.D == 128) return run_bwd<float, 128>(p, plan);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_normaliser_fwd(const float* m, const int32_t* n, float* slice_scale, int B,
