@@ -596,19 +596,20 @@ template <class F, int WAVE_BYTES>
 __device__ __forceinline__ void fused_state_pass(typename F::Acc& acc, const WideSrc& src,
                                                  const uint8_t* __restrict__ m, int N, int first_row,
                                                  int round_rows, float eps, unsigned char* sets,
-                                                 const Lane& L, bool swapped = false) {
+                                                 const Lane& L, bool swapped = false, int limit = -1) {
+  if (limit < 0) limit = N;  // rows that exist (0: the group has no slice and only keeps step)
   const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, group = L.wave >> 2;
   const int left = (swapped ? 2 + q : p) * kTileBytes, right = (swapped ? p : 2 + q) * kTileBytes;
   unsigned char* mine = sets + L.wave * WAVE_BYTES;
   acc.zero();
   WideRaw cur;
-  load_wide<true>(cur, L, src, first_row, row_bits(m, first_row, N, L));
-  int next_bits = row_bits(m, first_row + round_rows, N, L);
+  load_wide<true>(cur, L, src, first_row, row_bits(m, first_row, limit, L));
+  int next_bits = row_bits(m, first_row + round_rows, limit, L);
   for (int r0 = 0; r0 < N; r0 += round_rows) {
     float inv[2];
     stage_wide<F, mapped_mode<F>(), true>(cur, L, eps, mine, inv);
     load_wide<true>(cur, L, src, r0 + round_rows + first_row, next_bits);
-    next_bits = row_bits(m, r0 + 2 * round_rows + first_row, N, L);
+    next_bits = row_bits(m, r0 + 2 * round_rows + first_row, limit, L);
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -721,6 +722,64 @@ __global__ __launch_bounds__(512) void wide_fused_fwd_kernel(const LaunchArgs a,
   request_first_tile<8>(first, r, L);
   forward_images<F>(acc, scale, images, sets, kept == nullptr ? nullptr : kept + static_cast<size_t>(bh) * D * D, L);
   plain_tiles<F, 8, true, true>(r, images, sets + L.wave * Lds::kWaveBytes, L, &first);
+}
+
+// The forward with two slices per workgroup (waves 0-3 one slice, waves 4-7 the next), for
+// launches with more slices than compute units: the LDS of a compute unit admits one of these
+// workgroups at a time, and two slices that share it overlap their waits.  A group of four waves
+// owns its slice completely (one quadrant per wave, rounds of 64 rows, no sums to meet), so the
+// only thing the two groups share is the barriers of the state phase.
+template <class F>
+__global__ __launch_bounds__(512) void wide_paired_fwd_kernel(const LaunchArgs a, int slices,
+                                                              float* __restrict__ kept) {
+  using Lds = FusedLds<F, 2>;
+  constexpr int Dh = F::D, D = 2 * Dh;
+  const Lane L;
+  const int quadrant = L.wave & 3, group = L.wave >> 2;
+  const int slice = 2 * blockIdx.x + group;
+  const bool exists = slice < slices;
+  const int bh = exists ? slice : 0;
+  const int rows = exists ? a.N : 0;
+  const size_t base = a.st.slice_base(bh, a.H);
+  unsigned char* images = smem + group * Lds::kSetBytes;
+  unsigned char* sets = smem + Lds::kTiles;
+  typename F::Acc acc;
+  {
+    const WideSrc kv(a.K + base, a.V + base, a.N, a.st.row.stride);
+    const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
+    fused_state_pass<F, Lds::kWaveBytes>(acc, kv, keys, a.N, quadrant * TR, 4 * TR, a.eps, sets, L, false,
+                                         rows);
+  }
+  const float scale = a.slice_scale != nullptr ? a.slice_scale[bh] : a.scale;
+  Lane Lg = L;  // the wave's place in its group
+  Lg.wave = quadrant;
+  ApplyArgs r{};
+  r.X = a.Q + base;
+  r.mask = nullptr;  // queries are not masked
+  r.out = a.O + base;
+  r.N = a.N;
+  r.r_begin = 0;
+  r.r_end = rows;
+  r.stride = a.st.row.stride;
+  r.scale = scale;
+  r.eps = a.eps;
+  WideRaw first;
+  request_first_tile<4>(first, r, Lg);
+  const auto own = [&](int g) { return acc.group(g); };
+  quadrant_image<F, false>(own, scale, images + quadrant * F::kImageBytes, L);
+  if (kept != nullptr && exists) {  // S as it is, row-major, for the caller's backward call
+    float* __restrict__ out = kept + static_cast<size_t>(bh) * D * D;
+    const int p = quadrant >> 1, q = quadrant & 1;
+#pragma unroll
+    for (int g = 0; g < F::Acc::kGroups; ++g) {
+      const f32x4_t v = acc.group(g);
+      const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
+    }
+  }
+  __syncthreads();
+  plain_tiles<F, 4, true, true>(r, images, sets + L.wave * Lds::kWaveBytes, Lg, &first);
 }
 
 // d loss / d log(scale) = scale <S, dS> of the slice: the dS accumulators (waves 4-7) meet the S
@@ -1091,6 +1150,14 @@ hipError_t fused(const Problem& p, const Plan& plan, bool bwd) {
                          : reinterpret_cast<const void*>(wide_fused_fwd_kernel<F>);
   const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<8>());
   if (err != hipSuccess) return err;
+  if (!bwd && blocks > static_cast<unsigned>(kUnits)) {  // two slices per workgroup
+    const hipError_t e2 =
+        grant_dynamic_lds(reinterpret_cast<const void*>(wide_paired_fwd_kernel<F>), max_lds_bytes<8>());
+    if (e2 != hipSuccess) return e2;
+    hipLaunchKernelGGL((wide_paired_fwd_kernel<F>), dim3((blocks + 1) / 2), dim3(512), lds_bwd, p.stream,
+                       a, static_cast<int>(blocks), p.saved_state);
+    return hipGetLastError();
+  }
   if (bwd)
     hipLaunchKernelGGL((wide_fused_bwd_kernel<F>), dim3(blocks), dim3(512), lds_bwd,
                        p.stream, a, p.dlog_scale);
