@@ -49,6 +49,8 @@ def _inputs(seed, dtype, B, H, N, d):
     ("bf16", 100, 1, 257, 128),     # the shortest it does not
     ("f16", 128, 2, 300, 128),      # one launch, tiles streamed, fp16
     ("f16", 2, 2, 600, 128),        # three launches, workgroups of eight waves, fp16
+    ("bf16", 257, 1, 40, 128),      # forward with two slices per workgroup, the last one alone
+    ("f32", 129, 3, 90, 64),
     ("bf16", 100, 2, 600, 128),     # three launches, workgroups of four waves (600 of them)
     ("f32", 100, 2, 600, 64),
     ("f16", 100, 2, 600, 128),
