@@ -104,9 +104,7 @@ typedef enum cotten_feature_map {
                             "Linear Attention Models", on the same two products
                             O = scale * phi(Q) (phi(K)^T V) and their exact gradients.  No
                             normalising denominator (the section names none), eps unused.
-                            Served by the matrix-core kernels: fp32 with d_h in {16, 32, 64},
-                            16-bit with d_h in {16, 32, 64, 128}
-                            (COTTEN_ERR_UNSUPPORTED_HEAD_DIM otherwise); not with causal
+                            Every supported element type and d_h; not with causal
                             (COTTEN_ERR_BAD_PARAM)                                          */
 } cotten_feature_map;
 

@@ -37,7 +37,8 @@ struct Problem {
 //   path        : kResident one 16-wave workgroup keeps a short slice in LDS (no workspace)
 //                 kFused   one workgroup per slice runs every phase in one launch (no workspace)
 //                 kSplit   MFMA kernels, `splits` workgroups per slice, states via the workspace
-//                 kGeneric vector-ALU kernels for shapes the MFMA kernels do not cover
+//                 kGeneric kernels for wide rows (256 or 512 bytes): one launch per direction,
+//                          or partial states, reduction and apply via the workspace
 //   splits      : workgroups per slice in the state-reduction kernel; each reduces
 //                 `rows_per_split` consecutive rows to one partial d x d state
 //   workspace   : floats.  kGeneric: partial states [nstates][B*H*splits][D*D], followed, when
@@ -67,20 +68,20 @@ hipError_t grant_dynamic_lds(const void* kernel, int bytes);
 void launch_reduce_states(const float* partial, float* reduced, int splits, int dd, size_t slices,
                           hipStream_t stream);
 
-// Vector-ALU path (state reduction, then apply) for any supported shape.
+// Wide rows (Plan::kGeneric): everything the kernels for rows of up to 128 bytes do not serve.
 hipError_t launch_generic_fwd(const Problem& p, const Plan& plan);
 hipError_t launch_generic_bwd(const Problem& p, const Plan& plan);
 
-// Matrix-core kernels for 256-byte rows (fp32 d_h = 64, 16-bit d_h = 128) inside the launch
-// structure of the vector-ALU path: partial states into p.workspace in its layout, then, from
-// the reduced states ([B*H][D*D] floats each), O or dQ, dK, dV.
+// Matrix-core kernels for 256-byte rows (fp32 d_h = 64, 16-bit d_h = 128) and 512-byte rows (fp32
+// d_h = 128): partial states into p.workspace, then, from the reduced states ([B*H][D*D] floats
+// each), O or dQ, dK, dV.
 bool wide_supports(int dtype, int D);
 hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd);
 hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
                              const float* dstates, bool bwd);
 // Sequences that are not cut (wide_fused_applies): one launch per direction, the state stays in
 // LDS, no workspace; the forward writes p.saved_state, the backward p.dlog_scale, when given.
-bool wide_fused_applies(int B, int H, int splits, bool bwd);
+bool wide_fused_applies(int dtype, int D, int B, int H, int splits, bool bwd);
 hipError_t launch_wide_fused(const Problem& p, const Plan& plan, bool bwd);
 
 // MFMA path: bf16 or fp16 I/O with d_h = 64 and fp32 I/O with d_h = 32 (128-byte rows), and

@@ -1,5 +1,6 @@
 // Matrix-core kernels for 256-byte rows: fp32 I/O with d_h = 64, bf16 / fp16 I/O with d_h = 128
-// (d_model = 128 or 256 with two heads, "Sequence Length and Embedding Size").
+// (d_model = 128 or 256 with two heads, "Sequence Length and Embedding Size") - and, in their
+// three-launch form, for the 512-byte rows of fp32 I/O with d_h = 128.
 //
 // A 256-byte row is handled as two 128-byte halves, a d_h x d_h state as four quadrants of
 // the size the 128-byte-row formats work on (cotten_mfma_core.h), so that their tile layout,
@@ -8,15 +9,14 @@
 //     S[p][q] = sum_j khat_j[half p]^T v_j[half q]           (state kernel)
 //     O[half q] = sum_p Qhat[half p] S[p][q]                 (apply kernels; likewise dQ, dK, dV)
 //
-// with the row norm taken over both halves.  The launch structure is that of the vector-ALU
-// path whose place these kernels take for the shapes above (same plan, same workspace):
+// with the row norm taken over both halves.  Three launches (partial states in the caller's
+// workspace, [kinds][slices * splits][D * D] floats, then the reduced states):
 //
 //   wide_state_kernel   a workgroup of four (or eight) waves reduces a block of rows of one slice
 //                       to a partial state: per round every wave stages one 16-row tile in LDS,
 //                       then wave (p, q) adds four tiles of the round to its quadrant (with eight
 //                       waves two waves share a quadrant and their sums meet at the end)
-//   (the partial states of a slice are summed in split order by the reduction kernel of the
-//    vector-ALU path)
+//   (the partial states of a slice are summed in split order by reduce_states_kernel)
 //   wide_fwd_kernel / wide_bwd_kernel
 //                       a workgroup builds the operand images of the state it needs from the
 //                       reduced state, then every wave streams 16-row tiles through a private
@@ -34,27 +34,36 @@ using namespace mfma;
 
 // Every kernel exists for workgroups of 4 and of 8 waves (template parameter WAVES): 4 when there
 // are workgroups enough to put two on every compute unit, 8 when there are not.
-constexpr int kHalfBytes = kRowBytes;    // one half of a 256-byte row
+//
+// Template parameter P: the 128-byte pieces of a row.  2 for the 256-byte rows above; the kernels
+// of the three-launch structure also exist for P = 4, fp32 rows of 512 bytes (d_h = 128): the
+// state in 4 x 4 blocks of 32 x 32, four of them per wave of the state kernel, one set of sixteen
+// operand images in the LDS of an apply workgroup of four waves.
+constexpr int kHalfBytes = kRowBytes;    // one piece of a row
 
 // A 16-row tile of a tensor pair in the load layout: piece [h][c] is bytes 128 c + 16 ch .. + 15 of
 // row r8 + 8 h.  `live` bit h: the row takes part.
-struct WideRaw {
-  u32x4_t x[2][2], y[2][2];
+template <int P>
+struct WideRawT {
+  u32x4_t x[2][P], y[2][P];
   int live;
 };
+typedef WideRawT<2> WideRaw;
 
 // The two tensors of a pass as buffer resources over one slice (see Src in cotten_mfma_core.h:
 // lanes whose row does not take part get zeros and cause no traffic).
-struct WideSrc {
+template <int P>
+struct WideSrcT {
   __amdgpu_buffer_rsrc_t x, y;
   int stride;
-  __device__ __forceinline__ WideSrc(const unsigned char* X, const unsigned char* Y, int N, int stride_bytes)
+  __device__ __forceinline__ WideSrcT(const unsigned char* X, const unsigned char* Y, int N, int stride_bytes)
       : stride(stride_bytes) {
-    const int bytes = (N - 1) * stride + 2 * kHalfBytes;
+    const int bytes = (N - 1) * stride + P * kHalfBytes;
     x = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(X), 0, bytes, 0x00020000);
     y = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(Y), 0, bytes, 0x00020000);
   }
 };
+typedef WideSrcT<2> WideSrc;
 
 // Bit h: row row0 + r8 + 8 h is below `limit` and, if a mask is given, a valid key.
 __device__ __forceinline__ int row_bits(const uint8_t* __restrict__ mask, int row0, int limit,
@@ -68,8 +77,8 @@ __device__ __forceinline__ int row_bits(const uint8_t* __restrict__ mask, int ro
   return bits;
 }
 
-template <bool USE_Y>
-__device__ __forceinline__ void load_wide(WideRaw& r, const Lane& L, const WideSrc& src, int row0,
+template <bool USE_Y, int P>
+__device__ __forceinline__ void load_wide(WideRawT<P>& r, const Lane& L, const WideSrcT<P>& src, int row0,
                                           int bits) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
@@ -77,7 +86,7 @@ __device__ __forceinline__ void load_wide(WideRaw& r, const Lane& L, const WideS
     const uint32_t off =
         live ? static_cast<uint32_t>(row0 + L.r8 + 8 * h) * src.stride + L.ch * 16 : kOutOfBuffer;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < P; ++c) {
       r.x[h][c] = __builtin_amdgcn_raw_buffer_load_b128(src.x, off + c * kHalfBytes, 0, 0);
       if (USE_Y) r.y[h][c] = __builtin_amdgcn_raw_buffer_load_b128(src.y, off + c * kHalfBytes, 0, 0);
       else r.y[h][c] = u32x4_t{0, 0, 0, 0};
@@ -86,41 +95,41 @@ __device__ __forceinline__ void load_wide(WideRaw& r, const Lane& L, const WideS
   r.live = bits;
 }
 
-// The tile into LDS as four 16 x 128-byte tiles [x half 0 | x half 1 | y half 0 | y half 1]
-// (each in the layout of cotten_mfma_core.h); x raw, normalised over the whole row, or through
-// the element-wise map of the format (XMODE, see stage() in cotten_mfma_core.h).
+// The tile into LDS as 2 P tiles of 16 x 128 bytes [x pieces | y pieces] (each in the layout of
+// cotten_mfma_core.h); x raw, normalised over the whole row, or through the element-wise map of
+// the format (XMODE, see stage() in cotten_mfma_core.h).
 // inv[h] = 1/r of row r8 + 8 h (0 for a row that does not take part; with the element-wise map 1
 // for a row that does, and a row that does not is written as zeros explicitly: phi(0) is not 0).
-template <class F, int XMODE, bool USE_Y>
-__device__ __forceinline__ void stage_wide(const WideRaw& r, const Lane& L, float eps,
+template <class F, int XMODE, bool USE_Y, int P>
+__device__ __forceinline__ void stage_wide(const WideRawT<P>& r, const Lane& L, float eps,
                                            unsigned char* tiles, float (&inv)[2]) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    float f[2][F::EPL];
+    float f[P][F::EPL];
     const bool live = ((r.live >> h) & 1) != 0;
     const int off = (L.r8 + 8 * h) * kTileStride + L.ch * 16;
     if (XMODE == kXFeature) {
       inv[h] = live ? 1.0f : 0.0f;
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
+      for (int c = 0; c < P; ++c) {
         F::unpack(r.x[h][c], f[c]);
 #pragma unroll
         for (int i = 0; i < F::EPL; ++i) f[c][i] = live ? elu1(f[c][i]) : 0.0f;
         *reinterpret_cast<u32x4_t*>(tiles + c * kTileBytes + off) = F::pack(f[c]);
-        if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (2 + c) * kTileBytes + off) = r.y[h][c];
+        if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (P + c) * kTileBytes + off) = r.y[h][c];
       }
       continue;
     }
     float ss = 0.0f;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < P; ++c) {
       F::unpack(r.x[h][c], f[c]);
 #pragma unroll
       for (int i = 0; i < F::EPL; ++i) ss += f[c][i] * f[c][i];
     }
     inv[h] = inv_norm_or_zero(row_sum8(ss), eps, live);
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < P; ++c) {
       if (XMODE == kXNormalized) {
 #pragma unroll
         for (int i = 0; i < F::EPL; ++i) f[c][i] *= inv[h];
@@ -128,7 +137,7 @@ __device__ __forceinline__ void stage_wide(const WideRaw& r, const Lane& L, floa
       } else {
         *reinterpret_cast<u32x4_t*>(tiles + c * kTileBytes + off) = r.x[h][c];
       }
-      if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (2 + c) * kTileBytes + off) = r.y[h][c];
+      if (USE_Y) *reinterpret_cast<u32x4_t*>(tiles + (P + c) * kTileBytes + off) = r.y[h][c];
     }
   }
 }
@@ -152,11 +161,12 @@ __device__ __forceinline__ float inv_by_row(float* slot, const Lane& L, const fl
 
 // No row of the tile takes part (all of them masked or beyond the sequence): the wave can write
 // the zeros such rows come out as without computing them.
-__device__ __forceinline__ bool tile_dead(const WideRaw& r) {
+template <int P>
+__device__ __forceinline__ bool tile_dead(const WideRawT<P>& r) {
   return __builtin_amdgcn_ballot_w64(r.live != 0) == 0;
 }
 
-template <class F>
+template <class F, int P = 2>
 __device__ __forceinline__ void store_zero_rows(unsigned char* out, int row0, int r_end, int stride,
                                                 const Lane& L) {
   float z[2 * F::EPL];
@@ -165,7 +175,7 @@ __device__ __forceinline__ void store_zero_rows(unsigned char* out, int row0, in
   const int row = row0 + L.i16;
   if (row < r_end) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
+    for (int q = 0; q < P; ++q)
       store_product_row<F, kStoreStreamed>(out + q * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, z);
   }
 }
@@ -176,32 +186,37 @@ extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
 // grid (slices * splits, 1 or 2): blockIdx.y == 1 reduces (Q, dO) to sum_i qhat_i^T dO_i instead
 // of (K, V) under the key mask.  Partial states: row-major D x D floats per workgroup, the second
-// kind `second_offset` floats behind the first (the layout of the vector-ALU path).
-template <class F, int WAVES>
+// kind `second_offset` floats behind the first.
+// The P x P blocks of the state are dealt to the waves 0-3 of a group, P*P/4 consecutive ones
+// each (block i = piece i / P of x against piece i % P of y); with 8 waves two groups share the
+// tiles of a round and their sums meet at the end.
+template <class F, int WAVES, int P>
 __global__ __launch_bounds__(64 * WAVES) void wide_state_kernel(
     const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
     const unsigned char* __restrict__ V, const unsigned char* __restrict__ dO,
     const uint8_t* __restrict__ mask, float* __restrict__ ws, int H, int N, int splits,
     int rows_per_split, size_t second_offset, float eps, Strides st) {
-  constexpr int Dh = F::D, D = 2 * Dh, kRoundRows = WAVES * TR;
-  static_assert(WAVES == 4 || WAVES == 8, "one or two waves per quadrant");
-  unsigned char* round = smem;  // WAVES x [x half 0 | x half 1 | y half 0 | y half 1]
+  constexpr int Dh = F::D, D = P * Dh, kRoundRows = WAVES * TR, kBlocks = P * P / 4;
+  constexpr int kSetBytes = 2 * P * kTileBytes;  // the tiles one wave stages per round
+  static_assert(WAVES == 4 || WAVES == 8, "one or two groups of four waves");
+  unsigned char* round = smem;  // WAVES x [x pieces | y pieces]
   const Lane L;
   const int split = blockIdx.x % splits, bh = blockIdx.x / splits;
   const bool second = blockIdx.y == 1;
   const size_t base = st.slice_base(bh, H);
-  const WideSrc src((second ? Q : K) + base, (second ? dO : V) + base, N, st.row.stride);
+  const WideSrcT<P> src((second ? Q : K) + base, (second ? dO : V) + base, N, st.row.stride);
   const uint8_t* __restrict__ m =
       (second || mask == nullptr) ? nullptr : mask + static_cast<size_t>(bh / H) * N;
   const int r_begin = split * rows_per_split;
   const int r_end = N < r_begin + rows_per_split ? N : r_begin + rows_per_split;
-  // this wave's quadrant of the state, and (8 waves) which four tiles of a round it adds up
-  const int quadrant = L.wave & 3, p = quadrant >> 1, q = quadrant & 1, part = L.wave >> 2;
-  unsigned char* mine = round + L.wave * 4 * kTileBytes;
+  // this wave's blocks of the state, and (8 waves) which four tiles of a round it adds up
+  const int quadrant = L.wave & 3, part = L.wave >> 2;
+  unsigned char* mine = round + L.wave * kSetBytes;
 
-  typename F::Acc acc;
-  acc.zero();
-  WideRaw cur;
+  typename F::Acc acc[kBlocks];
+#pragma unroll
+  for (int j = 0; j < kBlocks; ++j) acc[j].zero();
+  WideRawT<P> cur;
   load_wide<true>(cur, L, src, r_begin + L.wave * TR, row_bits(m, r_begin + L.wave * TR, r_end, L));
   int next_bits = row_bits(m, r_begin + kRoundRows + L.wave * TR, r_end, L);
   for (int r0 = r_begin; r0 < r_end; r0 += kRoundRows) {
@@ -213,18 +228,24 @@ __global__ __launch_bounds__(64 * WAVES) void wide_state_kernel(
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const unsigned char* tile = round + (4 * part + t) * 4 * kTileBytes;
-      acc.mfma(tile + p * kTileBytes, tile + (2 + q) * kTileBytes, L);
+      const unsigned char* tile = round + (4 * part + t) * kSetBytes;
+#pragma unroll
+      for (int j = 0; j < kBlocks; ++j) {
+        const int block = quadrant * kBlocks + j;
+        acc[j].mfma(tile + (block / P) * kTileBytes, tile + (P + block % P) * kTileBytes, L);
+      }
     }
     __syncthreads();  // the round's tiles are overwritten next
   }
-  // 8 waves: the two sums of a quadrant meet in LDS (the round buffer is free), in a fixed order
-  f32x4_t* meet = reinterpret_cast<f32x4_t*>(round) + quadrant * F::Acc::kGroups * 64 + L.lane;
-  static_assert(4 * F::Acc::kGroups * 64 * 16 <= 8 * 4 * kTileBytes, "the sums fit the round buffer");
+  // 8 waves: the two sums of a block meet in LDS (the round buffer is free), in a fixed order
+  f32x4_t* meet = reinterpret_cast<f32x4_t*>(round) + quadrant * kBlocks * F::Acc::kGroups * 64 + L.lane;
+  static_assert(4 * kBlocks * F::Acc::kGroups * 64 * 16 <= 8 * kSetBytes, "the sums fit the round buffer");
   if (WAVES == 8) {
     if (part == 1) {
 #pragma unroll
-      for (int g = 0; g < F::Acc::kGroups; ++g) meet[g * 64] = acc.group(g);
+      for (int j = 0; j < kBlocks; ++j)
+#pragma unroll
+        for (int g = 0; g < F::Acc::kGroups; ++g) meet[(j * F::Acc::kGroups + g) * 64] = acc[j].group(g);
     }
     __syncthreads();
     if (part == 1) return;
@@ -232,25 +253,30 @@ __global__ __launch_bounds__(64 * WAVES) void wide_state_kernel(
   float* __restrict__ out =
       ws + (second ? second_offset : 0) + static_cast<size_t>(blockIdx.x) * D * D;
 #pragma unroll
-  for (int g = 0; g < F::Acc::kGroups; ++g) {
-    f32x4_t v = acc.group(g);
-    if (WAVES == 8) v += meet[g * 64];
-    const int row = p * Dh + F::Acc::group_row(g, L), col = q * Dh + F::Acc::group_col(g, L);
+  for (int j = 0; j < kBlocks; ++j) {
+    const int block = quadrant * kBlocks + j;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
+    for (int g = 0; g < F::Acc::kGroups; ++g) {
+      f32x4_t v = acc[j].group(g);
+      if (WAVES == 8) v += meet[(j * F::Acc::kGroups + g) * 64];
+      const int row = (block / P) * Dh + F::Acc::group_row(g, L);
+      const int col = (block % P) * Dh + F::Acc::group_col(g, L);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) out[(row + i) * D + col] = v[i];
+    }
   }
 }
 
 // ---- operand images --------------------------------------------------------------------------------
 
-// The four quadrant images of scale * M (M: a reduced state in global memory, row-major D x D),
-// image (p, q) at images + (2 p + q) * F::kImageBytes:
+// The P x P block images of scale * M (M: a reduced state in global memory, row-major D x D),
+// image (p, q) at images + (P p + q) * F::kImageBytes:
 //   natural     op[m][n] = M[p Dh + m][q Dh + n]     for products that contract over n
 //   transposed  op[n][m] = M[p Dh + m][q Dh + n]     for products that contract over m
-template <class F, int WAVES, bool TRANSPOSED>
+template <class F, int WAVES, bool TRANSPOSED, int P>
 __device__ __forceinline__ void build_images(const float* __restrict__ M, float scale,
                                              unsigned char* images) {
-  constexpr int Dh = F::D, D = 2 * Dh, kThreads = 64 * WAVES;
+  constexpr int Dh = F::D, D = P * Dh, kThreads = 64 * WAVES;
   // element pairs; the loads of a batch travel together
   constexpr int kPairs = D * D / 2, kBatch = kPairs / kThreads < 8 ? kPairs / kThreads : 8;
   static_assert(kBatch >= 1 && kPairs % (kBatch * kThreads) == 0, "state size");
@@ -275,40 +301,42 @@ __device__ __forceinline__ void build_images(const float* __restrict__ M, float 
       const int e = e0 + j * kThreads;
       const int m = TRANSPOSED ? 2 * (e / D) : e / (D / 2);
       const int n = TRANSPOSED ? e % D : 2 * (e % (D / 2));
-      unsigned char* image = images + (2 * (m / Dh) + n / Dh) * F::kImageBytes;
+      unsigned char* image = images + (P * (m / Dh) + n / Dh) * F::kImageBytes;
       if (TRANSPOSED) F::write_image_pair(image, n % Dh, m % Dh, v0[j] * scale, v1[j] * scale);
       else F::write_image_pair(image, m % Dh, n % Dh, v0[j] * scale, v1[j] * scale);
     }
   }
 }
 
-// The four quadrant operands of a role: held in registers for all the tiles of the wave (HOLD:
-// 4 x 32 registers for the 16-bit formats), or fetched from the images for every product (the
-// backward roles share one kernel and do better at two waves per SIMD than with the operands
-// held at one).
-template <class F, bool HOLD>
+// The P x P block operands of a role: held in registers for all the tiles of the wave (HOLD:
+// 4 x 32 registers for the 16-bit formats with P = 2), or fetched from the images for every
+// product (the backward roles share one kernel and do better at two waves per SIMD than with
+// the operands held at one).
+template <class F, bool HOLD, int P = 2>
 struct Quadrants {
-  typename F::Operand held[HOLD ? 4 : 1];
+  typename F::Operand held[HOLD ? P * P : 1];
   const unsigned char* images;
   __device__ __forceinline__ Quadrants(const unsigned char* img, const Lane& L) : images(img) {
     if (HOLD) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) held[i].load(images + i * F::kImageBytes, L);
+      for (int i = 0; i < P * P; ++i) held[i].load(images + i * F::kImageBytes, L);
     }
   }
-  // out = X[half 0] W(i0) + X[half 1] W(i1), images numbered 2 p + q
-  __device__ __forceinline__ void apply(const typename F::TileRows (&X)[2], int i0, int i1,
+  // out = sum_c X[piece c] W(first + c * step), images numbered P p + q
+  __device__ __forceinline__ void apply(const typename F::TileRows (&X)[P], int first, int step,
                                         const Lane& L, float (&out)[2 * F::EPL]) const {
     f32x4_t a[F::NT];
-    if (HOLD) {
-      F::apply(X[0], held[i0], a);
-      F::apply_onto(X[1], held[i1], a);
-    } else {
-      typename F::Operand W;
-      W.load(images + i0 * F::kImageBytes, L);
-      F::apply(X[0], W, a);
-      W.load(images + i1 * F::kImageBytes, L);
-      F::apply_onto(X[1], W, a);
+#pragma unroll
+    for (int c = 0; c < P; ++c) {
+      if (HOLD) {
+        if (c == 0) F::apply(X[c], held[first], a);
+        else F::apply_onto(X[c], held[first + c * step], a);
+      } else {
+        typename F::Operand W;
+        W.load(images + (first + c * step) * F::kImageBytes, L);
+        if (c == 0) F::apply(X[c], W, a);
+        else F::apply_onto(X[c], W, a);
+      }
     }
     product_rows<F>(a, out);
   }
@@ -326,37 +354,37 @@ struct ApplyArgs {
   float scale, eps;
 };
 
-// LDS of the apply kernels: [four images][per wave: four tiles, 16 floats]
-template <class F, int WAVES>
+// LDS of the apply kernels: [P x P images][per wave: 2 P tiles, 16 floats]
+template <class F, int WAVES, int P = 2>
 struct ApplyLds {
   static constexpr int kImages = 0;
-  static constexpr int kWave = 4 * F::kImageBytes;
-  static constexpr int kWaveBytes = 4 * kTileBytes + TR * 4;
+  static constexpr int kWave = P * P * F::kImageBytes;
+  static constexpr int kWaveBytes = 2 * P * kTileBytes + TR * 4;
   static constexpr int kBytes = kWave + WAVES * kWaveBytes;
 };
 
 // out rows = (x rows) M / r, contraction over the rows of M:  O = scale qhat S,  dV = scale khat dS.
 // One tile of the plain role: `cur` staged raw into the wave's tile set, out rows = x W / r.
-template <class F, bool HOLD>
-__device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD>& W, const WideRaw& cur, int row0,
+template <class F, bool HOLD, int P>
+__device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD, P>& W, const WideRawT<P>& cur, int row0,
                                            int r_end, unsigned char* out, int stride, float eps,
                                            unsigned char* tiles, const Lane& L) {
   if (tile_dead(cur)) {
-    store_zero_rows<F>(out, row0, r_end, stride, L);
+    store_zero_rows<F, P>(out, row0, r_end, stride, L);
     return;
   }
-  float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
+  float* inv_slot = reinterpret_cast<float*>(tiles + 2 * P * kTileBytes);
   float inv[2];
   stage_wide<F, plain_mode<F>(), false>(cur, L, eps, tiles, inv);
   const float inv_r = inv_by_row(inv_slot, L, inv);
-  typename F::TileRows X[2];
-  X[0].load(tiles, L);
-  X[1].load(tiles + kTileBytes, L);
+  typename F::TileRows X[P];
+#pragma unroll
+  for (int c = 0; c < P; ++c) X[c].load(tiles + c * kTileBytes, L);
   const int row = row0 + L.i16;
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
+  for (int q = 0; q < P; ++q) {
     float o[2 * F::EPL];
-    W.apply(X, q, 2 + q, L, o);
+    W.apply(X, q, P, L, o);
 #pragma unroll
     for (int i = 0; i < 2 * F::EPL; ++i) o[i] *= inv_r;
     if (row < r_end)
@@ -365,58 +393,58 @@ __device__ __forceinline__ void plain_tile(const Quadrants<F, HOLD>& W, const Wi
   wave_lds_fence();
 }
 
-// `images`: the four transposed quadrant images of scale * M; `tiles`: this wave's tile set.
+// `images`: the transposed block images of scale * M; `tiles`: this wave's tile set.
 // The wave's first tile: requested here, or (REQUESTED) by the caller with request_first_tile.
-template <int WAVES>
-__device__ __forceinline__ void request_first_tile(WideRaw& cur, const ApplyArgs& a, const Lane& L) {
-  const WideSrc src(a.X, a.X, a.N, a.stride);
+template <int WAVES, int P>
+__device__ __forceinline__ void request_first_tile(WideRawT<P>& cur, const ApplyArgs& a, const Lane& L) {
+  const WideSrcT<P> src(a.X, a.X, a.N, a.stride);
   const int row0 = a.r_begin + L.wave * TR;
   load_wide<false>(cur, L, src, row0, row_bits(a.mask, row0, a.r_end, L));
 }
 
-template <class F, int WAVES, bool HOLD, bool REQUESTED = false>
+template <class F, int WAVES, bool HOLD, bool REQUESTED = false, int P = 2>
 __device__ __forceinline__ void plain_tiles(const ApplyArgs& a, const unsigned char* images,
                                             unsigned char* tiles, const Lane& L,
-                                            const WideRaw* first = nullptr) {
+                                            const WideRawT<P>* first = nullptr) {
   constexpr int kRoundRows = WAVES * TR;  // rows between two tiles of a wave
-  const Quadrants<F, HOLD> W(images, L);
-  const WideSrc src(a.X, a.X, a.N, a.stride);
+  const Quadrants<F, HOLD, P> W(images, L);
+  const WideSrcT<P> src(a.X, a.X, a.N, a.stride);
   int row0 = a.r_begin + L.wave * TR;
-  WideRaw cur;
+  WideRawT<P> cur;
   if (REQUESTED) cur = *first;
   else request_first_tile<WAVES>(cur, a, L);
   int next_bits = row_bits(a.mask, row0 + kRoundRows, a.r_end, L);
   for (; row0 < a.r_end; row0 += kRoundRows) {
-    const WideRaw tile = cur;
+    const WideRawT<P> tile = cur;
     load_wide<false>(cur, L, src, row0 + kRoundRows, next_bits);
     next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
     plain_tile<F, HOLD>(W, tile, row0, a.r_end, a.out, a.stride, a.eps, tiles, L);
   }
 }
 
-template <class F, int WAVES, bool HOLD>
+template <class F, int WAVES, bool HOLD, int P>
 __device__ __forceinline__ void plain_role(const ApplyArgs& a) {
   const Lane L;
-  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
-  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
-  build_images<F, WAVES, true>(a.state, a.scale, images);
+  unsigned char* images = smem + ApplyLds<F, WAVES, P>::kImages;
+  unsigned char* tiles = smem + ApplyLds<F, WAVES, P>::kWave + L.wave * ApplyLds<F, WAVES, P>::kWaveBytes;
+  build_images<F, WAVES, true, P>(a.state, a.scale, images);
   __syncthreads();
-  plain_tiles<F, WAVES, HOLD>(a, images, tiles, L);
+  plain_tiles<F, WAVES, HOLD, false, P>(a, images, tiles, L);
 }
 
-// The row epilogue of dQ and dK over both halves of a row, E holding the mapped rows (xhat, or
+// The row epilogue of dQ and dK over all pieces of a row, E holding the mapped rows (xhat, or
 // phi(x)):  cosine map  g <- (g - xhat (xhat . g)) / r;   ELU + 1  g <- g * phi'(x), phi' = min(phi, 1).
-template <class F>
-__device__ __forceinline__ void finish_projected(float (&g)[2][2 * F::EPL], typename F::TileRows (&E)[2],
+template <class F, int P>
+__device__ __forceinline__ void finish_projected(float (&g)[P][2 * F::EPL], typename F::TileRows (&E)[P],
                                                  float inv_r, const Lane& L) {
   if (F::kMap == kMapElu1) {
 #pragma unroll
-    for (int p = 0; p < 2; ++p) feature_grad_rows<F>(g[p], E[p]);
+    for (int p = 0; p < P; ++p) feature_grad_rows<F>(g[p], E[p]);
     return;
   }
   float proj = 0.0f;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < P; ++p) {
     float u[2 * F::EPL];
     E[p].unpack(u);
 #pragma unroll
@@ -425,7 +453,7 @@ __device__ __forceinline__ void finish_projected(float (&g)[2][2 * F::EPL], type
   }
   proj = row_sum_groups(proj, L);
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < P; ++p) {
     float u[2 * F::EPL];
     E[p].unpack(u);
 #pragma unroll
@@ -435,23 +463,23 @@ __device__ __forceinline__ void finish_projected(float (&g)[2][2 * F::EPL], type
 
 // out rows = (g - xhat (xhat . g)) / r with g = (y rows) M^T, contraction over the columns of M:
 //   dQ from (Q, dO) and scale S;   dK from (K, V) and scale dS (masked rows come out as zeros).
-// `images`: the four natural quadrant images of scale * M.
-template <class F, int WAVES>
+// `images`: the natural block images of scale * M.
+template <class F, int WAVES, int P = 2>
 __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsigned char* images,
                                                 unsigned char* tiles, const Lane& L) {
   constexpr int kRoundRows = WAVES * TR;
-  float* inv_slot = reinterpret_cast<float*>(tiles + 4 * kTileBytes);
-  const Quadrants<F, false> W(images, L);
-  const WideSrc src(a.X, a.Y, a.N, a.stride);
+  float* inv_slot = reinterpret_cast<float*>(tiles + 2 * P * kTileBytes);
+  const Quadrants<F, false, P> W(images, L);
+  const WideSrcT<P> src(a.X, a.Y, a.N, a.stride);
   int row0 = a.r_begin + L.wave * TR;
-  WideRaw cur;
+  WideRawT<P> cur;
   load_wide<true>(cur, L, src, row0, row_bits(a.mask, row0, a.r_end, L));
   int next_bits = row_bits(a.mask, row0 + kRoundRows, a.r_end, L);
   for (; row0 < a.r_end; row0 += kRoundRows) {
     if (tile_dead(cur)) {  // nothing was fetched: zeros
       load_wide<true>(cur, L, src, row0 + kRoundRows, next_bits);
       next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
-      store_zero_rows<F>(a.out, row0, a.r_end, a.stride, L);
+      store_zero_rows<F, P>(a.out, row0, a.r_end, a.stride, L);
       continue;
     }
     float inv[2];
@@ -459,19 +487,19 @@ __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsign
     load_wide<true>(cur, L, src, row0 + kRoundRows, next_bits);
     next_bits = row_bits(a.mask, row0 + 2 * kRoundRows, a.r_end, L);
     const float inv_r = inv_by_row(inv_slot, L, inv);
-    typename F::TileRows Y[2], E[2];
-    Y[0].load(tiles + 2 * kTileBytes, L);
-    Y[1].load(tiles + 3 * kTileBytes, L);
-    float g[2][2 * F::EPL];
+    typename F::TileRows Y[P], E[P];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
-      W.apply(Y, 2 * p, 2 * p + 1, L, g[p]);
-    E[0].load(tiles, L);
-    E[1].load(tiles + kTileBytes, L);
+    for (int c = 0; c < P; ++c) Y[c].load(tiles + (P + c) * kTileBytes, L);
+    float g[P][2 * F::EPL];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      W.apply(Y, P * p, 1, L, g[p]);
+#pragma unroll
+    for (int c = 0; c < P; ++c) E[c].load(tiles + c * kTileBytes, L);
     finish_projected<F>(g, E, inv_r, L);
     const int row = row0 + L.i16;
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < P; ++p) {
       if (row < a.r_end)
         store_product_row<F, kStoreStreamed>(a.out + p * kHalfBytes, row, RowAddr{a.stride, kHalfBytes}, L, g[p]);
     }
@@ -479,14 +507,14 @@ __device__ __forceinline__ void projected_tiles(const ApplyArgs& a, const unsign
   }
 }
 
-template <class F, int WAVES>
+template <class F, int WAVES, int P>
 __device__ __forceinline__ void projected_role(const ApplyArgs& a) {
   const Lane L;
-  unsigned char* images = smem + ApplyLds<F, WAVES>::kImages;
-  unsigned char* tiles = smem + ApplyLds<F, WAVES>::kWave + L.wave * ApplyLds<F, WAVES>::kWaveBytes;
-  build_images<F, WAVES, false>(a.state, a.scale, images);
+  unsigned char* images = smem + ApplyLds<F, WAVES, P>::kImages;
+  unsigned char* tiles = smem + ApplyLds<F, WAVES, P>::kWave + L.wave * ApplyLds<F, WAVES, P>::kWaveBytes;
+  build_images<F, WAVES, false, P>(a.state, a.scale, images);
   __syncthreads();
-  projected_tiles<F, WAVES>(a, images, tiles, L);
+  projected_tiles<F, WAVES, P>(a, images, tiles, L);
 }
 
 struct LaunchArgs {
@@ -507,7 +535,7 @@ struct LaunchArgs {
   Strides st;
 };
 
-__device__ __forceinline__ ApplyArgs role_args(const LaunchArgs& a, int dd) {
+__device__ __forceinline__ ApplyArgs role_args(const LaunchArgs& a) {
   ApplyArgs r{};
   const int split = blockIdx.x % a.splits, bh = blockIdx.x / a.splits;
   r.N = a.N;
@@ -519,26 +547,26 @@ __device__ __forceinline__ ApplyArgs role_args(const LaunchArgs& a, int dd) {
   return r;
 }
 
-template <class F, int WAVES>
+template <class F, int WAVES, int P>
 __global__ __launch_bounds__(64 * WAVES) void wide_fwd_kernel(const LaunchArgs a) {
-  constexpr int D = 2 * F::D;
+  constexpr int D = P * F::D;
   const int bh = blockIdx.x / a.splits;
   const size_t base = a.st.slice_base(bh, a.H);
-  ApplyArgs r = role_args(a, D * D);
+  ApplyArgs r = role_args(a);
   r.X = a.Q + base;
   r.mask = nullptr;  // queries are not masked
   r.state = a.states + static_cast<size_t>(bh) * D * D;
   r.out = a.O + base;
-  plain_role<F, WAVES, true>(r);
+  plain_role<F, WAVES, P == 2, P>(r);  // operands held in registers where they fit
 }
 
 // blockIdx.y: 0 dQ, 1 dV, 2 dK
-template <class F, int WAVES>
+template <class F, int WAVES, int P>
 __global__ __launch_bounds__(64 * WAVES) void wide_bwd_kernel(const LaunchArgs a) {
-  constexpr int D = 2 * F::D;
+  constexpr int D = P * F::D;
   const int bh = blockIdx.x / a.splits;
   const size_t base = a.st.slice_base(bh, a.H);
-  ApplyArgs r = role_args(a, D * D);
+  ApplyArgs r = role_args(a);
   const uint8_t* keys = a.mask == nullptr ? nullptr : a.mask + static_cast<size_t>(bh / a.H) * a.N;
   if (blockIdx.y == 0) {
     r.X = a.Q + base;
@@ -546,20 +574,20 @@ __global__ __launch_bounds__(64 * WAVES) void wide_bwd_kernel(const LaunchArgs a
     r.mask = nullptr;
     r.state = a.states + static_cast<size_t>(bh) * D * D;
     r.out = a.dQ + base;
-    projected_role<F, WAVES>(r);
+    projected_role<F, WAVES, P>(r);
   } else if (blockIdx.y == 1) {
     r.X = a.K + base;
     r.mask = keys;
     r.state = a.dstates + static_cast<size_t>(bh) * D * D;
     r.out = a.dV + base;
-    plain_role<F, WAVES, false>(r);
+    plain_role<F, WAVES, false, P>(r);
   } else {
     r.X = a.K + base;
     r.Y = a.V + base;
     r.mask = keys;
     r.state = a.dstates + static_cast<size_t>(bh) * D * D;
     r.out = a.dK + base;
-    projected_role<F, WAVES>(r);
+    projected_role<F, WAVES, P>(r);
   }
 }
 
@@ -960,7 +988,7 @@ __device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N,
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       float o[2 * F::EPL];
-      W.apply(E, q, 2 + q, L, o);
+      W.apply(E, q, 2, L, o);
       if (row < N)
         store_product_row<F, kStoreStreamed>(out_plain + q * kHalfBytes, row, RowAddr{stride, kHalfBytes}, L, o);
     }
@@ -974,7 +1002,7 @@ __device__ __forceinline__ void kept_tile_bwd(const WideRaw& t, int row0, int N,
   const Quadrants<F, false> W(natural, L);
   float g[2][2 * F::EPL];
 #pragma unroll
-  for (int p = 0; p < 2; ++p) W.apply(Y, 2 * p, 2 * p + 1, L, g[p]);
+  for (int p = 0; p < 2; ++p) W.apply(Y, 2 * p, 1, L, g[p]);
   finish_projected<F>(g, E, inv_r, L);
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
@@ -1073,23 +1101,25 @@ LaunchArgs launch_args(const Problem& p, const Plan& plan, const float* states, 
 
 // Workgroups of 8 waves (the whole LDS of a compute unit at their disposal) when the launch has
 // no more workgroups than there are compute units, of 4 waves (two per compute unit) otherwise.
+// With rows of four pieces one set of images and four tile sets fill the LDS of a compute unit:
+// the apply workgroups have 4 waves and a compute unit to themselves.
 constexpr int kUnits = 256;
-template <int WAVES>
+template <int WAVES, int P = 2>
 constexpr int max_lds_bytes() {
-  return WAVES == 8 ? 160 * 1024 : 80 * 1024;
+  return (WAVES == 8 || P == 4) ? 160 * 1024 : 80 * 1024;
 }
 
-template <class F, int WAVES>
+template <class F, int WAVES, int P>
 hipError_t states_w(const Problem& p, const Plan& plan, bool bwd) {
-  constexpr int D = 2 * F::D;
-  constexpr int lds = WAVES * 4 * kTileBytes;
-  static_assert(lds <= max_lds_bytes<WAVES>(), "round buffer");
+  constexpr int D = P * F::D;
+  constexpr int lds = WAVES * 2 * P * kTileBytes;
+  static_assert(lds <= max_lds_bytes<WAVES, P>(), "round buffer");
   const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
   const size_t second = static_cast<size_t>(blocks) * D * D;
-  const hipError_t err =
-      grant_dynamic_lds(reinterpret_cast<const void*>(wide_state_kernel<F, WAVES>), max_lds_bytes<WAVES>());
+  const hipError_t err = grant_dynamic_lds(reinterpret_cast<const void*>(wide_state_kernel<F, WAVES, P>),
+                                           max_lds_bytes<WAVES, P>());
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL((wide_state_kernel<F, WAVES>), dim3(blocks, bwd ? 2 : 1), dim3(64 * WAVES), lds,
+  hipLaunchKernelGGL((wide_state_kernel<F, WAVES, P>), dim3(blocks, bwd ? 2 : 1), dim3(64 * WAVES), lds,
                      p.stream, static_cast<const unsigned char*>(p.Q),
                      static_cast<const unsigned char*>(p.K), static_cast<const unsigned char*>(p.V),
                      static_cast<const unsigned char*>(p.dO), p.mask, p.workspace, p.H, p.N,
@@ -1097,20 +1127,20 @@ hipError_t states_w(const Problem& p, const Plan& plan, bool bwd) {
   return hipGetLastError();
 }
 
-template <class F, int WAVES>
+template <class F, int WAVES, int P>
 hipError_t apply_w(const Problem& p, const Plan& plan, const float* st, const float* dst, bool bwd) {
-  constexpr int lds = ApplyLds<F, WAVES>::kBytes;
-  static_assert(lds <= max_lds_bytes<WAVES>(), "images and tiles");
+  constexpr int lds = ApplyLds<F, WAVES, P>::kBytes;
+  static_assert(lds <= max_lds_bytes<WAVES, P>(), "images and tiles");
   const LaunchArgs a = launch_args(p, plan, st, dst);
   const unsigned blocks = static_cast<unsigned>(p.B) * p.H * plan.splits;
-  const void* kern = bwd ? reinterpret_cast<const void*>(wide_bwd_kernel<F, WAVES>)
-                         : reinterpret_cast<const void*>(wide_fwd_kernel<F, WAVES>);
-  const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<WAVES>());
+  const void* kern = bwd ? reinterpret_cast<const void*>(wide_bwd_kernel<F, WAVES, P>)
+                         : reinterpret_cast<const void*>(wide_fwd_kernel<F, WAVES, P>);
+  const hipError_t err = grant_dynamic_lds(kern, max_lds_bytes<WAVES, P>());
   if (err != hipSuccess) return err;
   if (bwd)
-    hipLaunchKernelGGL((wide_bwd_kernel<F, WAVES>), dim3(blocks, 3), dim3(64 * WAVES), lds, p.stream, a);
+    hipLaunchKernelGGL((wide_bwd_kernel<F, WAVES, P>), dim3(blocks, 3), dim3(64 * WAVES), lds, p.stream, a);
   else
-    hipLaunchKernelGGL((wide_fwd_kernel<F, WAVES>), dim3(blocks), dim3(64 * WAVES), lds, p.stream, a);
+    hipLaunchKernelGGL((wide_fwd_kernel<F, WAVES, P>), dim3(blocks), dim3(64 * WAVES), lds, p.stream, a);
   return hipGetLastError();
 }
 
@@ -1119,15 +1149,17 @@ inline bool few_workgroups(const Problem& p, const Plan& plan, int kinds) {
   return static_cast<long>(p.B) * p.H * plan.splits * kinds <= kUnits;
 }
 
-template <class F>
+template <class F, int P>
 hipError_t states(const Problem& p, const Plan& plan, bool bwd) {
-  return few_workgroups(p, plan, bwd ? 2 : 1) ? states_w<F, 8>(p, plan, bwd) : states_w<F, 4>(p, plan, bwd);
+  return few_workgroups(p, plan, bwd ? 2 : 1) ? states_w<F, 8, P>(p, plan, bwd)
+                                              : states_w<F, 4, P>(p, plan, bwd);
 }
 
-template <class F>
+template <class F, int P>
 hipError_t apply(const Problem& p, const Plan& plan, const float* st, const float* dst, bool bwd) {
-  return few_workgroups(p, plan, bwd ? 3 : 1) ? apply_w<F, 8>(p, plan, st, dst, bwd)
-                                              : apply_w<F, 4>(p, plan, st, dst, bwd);
+  if (P == 4) return apply_w<F, 4, P>(p, plan, st, dst, bwd);
+  return few_workgroups(p, plan, bwd ? 3 : 1) ? apply_w<F, 8, 2>(p, plan, st, dst, bwd)
+                                              : apply_w<F, 4, 2>(p, plan, st, dst, bwd);
 }
 
 template <class F>
@@ -1170,9 +1202,12 @@ hipError_t fused(const Problem& p, const Plan& plan, bool bwd) {
 }  // namespace wide
 }  // namespace
 
-bool wide_supports(int dtype, int D) { return dtype == 0 ? D == 64 : D == 128; }
+bool wide_supports(int dtype, int D) { return dtype == 0 ? (D == 64 || D == 128) : D == 128; }
 
 namespace {
+// rows of four 128-byte pieces: fp32 d_h = 128 (three-launch structure only)
+inline bool four_pieces(int dtype, int D) { return dtype == 0 && D == 128; }
+
 // fn(F{}) for the element format of the problem, with the feature map of its params
 template <class Fn>
 hipError_t for_format(const Problem& p, Fn fn) {
@@ -1186,24 +1221,33 @@ hipError_t for_format(const Problem& p, Fn fn) {
 }  // namespace
 
 hipError_t launch_wide_states(const Problem& p, const Plan& plan, bool bwd) {
-  return for_format(p, [&](auto f) { return wide::states<decltype(f)>(p, plan, bwd); });
+  using namespace mfma;
+  if (four_pieces(p.dtype, p.D))
+    return p.feature_map == kMapElu1 ? wide::states<WithElu1<F32x32>, 4>(p, plan, bwd)
+                                     : wide::states<F32x32, 4>(p, plan, bwd);
+  return for_format(p, [&](auto f) { return wide::states<decltype(f), 2>(p, plan, bwd); });
 }
 
 // One launch per direction whenever the sequence is not cut - except a backward over so few
 // slices that its three roles as workgroups of their own are what fills the chip (64 slices of
-// 200 rows, bf16 d_h = 128: 17.5 us against 19.4 us in one launch; the forward: 13.8 against 10.0).
-bool wide_fused_applies(int B, int H, int splits, bool bwd) {
-  return splits == 1 && !(bwd && static_cast<long>(B) * H * 3 <= wide::kUnits);
+// 200 rows, bf16 d_h = 128: 17.5 us against 19.4 us in one launch; the forward: 13.8 against 10.0),
+// and except rows of four pieces, for which only the three-launch kernels exist.
+bool wide_fused_applies(int dtype, int D, int B, int H, int splits, bool bwd) {
+  return !four_pieces(dtype, D) && splits == 1 && !(bwd && static_cast<long>(B) * H * 3 <= wide::kUnits);
 }
 
 hipError_t launch_wide_fused(const Problem& p, const Plan& plan, bool bwd) {
-  if (!wide_fused_applies(p.B, p.H, plan.splits, bwd)) return hipErrorInvalidValue;
+  if (!wide_fused_applies(p.dtype, p.D, p.B, p.H, plan.splits, bwd)) return hipErrorInvalidValue;
   return for_format(p, [&](auto f) { return wide::fused<decltype(f)>(p, plan, bwd); });
 }
 
 hipError_t launch_wide_apply(const Problem& p, const Plan& plan, const float* states,
                              const float* dstates, bool bwd) {
-  return for_format(p, [&](auto f) { return wide::apply<decltype(f)>(p, plan, states, dstates, bwd); });
+  using namespace mfma;
+  if (four_pieces(p.dtype, p.D))
+    return p.feature_map == kMapElu1 ? wide::apply<WithElu1<F32x32>, 4>(p, plan, states, dstates, bwd)
+                                     : wide::apply<F32x32, 4>(p, plan, states, dstates, bwd);
+  return for_format(p, [&](auto f) { return wide::apply<decltype(f), 2>(p, plan, states, dstates, bwd); });
 }
 
 }  // namespace cotten

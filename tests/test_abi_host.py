@@ -85,14 +85,12 @@ def test_validation_errors_touch_no_device(lib):
     assert _fwd(lib, prm=p) == -7
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 1)
     assert _fwd(lib, d=128, prm=p) == -3
-    # the feature map: one of the two enumerators, not with causal, only where the matrix-core
-    # kernels serve the shape (positional: ..., layout, causal, saved_state, feature_map)
+    # the feature map: one of the two enumerators, not with causal
+    # (positional: ..., layout, causal, saved_state, feature_map)
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 0, None, 2)
     assert _fwd(lib, prm=p) == -7
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 1, None, 1)
     assert _fwd(lib, prm=p) == -7
-    p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 0, None, 1)
-    assert _fwd(lib, d=128, prm=p) == -3      # fp32 d_h = 128: vector-ALU kernels only
     # a saved state must be 16-byte aligned like every other tensor
     p = binding.CottenParams(binding.COTTEN_F32, 0.0, -1.0, None, 0, None, None, 0, 0, 0x9004, 0)
     assert _fwd(lib, prm=p) == -5

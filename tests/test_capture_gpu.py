@@ -23,7 +23,7 @@ code = {torch.float32: binding.COTTEN_F32, torch.bfloat16: binding.COTTEN_BF16}
 # (dtype, B, H, N, d): sequence cut over several workgroups (needs a workspace), slice kept
 # in LDS, one workgroup per slice with tiles in registers, streaming; 256-byte rows with three
 # launches in the backward, with one launch per direction (tiles kept, tiles streamed);
-# vector-ALU kernels
+# 512-byte rows
 shapes = [(torch.bfloat16, 2, 2, 1500, 64), (torch.bfloat16, 5, 2, 200, 64),
           (torch.float32, 6, 2, 200, 32), (torch.float32, 130, 2, 300, 32),
           (torch.float32, 2, 2, 150, 64), (torch.bfloat16, 100, 1, 200, 128),

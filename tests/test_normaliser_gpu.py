@@ -1,6 +1,6 @@
 """GPU parity of the learnable normaliser 1/n^m (scaled CosineAttention): per-slice scales in
 both directions, d loss / d log(scale) from the backward call, and the exponent gradient,
-against the fp64 oracle, on every kernel family (resident, fused, split, vector-ALU)."""
+against the fp64 oracle, on every kernel family (resident, fused, split, wide rows)."""
 import numpy as np
 import pytest
 import torch
@@ -24,9 +24,11 @@ CASES = [
     ("half-width rows f32 d=16 (fused)", "f32", 3, 2, 70, 16),
     ("half-width rows bf16 d=32 (resident)", "bf16", 3, 2, 150, 32),
     ("half-width rows bf16 d=32 (split)", "bf16", 2, 2, 1030, 32),
-    ("vector-ALU f32 d=64", "f32", 3, 2, 70, 64),
+    ("256-byte rows f32 d=64", "f32", 3, 2, 70, 64),
     ("quarter-width rows bf16 d=16 (split)", "bf16", 2, 2, 300, 16),
-    ("vector-ALU f32 d=64, several splits", "f32", 2, 2, 300, 64),
+    ("256-byte rows f32 d=64, several splits", "f32", 2, 2, 300, 64),
+    ("512-byte rows f32 d=128", "f32", 3, 2, 70, 128),
+    ("256-byte rows bf16 d=128, one launch", "bf16", 45, 2, 100, 128),
 ]
 
 

@@ -274,7 +274,7 @@ def test_extreme_shapes(oracle, dtype, d):
                                      (3, 2, 70, 32), (2, 2, 300, 16)])
 def test_fp16_io(oracle, B, H, N, d):
     """IEEE half I/O (the mixed-precision mode of the paper's training runs) on every kernel
-    family: resident (N <= 208), fused and split streamers (d_h = 64), vector-ALU (d_h = 32, 16).
+    family: resident (N <= 208), fused and split streamers (d_h = 64), narrower rows (d_h = 32, 16).
     Bar 2.5e-3: unit roundoff 2^-11 against bf16's 2^-8 and its bar of 2e-2."""
     Q, K, V, dO = _case(8000 + N + d, B, H, N, d, "f16")
     rng = np.random.default_rng(N)
@@ -289,8 +289,8 @@ def test_fp16_io(oracle, B, H, N, d):
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("N", [33, 200, 700])
 def test_head_dim_128(oracle, dtype, N):
-    """d_h = 128 (d_model 256 with two heads): served by the vector-ALU kernels, whose backward
-    splits dV and dK over separate blocks at this size."""
+    """d_h = 128 (d_model 256 with two heads): the kernels for 256-byte rows (16-bit) and for
+    512-byte rows (fp32)."""
     B, H, d = 2, 2, 128
     Q, K, V, dO = _case(9100 + N, B, H, N, d, dtype)
     mask = (np.random.default_rng(N).random((B, N)) < 0.7).astype(np.uint8)

@@ -29,7 +29,8 @@ CASES = [
     ("f32", 2, 2, 1030, 32),     # sequence cut over several workgroups
     ("bf16", 3, 2, 3000, 64),
     ("f16", 2, 2, 1030, 32),
-    ("f32", 2, 2, 150, 64),      # vector-ALU kernels: state written, backward rebuilds it
+    ("f32", 2, 2, 150, 64),      # 256-byte rows: state written, backward rebuilds it
+    ("f32", 2, 2, 150, 128),     # 512-byte rows: the same
 ]
 
 
